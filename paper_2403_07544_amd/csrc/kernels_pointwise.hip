@@ -1,0 +1,629 @@
+// HBM-bound kernels of the routed training step: token bookkeeping, embedding gather and its
+// gradient, LayerNorm forward/backward, column sums (bias gradients), label-smoothed
+// cross-entropy, Adam.  gfx950, 64-wide wavefronts, 16-byte accesses wherever rows allow.
+#include "mm_kernels.h"
+
+namespace mm {
+
+namespace {
+
+constexpr int WAVE = 64;
+
+template <typename T> struct Io;
+template <> struct Io<float> {
+  static __device__ __forceinline__ float ld(const float* p) { return *p; }
+  static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+  static __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  static __device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+};
+template <> struct Io<bf16_t> {
+  static __device__ __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+  static __device__ __forceinline__ float4 ld4(const bf16_t* p) {
+    uint2 r = *reinterpret_cast<const uint2*>(p);
+    float4 f;
+    f.x = __uint_as_float(r.x << 16); f.y = __uint_as_float(r.x & 0xffff0000u);
+    f.z = __uint_as_float(r.y << 16); f.w = __uint_as_float(r.y & 0xffff0000u);
+    return f;
+  }
+  static __device__ __forceinline__ void st4(bf16_t* p, float4 v) {
+    uint2 r;
+    r.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+    r.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+    *reinterpret_cast<uint2*>(p) = r;
+  }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+  return v;
+}
+
+// ----------------------------------------------------------------------------------------------
+// token bookkeeping
+// ----------------------------------------------------------------------------------------------
+__global__ void pack_ids_kernel(const int32_t* __restrict__ src_ids, const int32_t* __restrict__ tgt_ids,
+                                const int32_t* __restrict__ lens, const int32_t* __restrict__ cu_s,
+                                const int32_t* __restrict__ cu_u, int S_max, int T_max, int V,
+                                int32_t* src_tok, int32_t* src_pos, int32_t* dec_tok, int32_t* dec_pos,
+                                int32_t* label, int32_t* flag) {
+  const int b = blockIdx.x;
+  const int s = lens[2 * b], t = lens[2 * b + 1];
+  int bad = 0;
+  for (int i = threadIdx.x; i < S_max; i += blockDim.x) {
+    int id = src_ids[(int64_t)b * S_max + i];
+    if (i < s) {
+      if (id < 0 || id >= V) { bad |= 1; id = 0; }
+      const int row = cu_s[b] + i;
+      src_tok[row] = id;
+      src_pos[row] = i;
+    } else if (id != 0) {
+      bad |= 2;
+    }
+  }
+  for (int i = threadIdx.x; i < T_max; i += blockDim.x) {
+    int id = tgt_ids[(int64_t)b * T_max + i];
+    if (i < t) {
+      if (id < 0 || id >= V) { bad |= 1; id = 0; }
+      if (i < t - 1) {
+        const int row = cu_u[b] + i;
+        dec_tok[row] = id;
+        dec_pos[row] = i;
+      }
+      if (i >= 1) label[cu_u[b] + i - 1] = id;
+    } else if (id != 0) {
+      bad |= 2;
+    }
+  }
+  if (bad) atomicOr(flag, bad);
+}
+
+// The attention kernels use the same predicate (attn_blocked in kernels_attention.hip states it
+// again for its own use; this kernel materialises it for bit-exact checks).
+__global__ void mask_dump_kernel(const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
+                                 int Lq, int Lk, int mode, uint8_t* out) {
+  const int b = blockIdx.x;
+  const int len_k = cu_k[b + 1] - cu_k[b];
+  (void)cu_q;
+  for (int e = threadIdx.x; e < Lq * Lk; e += blockDim.x) {
+    const int i = e / Lk, j = e % Lk;
+    const bool blocked = (j >= len_k) || (mode == 1 && j > i);
+    out[(int64_t)b * Lq * Lk + e] = blocked ? 1 : 0;
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// embedding gather + positional encoding
+// ----------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void embed_fwd_kernel(const T* __restrict__ E, const float* __restrict__ pe,
+                                 const int32_t* __restrict__ tok, const int32_t* __restrict__ pos,
+                                 float* __restrict__ x, int rows, int d, float sqrt_d) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one float4 each
+  const int per_row = d >> 2;
+  if (q >= (int64_t)rows * per_row) return;
+  const int row = (int)(q / per_row), c = (int)(q % per_row) << 2;
+  const float4 e = Io<T>::ld4(E + (int64_t)tok[row] * d + c);
+  const float4 p = Io<float>::ld4(pe + (int64_t)pos[row] * d + c);
+  float4 o;  // product rounded, then sum rounded (no fused multiply-add)
+  o.x = __fadd_rn(__fmul_rn(sqrt_d, e.x), p.x);
+  o.y = __fadd_rn(__fmul_rn(sqrt_d, e.y), p.y);
+  o.z = __fadd_rn(__fmul_rn(sqrt_d, e.z), p.z);
+  o.w = __fadd_rn(__fmul_rn(sqrt_d, e.w), p.w);
+  Io<float>::st4(x + (int64_t)row * d + c, o);
+}
+
+// ----------------------------------------------------------------------------------------------
+// embedding gradient: sort (token, row) keys in one workgroup, then one workgroup per run of
+// equal tokens adds its rows in ascending row order.  No atomics: same bits every run.
+// ----------------------------------------------------------------------------------------------
+constexpr int ROW_BITS = 14;  // rows < 16384, tokens < 2^17
+
+__global__ void __launch_bounds__(1024) sort_keys_kernel(const int32_t* __restrict__ tok, int rows,
+                                                         int n_pow2, uint32_t* __restrict__ keys) {
+  extern __shared__ uint32_t sk[];
+  for (int i = threadIdx.x; i < n_pow2; i += blockDim.x)
+    sk[i] = i < rows ? (((uint32_t)tok[i] << ROW_BITS) | (uint32_t)i) : 0xffffffffu;
+  __syncthreads();
+  for (int k = 2; k <= n_pow2; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = threadIdx.x; i < n_pow2; i += blockDim.x) {
+        const int l = i ^ j;
+        if (l > i) {
+          const uint32_t a = sk[i], b = sk[l];
+          const bool up = (i & k) == 0;
+          if ((a > b) == up) { sk[i] = b; sk[l] = a; }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  for (int i = threadIdx.x; i < n_pow2; i += blockDim.x) keys[i] = sk[i];
+}
+
+template <int NV>  // float4 chunks per lane: d <= NV * 256
+__global__ void __launch_bounds__(256) embed_grad_kernel(const uint32_t* __restrict__ keys,
+                                                         const float* __restrict__ dx,
+                                                         float* __restrict__ bucket, int rows, int d,
+                                                         float sqrt_d) {
+  const int p = blockIdx.x;
+  const uint32_t token = keys[p] >> ROW_BITS;
+  if (p > 0 && (keys[p - 1] >> ROW_BITS) == token) return;  // not the head of a run
+  __shared__ int s_end;
+  __shared__ float red[3][NV * 256];
+  if (threadIdx.x == 0) s_end = rows;
+  __syncthreads();
+  for (int q = p + 1 + threadIdx.x; q < rows; q += blockDim.x)
+    if ((keys[q] >> ROW_BITS) != token) { atomicMin(&s_end, q); break; }
+  __syncthreads();
+  const int end = s_end;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float4 acc[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int q = p + wave; q < end; q += 4) {
+    const int row = keys[q] & ((1u << ROW_BITS) - 1);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int c = (lane << 2) + v * 256;
+      if (c < d) {
+        const float4 g = Io<float>::ld4(dx + (int64_t)row * d + c);
+        acc[v].x += g.x; acc[v].y += g.y; acc[v].z += g.z; acc[v].w += g.w;
+      }
+    }
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      float* r = &red[wave - 1][v * 256 + (lane << 2)];
+      r[0] = acc[v].x; r[1] = acc[v].y; r[2] = acc[v].z; r[3] = acc[v].w;
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int c = (lane << 2) + v * 256;
+      if (c < d) {
+        float4 s = acc[v];
+        for (int w = 0; w < 3; ++w) {
+          const float* r = &red[w][v * 256 + (lane << 2)];
+          s.x += r[0]; s.y += r[1]; s.z += r[2]; s.w += r[3];
+        }
+        float* dst = bucket + (int64_t)token * d + c;
+        float4 o = Io<float>::ld4(dst);
+        o.x += sqrt_d * s.x; o.y += sqrt_d * s.y; o.z += sqrt_d * s.z; o.w += sqrt_d * s.w;
+        Io<float>::st4(dst, o);
+      }
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// LayerNorm
+// ----------------------------------------------------------------------------------------------
+template <typename T, int NV>
+__global__ void __launch_bounds__(256) layernorm_fwd_kernel(const float* __restrict__ x,
+                                                            const float* __restrict__ gamma,
+                                                            const float* __restrict__ beta,
+                                                            T* __restrict__ y, float* __restrict__ mean,
+                                                            float* __restrict__ rstd, int rows, int d,
+                                                            float eps) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  float4 v[NV];
+  float s = 0.f;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int c = (lane << 2) + k * 256;
+    v[k] = c < d ? Io<float>::ld4(x + (int64_t)row * d + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    s += (v[k].x + v[k].y) + (v[k].z + v[k].w);
+  }
+  const float mu = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int c = (lane << 2) + k * 256;
+    if (c < d) {
+      v[k].x -= mu; v[k].y -= mu; v[k].z -= mu; v[k].w -= mu;
+      q += (v[k].x * v[k].x + v[k].y * v[k].y) + (v[k].z * v[k].z + v[k].w * v[k].w);
+    }
+  }
+  const float var = wave_sum(q) / (float)d;
+  const float rs = 1.0f / sqrtf(var + eps);
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int c = (lane << 2) + k * 256;
+    if (c < d) {
+      const float4 g = Io<float>::ld4(gamma + c), b = Io<float>::ld4(beta + c);
+      float4 o;
+      o.x = v[k].x * rs * g.x + b.x; o.y = v[k].y * rs * g.y + b.y;
+      o.z = v[k].z * rs * g.z + b.z; o.w = v[k].w * rs * g.w + b.w;
+      Io<T>::st4(y + (int64_t)row * d + c, o);
+    }
+  }
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+}
+
+// Each wavefront walks rows blockIdx*4+wave, +gridDim*4, ...; column sums for gamma/beta stay in
+// registers and leave as one partial row per workgroup: partial[block][0][d] = dgamma part,
+// partial[block][1][d] = dbeta part.
+template <typename T, int NV>
+__global__ void __launch_bounds__(256) layernorm_bwd_kernel(
+    const float* __restrict__ dy, const float* __restrict__ x, const float* __restrict__ mean,
+    const float* __restrict__ rstd, const float* __restrict__ gamma, const float* __restrict__ dres,
+    float* __restrict__ dx_out, T* __restrict__ dxT_out, float* __restrict__ partial, int rows, int d) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float4 g[NV], ag[NV], ab[NV];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int c = (lane << 2) + k * 256;
+    g[k] = c < d ? Io<float>::ld4(gamma + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    ag[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    ab[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  const float inv_d = 1.0f / (float)d;
+  for (int row = blockIdx.x * 4 + wave; row < rows; row += gridDim.x * 4) {
+    const float mu = mean[row], rs = rstd[row];
+    float4 xh[NV], dh[NV];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int c = (lane << 2) + k * 256;
+      if (c < d) {
+        const float4 xv = Io<float>::ld4(x + (int64_t)row * d + c);
+        const float4 dv = Io<float>::ld4(dy + (int64_t)row * d + c);
+        xh[k].x = (xv.x - mu) * rs; xh[k].y = (xv.y - mu) * rs;
+        xh[k].z = (xv.z - mu) * rs; xh[k].w = (xv.w - mu) * rs;
+        ag[k].x += dv.x * xh[k].x; ag[k].y += dv.y * xh[k].y;
+        ag[k].z += dv.z * xh[k].z; ag[k].w += dv.w * xh[k].w;
+        ab[k].x += dv.x; ab[k].y += dv.y; ab[k].z += dv.z; ab[k].w += dv.w;
+        dh[k].x = dv.x * g[k].x; dh[k].y = dv.y * g[k].y;
+        dh[k].z = dv.z * g[k].z; dh[k].w = dv.w * g[k].w;
+        s1 += (dh[k].x + dh[k].y) + (dh[k].z + dh[k].w);
+        s2 += (dh[k].x * xh[k].x + dh[k].y * xh[k].y) + (dh[k].z * xh[k].z + dh[k].w * xh[k].w);
+      }
+    }
+    const float m1 = wave_sum(s1) * inv_d, m2 = wave_sum(s2) * inv_d;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int c = (lane << 2) + k * 256;
+      if (c < d) {
+        float4 o;
+        o.x = rs * (dh[k].x - m1 - xh[k].x * m2); o.y = rs * (dh[k].y - m1 - xh[k].y * m2);
+        o.z = rs * (dh[k].z - m1 - xh[k].z * m2); o.w = rs * (dh[k].w - m1 - xh[k].w * m2);
+        if (dres) {
+          const float4 r = Io<float>::ld4(dres + (int64_t)row * d + c);
+          o.x += r.x; o.y += r.y; o.z += r.z; o.w += r.w;
+        }
+        Io<float>::st4(dx_out + (int64_t)row * d + c, o);
+        if (dxT_out) Io<T>::st4(dxT_out + (int64_t)row * d + c, o);
+      }
+    }
+  }
+  // workgroup reduction of the 4 waves' column sums, fixed order
+  __shared__ float red[3][2][NV * 256];
+  if (wave > 0) {
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      float* r0 = &red[wave - 1][0][k * 256 + (lane << 2)];
+      float* r1 = &red[wave - 1][1][k * 256 + (lane << 2)];
+      r0[0] = ag[k].x; r0[1] = ag[k].y; r0[2] = ag[k].z; r0[3] = ag[k].w;
+      r1[0] = ab[k].x; r1[1] = ab[k].y; r1[2] = ab[k].z; r1[3] = ab[k].w;
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int c = (lane << 2) + k * 256;
+      if (c < d) {
+        float4 sg = ag[k], sb = ab[k];
+        for (int w = 0; w < 3; ++w) {
+          const float* r0 = &red[w][0][k * 256 + (lane << 2)];
+          const float* r1 = &red[w][1][k * 256 + (lane << 2)];
+          sg.x += r0[0]; sg.y += r0[1]; sg.z += r0[2]; sg.w += r0[3];
+          sb.x += r1[0]; sb.y += r1[1]; sb.z += r1[2]; sb.w += r1[3];
+        }
+        Io<float>::st4(partial + ((int64_t)blockIdx.x * 2 + 0) * d + c, sg);
+        Io<float>::st4(partial + ((int64_t)blockIdx.x * 2 + 1) * d + c, sb);
+      }
+    }
+  }
+}
+
+// dst[seg(n)] += sum_p partial[p * pstride + n]   (one thread per column, fixed order over p)
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_partial, int64_t pstride,
+                                       int N, float* __restrict__ dst, int split, int64_t seg_stride) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  float s = 0.f;
+  for (int p = 0; p < n_partial; ++p) s += partial[(int64_t)p * pstride + n];
+  float* o = split ? dst + (int64_t)(n / split) * seg_stride + (n % split) : dst + n;
+  *o += s;
+}
+
+// ----------------------------------------------------------------------------------------------
+// column sums: grid (ceil(N/256), chunks); each workgroup sums its row chunk for 256 columns
+// ----------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) colsum_kernel(const T* __restrict__ Y, int64_t ldy, int M, int N,
+                                                     int rows_per_chunk, float* __restrict__ partial) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  const int r0 = blockIdx.y * rows_per_chunk;
+  const int r1 = min(M, r0 + rows_per_chunk);
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int r = r0;
+  for (; r + 3 < r1; r += 4) {
+    s0 += Io<T>::ld(Y + (int64_t)r * ldy + n);
+    s1 += Io<T>::ld(Y + (int64_t)(r + 1) * ldy + n);
+    s2 += Io<T>::ld(Y + (int64_t)(r + 2) * ldy + n);
+    s3 += Io<T>::ld(Y + (int64_t)(r + 3) * ldy + n);
+  }
+  for (; r < r1; ++r) s0 += Io<T>::ld(Y + (int64_t)r * ldy + n);
+  partial[(int64_t)blockIdx.y * N + n] = (s0 + s1) + (s2 + s3);
+}
+
+// ----------------------------------------------------------------------------------------------
+// label-smoothed cross-entropy, one workgroup per row
+// ----------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(1024) ce_kernel(T* __restrict__ z, const int32_t* __restrict__ label,
+                                                  float* __restrict__ loss_rows, int V, float eps,
+                                                  float scale, const int32_t* __restrict__ flag) {
+  const int row = blockIdx.x;
+  T* zr = z + (int64_t)row * V;
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int wave = tid >> 6, lane = tid & 63, nwave = nthr >> 6;
+  // pass 1: running max, rescaled sum of exponentials, plain sum
+  float mx = -INFINITY, se = 0.f, sz = 0.f;
+  for (int c = tid * 4; c < V; c += nthr * 4) {  // V % 4 == 0
+    const float4 v = Io<T>::ld4(zr + c);
+    const float m4 = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+    if (m4 > mx) { se *= __expf(mx - m4); mx = m4; }
+    se += (__expf(v.x - mx) + __expf(v.y - mx)) + (__expf(v.z - mx) + __expf(v.w - mx));
+    sz += (v.x + v.y) + (v.z + v.w);
+  }
+  __shared__ float s_mx[16], s_se[16], s_sz[16];
+  __shared__ float s_lse, s_sumz;
+  const float wmx = wave_max(mx);
+  se = (mx == -INFINITY) ? 0.f : se * __expf(mx - wmx);
+  se = wave_sum(se);
+  sz = wave_sum(sz);
+  if (lane == 0) { s_mx[wave] = wmx; s_se[wave] = se; s_sz[wave] = sz; }
+  __syncthreads();
+  if (tid == 0) {
+    float gm = s_mx[0];
+    for (int w = 1; w < nwave; ++w) gm = fmaxf(gm, s_mx[w]);
+    float gs = 0.f, gz = 0.f;
+    for (int w = 0; w < nwave; ++w) { gs += s_se[w] * __expf(s_mx[w] - gm); gz += s_sz[w]; }
+    s_lse = gm + logf(gs);
+    s_sumz = gz;
+  }
+  __syncthreads();
+  const float lse = s_lse;
+  const int y = label[row];
+  if (tid == 0) {
+    const float zy = Io<T>::ld(zr + y);
+    loss_rows[row] = lse - (1.0f - eps) * zy - (eps / (float)V) * s_sumz;
+  }
+  // pass 2 (the row was just read: served from cache): z <- (softmax - q) * scale * ok
+  const float ok = (*flag == 0) ? scale : 0.0f;
+  const float uni = eps / (float)V;
+  for (int c = tid * 4; c < V; c += nthr * 4) {
+    const float4 v = Io<T>::ld4(zr + c);
+    float4 o;
+    o.x = __expf(v.x - lse) - uni; o.y = __expf(v.y - lse) - uni;
+    o.z = __expf(v.z - lse) - uni; o.w = __expf(v.w - lse) - uni;
+    if (y >= c && y < c + 4) {
+      const float one = 1.0f - eps;
+      if (y == c) o.x -= one; else if (y == c + 1) o.y -= one; else if (y == c + 2) o.z -= one; else o.w -= one;
+    }
+    o.x *= ok; o.y *= ok; o.z *= ok; o.w *= ok;
+    Io<T>::st4(zr + c, o);
+  }
+}
+
+__global__ void __launch_bounds__(1024) sum_scaled_kernel(const float* __restrict__ v, int n, float scale,
+                                                          float* __restrict__ out) {
+  __shared__ float part[16];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) s += v[i];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += part[w];
+    out[0] = t * scale;
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Adam over a segment list
+// ----------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict__ segs, int n_segs,
+                                                   float lr, float beta1, float beta2, float eps) {
+  // find the segment of this chunk (n_segs is small)
+  int lo = 0, hi = n_segs - 1;
+  const int chunk = blockIdx.x;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (segs[mid].first_chunk <= chunk) lo = mid; else hi = mid - 1;
+  }
+  const AdamSegment sg = segs[lo];
+  const int64_t base = (int64_t)(chunk - sg.first_chunk) * ADAM_CHUNK;
+  const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+#pragma unroll
+  for (int it = 0; it < ADAM_CHUNK / 1024; ++it) {
+    const int64_t i = base + it * 1024 + threadIdx.x * 4;
+    if (i >= sg.len) break;
+    float4 g = Io<float>::ld4(sg.g + i), th = Io<float>::ld4(sg.theta + i);
+    float4 m = Io<float>::ld4(sg.m + i), v = Io<float>::ld4(sg.v + i);
+    float* gp = &g.x; float* tp = &th.x; float* mp = &m.x; float* vp = &v.x;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float ge = gp[e] * sg.inv_n;
+      mp[e] = beta1 * mp[e] + omb1 * ge;
+      vp[e] = beta2 * vp[e] + omb2 * ge * ge;
+      const float mh = mp[e] / sg.bc1, vh = vp[e] / sg.bc2;
+      tp[e] = tp[e] - lr * mh / (sqrtf(vh) + eps);
+    }
+    Io<float>::st4(sg.theta + i, th);
+    Io<float>::st4(sg.m + i, m);
+    Io<float>::st4(sg.v + i, v);
+    Io<float>::st4(sg.g + i, make_float4(0.f, 0.f, 0.f, 0.f));
+    if (sg.w16) Io<bf16_t>::st4(sg.w16 + i, th);
+  }
+}
+
+__global__ void to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n4) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4) Io<bf16_t>::st4(dst + i * 4, Io<float>::ld4(src + i * 4));
+}
+__global__ void fill_f32_kernel(float* dst, int64_t n, float v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = v;
+}
+__global__ void fill_i32_kernel(int32_t* dst, int64_t n, int32_t v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = v;
+}
+
+inline int nv_for(int d) { return d <= 256 ? 1 : d <= 512 ? 2 : d <= 1024 ? 4 : 8; }
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------------
+void launch_pack_ids(hipStream_t st, const int32_t* src_ids, const int32_t* tgt_ids, const int32_t* lens,
+                     const int32_t* cu_s, const int32_t* cu_u, int B, int S_max, int T_max, int V,
+                     int32_t* src_tok, int32_t* src_pos, int32_t* dec_tok, int32_t* dec_pos,
+                     int32_t* label, int32_t* flag) {
+  pack_ids_kernel<<<B, 128, 0, st>>>(src_ids, tgt_ids, lens, cu_s, cu_u, S_max, T_max, V, src_tok,
+                                     src_pos, dec_tok, dec_pos, label, flag);
+}
+
+void launch_mask_dump(hipStream_t st, const int32_t* cu_q, const int32_t* cu_k, int B, int Lq, int Lk,
+                      int mode, uint8_t* out) {
+  mask_dump_kernel<<<B, 256, 0, st>>>(cu_q, cu_k, Lq, Lk, mode, out);
+}
+
+void launch_embed_fwd(hipStream_t st, Dtype dt, const void* E, const float* pe, const int32_t* tok,
+                      const int32_t* pos, float* x, int rows, int d, float sqrt_d) {
+  const int64_t n4 = (int64_t)rows * (d / 4);
+  const int grid = (int)((n4 + 255) / 256);
+  if (dt == BF16)
+    embed_fwd_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)E, pe, tok, pos, x, rows, d, sqrt_d);
+  else
+    embed_fwd_kernel<float><<<grid, 256, 0, st>>>((const float*)E, pe, tok, pos, x, rows, d, sqrt_d);
+}
+
+void launch_embed_grad(hipStream_t st, const int32_t* tok, const float* dx, float* bucket, uint32_t* keys,
+                       int rows, int d, float sqrt_d) {
+  int n_pow2 = 64;
+  while (n_pow2 < rows) n_pow2 <<= 1;
+  sort_keys_kernel<<<1, 1024, n_pow2 * sizeof(uint32_t), st>>>(tok, rows, n_pow2, keys);
+  switch (nv_for(d)) {
+    case 1: embed_grad_kernel<1><<<rows, 256, 0, st>>>(keys, dx, bucket, rows, d, sqrt_d); break;
+    case 2: embed_grad_kernel<2><<<rows, 256, 0, st>>>(keys, dx, bucket, rows, d, sqrt_d); break;
+    case 4: embed_grad_kernel<4><<<rows, 256, 0, st>>>(keys, dx, bucket, rows, d, sqrt_d); break;
+    default: embed_grad_kernel<8><<<rows, 256, 0, st>>>(keys, dx, bucket, rows, d, sqrt_d); break;
+  }
+}
+
+#define MM_LN_DISPATCH(KERNEL, T, ...)                                        \
+  switch (nv_for(d)) {                                                        \
+    case 1: KERNEL<T, 1><<<grid, 256, 0, st>>>(__VA_ARGS__); break;           \
+    case 2: KERNEL<T, 2><<<grid, 256, 0, st>>>(__VA_ARGS__); break;           \
+    case 4: KERNEL<T, 4><<<grid, 256, 0, st>>>(__VA_ARGS__); break;           \
+    default: KERNEL<T, 8><<<grid, 256, 0, st>>>(__VA_ARGS__); break;          \
+  }
+
+void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float* gamma, const float* beta,
+                          void* y, float* mean, float* rstd, int rows, int d, float eps) {
+  const int grid = (rows + 3) / 4;
+  if (dt == BF16) {
+    MM_LN_DISPATCH(layernorm_fwd_kernel, bf16_t, x, gamma, beta, (bf16_t*)y, mean, rstd, rows, d, eps)
+  } else {
+    MM_LN_DISPATCH(layernorm_fwd_kernel, float, x, gamma, beta, (float*)y, mean, rstd, rows, d, eps)
+  }
+}
+
+int ln_bwd_partial_rows(int rows) {
+  const int want = (rows + 3) / 4;
+  return want < 512 ? want : 512;
+}
+
+void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float* x, const float* mean,
+                          const float* rstd, const float* gamma, const float* dres, float* dx_out,
+                          void* dxT_out, float* partial, float* dgamma, float* dbeta, int rows, int d) {
+  const int grid = ln_bwd_partial_rows(rows);
+  if (dt == BF16) {
+    MM_LN_DISPATCH(layernorm_bwd_kernel, bf16_t, dy, x, mean, rstd, gamma, dres, dx_out, (bf16_t*)dxT_out,
+                   partial, rows, d)
+  } else {
+    MM_LN_DISPATCH(layernorm_bwd_kernel, float, dy, x, mean, rstd, gamma, dres, dx_out, (float*)nullptr,
+                   partial, rows, d)
+  }
+  const int g2 = (d + 255) / 256;
+  reduce_partials_kernel<<<g2, 256, 0, st>>>(partial, grid, 2 * (int64_t)d, d, dgamma, 0, 0);
+  reduce_partials_kernel<<<g2, 256, 0, st>>>(partial + d, grid, 2 * (int64_t)d, d, dbeta, 0, 0);
+}
+
+int colsum_partial_rows(int M) {
+  int chunks = (M + 127) / 128;
+  return chunks < 64 ? chunks : 64;
+}
+
+void launch_colsum(hipStream_t st, Dtype dt, const void* Y, int y_f32, int64_t ldy, int M, int N,
+                   float* partial, float* dst, int split, int64_t seg_stride) {
+  const int chunks = colsum_partial_rows(M);
+  const int rows_per_chunk = (M + chunks - 1) / chunks;
+  dim3 grid((N + 255) / 256, chunks);
+  if (y_f32 || dt == F32)
+    colsum_kernel<float><<<grid, 256, 0, st>>>((const float*)Y, ldy, M, N, rows_per_chunk, partial);
+  else
+    colsum_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)Y, ldy, M, N, rows_per_chunk, partial);
+  reduce_partials_kernel<<<(N + 255) / 256, 256, 0, st>>>(partial, chunks, N, N, dst, split, seg_stride);
+}
+
+void launch_ce(hipStream_t st, Dtype dt, void* z, const int32_t* label, float* loss_rows, int U, int V,
+               float eps, float scale, const int32_t* flag) {
+  const int threads = V >= 16384 ? 1024 : V >= 2048 ? 256 : 64;
+  if (dt == BF16)
+    ce_kernel<bf16_t><<<U, threads, 0, st>>>((bf16_t*)z, label, loss_rows, V, eps, scale, flag);
+  else
+    ce_kernel<float><<<U, threads, 0, st>>>((float*)z, label, loss_rows, V, eps, scale, flag);
+}
+
+void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float* out) {
+  sum_scaled_kernel<<<1, 1024, 0, st>>>(v, n, scale, out);
+}
+
+void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int total_chunks, float lr,
+                 float beta1, float beta2, float eps) {
+  if (total_chunks > 0) adam_kernel<<<total_chunks, 256, 0, st>>>(segs_dev, n_segs, lr, beta1, beta2, eps);
+}
+
+void launch_to_bf16(hipStream_t st, const float* src, bf16_t* dst, int64_t n) {
+  const int64_t n4 = n / 4;
+  if (n4 > 0) to_bf16_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, st>>>(src, dst, n4);
+}
+void launch_fill_f32(hipStream_t st, float* dst, int64_t n, float v) {
+  if (n > 0) fill_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(dst, n, v);
+}
+void launch_fill_i32(hipStream_t st, int32_t* dst, int64_t n, int32_t v) {
+  if (n > 0) fill_i32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(dst, n, v);
+}
+
+}  // namespace mm

@@ -1,0 +1,145 @@
+// Internal launcher interface between the host runtime and the gfx950 kernels.
+// Everything here runs on the stream it is given; nothing allocates.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mm {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+enum Dtype { F32 = 0, BF16 = 1 };
+
+__host__ __device__ inline float bf16_to_f32(bf16_t h) {
+  union { uint32_t u; float f; } c;
+  c.u = (uint32_t)h << 16;
+  return c.f;
+}
+// round to nearest even; NaN stays NaN
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+  union { uint32_t u; float f; } c;
+  c.f = f;
+  if ((c.u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((c.u >> 16) | 0x40);
+  c.u += 0x7fffu + ((c.u >> 16) & 1u);
+  return (bf16_t)(c.u >> 16);
+}
+
+// ---------------------------------------------------------------------------------------------
+// GEMM:  C[M,N] = epilogue( op(A)[M,K] * op(B)[K,N] )
+//   transA = 0: A stored [M,K] row-major (lda = row stride); 1: stored [K,M] row-major.
+//   transB = 0: B stored [K,N] row-major (ldb);              1: stored [N,K] row-major.
+//   A and B hold the context's working dtype (float or bf16); accumulation is fp32.
+//   Split operands: the canonical parameter layout keeps Wq, Wk, Wv (and their biases and
+//   gradients) as separate tensors a fixed distance apart; a fused QKV product addresses them
+//   as one matrix whose N (or K) axis is cut into segments of `*_split` indices, segment s
+//   starting `s * *_seg_stride` elements after the base pointer.
+// ---------------------------------------------------------------------------------------------
+struct GemmParams {
+  const void* A; const void* B; void* C;
+  int M, N, K;
+  int64_t lda, ldb, ldc;
+  int transA, transB;
+  int b_split;            // 0 = B is one matrix; else segment length along N (or K)
+  int b_split_on_k;       // 1: segments along K (used by the fused QKV input-gradient product)
+  int64_t b_seg_stride;
+  int c_split;            // segments along N for C (and for the residual)
+  int64_t c_seg_stride;
+  const float* bias;      // [N] fp32 or null; added before relu
+  int bias_split;         // segments along N for the bias vector
+  int64_t bias_seg_stride;
+  int relu;               // max(.,0)
+  const void* relu_mask;  // working dtype [M,N], row stride ldm: result *= (mask > 0)
+  int64_t ldm;
+  const float* residual;  // fp32 [M,N], row stride ldr, same segmentation as C: added last
+  int64_t ldr;
+  int out_f32;            // 1: C is fp32; 0: C has the working dtype
+};
+void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p);
+
+// ---------------------------------------------------------------------------------------------
+// token bookkeeping
+// ---------------------------------------------------------------------------------------------
+// flag[0] |= 1 for an id outside [0,V) at a real position, |= 2 for a non-pad id after the end.
+void launch_pack_ids(hipStream_t st, const int32_t* src_ids, const int32_t* tgt_ids,
+                     const int32_t* lens, const int32_t* cu_s, const int32_t* cu_u, int B,
+                     int S_max, int T_max, int V, int32_t* src_tok, int32_t* src_pos,
+                     int32_t* dec_tok, int32_t* dec_pos, int32_t* label, int32_t* flag);
+// mode 0: key j blocked iff j >= len_k; mode 1: also j > i.  out uint8 [B, Lq, Lk].
+void launch_mask_dump(hipStream_t st, const int32_t* cu_q, const int32_t* cu_k, int B, int Lq,
+                      int Lk, int mode, uint8_t* out);
+
+// x[row,:] = sqrt_d * E[tok[row],:] + pe[pos[row],:]   (multiply, then add; fp32 out)
+void launch_embed_fwd(hipStream_t st, Dtype dt, const void* E, const float* pe, const int32_t* tok,
+                      const int32_t* pos, float* x, int rows, int d, float sqrt_d);
+// bucket[tok,:] += sqrt_d * sum over rows with that token of dx[row,:]; deterministic.
+// keys: scratch uint32 [pow2 >= rows].
+void launch_embed_grad(hipStream_t st, const int32_t* tok, const float* dx, float* bucket,
+                       uint32_t* keys, int rows, int d, float sqrt_d);
+
+// ---------------------------------------------------------------------------------------------
+// LayerNorm over the last axis, one row per wavefront
+// ---------------------------------------------------------------------------------------------
+void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float* gamma,
+                          const float* beta, void* y, float* mean, float* rstd, int rows, int d,
+                          float eps);
+// dx_out = dres + LN'(dy);  dxT_out (working dtype, may be null) = same, rounded;
+// dgamma/dbeta (bucket slices) += column sums.  partial: scratch float [ln_bwd_partial_rows() * 2 * d].
+int ln_bwd_partial_rows(int rows);
+void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float* x,
+                          const float* mean, const float* rstd, const float* gamma,
+                          const float* dres, float* dx_out, void* dxT_out, float* partial,
+                          float* dgamma, float* dbeta, int rows, int d);
+
+// dst[n] += sum_m Y[m,n]; Y is fp32 (y_f32=1) or working dtype; dst segmented like GemmParams C.
+int colsum_partial_rows(int M);
+void launch_colsum(hipStream_t st, Dtype dt, const void* Y, int y_f32, int64_t ldy, int M, int N,
+                   float* partial, float* dst, int split, int64_t seg_stride);
+
+// ---------------------------------------------------------------------------------------------
+// attention, one (sentence, head) per workgroup; q/k/v/o rows are packed tokens
+// ---------------------------------------------------------------------------------------------
+struct AttnParams {
+  const void* q; const void* k; const void* v; void* o;  // working dtype
+  int64_t ldq, ldk, ldv, ldo;                              // row strides (elements)
+  float* lse;                                              // [H, rows_q] log-sum-exp of scaled scores
+  const int32_t* cu_q; const int32_t* cu_k;                // [B+1] row offsets per sentence
+  int B, H, dh, causal, rows_q;
+  int max_lq, max_lk;                                      // longest sentence in the batch
+  // backward only
+  const void* d_o; void* dq; void* dk; void* dv;
+  int64_t lddo, lddq, lddk, lddv;
+};
+size_t attn_lds_bytes(Dtype dt, int dh, int max_lq, int max_lk, bool backward);
+void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p);
+void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p);
+
+// ---------------------------------------------------------------------------------------------
+// label-smoothed cross-entropy over the vocabulary, forward and backward in one pass
+//   loss_rows[u] = lse - (1-eps) z[y] - (eps/V) sum_v z[v];  z <- (softmax(z) - q) * scale * ok
+//   where ok = (flag[0] == 0).  z has the working dtype, [U, V] with row stride V.
+// ---------------------------------------------------------------------------------------------
+void launch_ce(hipStream_t st, Dtype dt, void* z, const int32_t* label, float* loss_rows, int U,
+               int V, float eps, float scale, const int32_t* flag);
+// out[0] = (sum of loss_rows) * scale
+void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float* out);
+
+// ---------------------------------------------------------------------------------------------
+// Adam over a list of module buckets, one launch
+// ---------------------------------------------------------------------------------------------
+struct AdamSegment {
+  float* theta; float* m; float* v; float* g; bf16_t* w16;  // w16 null in fp32 contexts
+  int64_t len;                                               // multiple of 64
+  float inv_n, bc1, bc2;                                     // 1/n_j, 1-beta1^t, 1-beta2^t
+  int32_t first_chunk;                                       // running chunk index of this segment
+  int32_t pad;
+};
+static const int ADAM_CHUNK = 4096;
+void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int total_chunks,
+                 float lr, float beta1, float beta2, float eps);
+
+// fp32 -> bf16 copy (working weights) and fill
+void launch_to_bf16(hipStream_t st, const float* src, bf16_t* dst, int64_t n);
+void launch_fill_f32(hipStream_t st, float* dst, int64_t n, float v);
+void launch_fill_i32(hipStream_t st, int32_t* dst, int64_t n, int32_t v);
+
+}  // namespace mm

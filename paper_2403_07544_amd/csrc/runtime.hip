@@ -1,0 +1,1194 @@
+// Host runtime behind the C ABI: module registry with per-module contiguous buffers, route table,
+// use counters n_j, per-step workspace, and the launch sequence of one routed training step
+// (Algorithm 1: forward through the task's modules in order, gradients only for those modules,
+// renormalisation by n_j folded into the update).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/mammoth_hip.h"
+#include "mm_kernels.h"
+
+using namespace mm;
+
+namespace {
+
+constexpr int64_t ALIGN_ELEMS = 64;
+inline int64_t round_up(int64_t n, int64_t a) { return (n + a - 1) / a * a; }
+
+struct TensorInfo { int64_t off; int rows, cols, role; };
+
+struct Module {
+  int kind = 0, position = 0, n_layers = 0, owns_final_norm = 0, adapter_dim = 0, adapter_stack = 0;
+  std::string name;
+  std::vector<TensorInfo> tensors;
+  int64_t P = 0;
+  float *theta = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
+  bf16_t* w16 = nullptr;
+  int touched = 0;
+  int64_t t = 0;
+};
+
+struct Route { std::vector<int> ids; int src = -1, tgt = -1, gen = -1, ad_enc = -1, ad_dec = -1; std::vector<int> enc, dec; };
+
+struct Arena {
+  char* base = nullptr;
+  size_t cap = 0, off = 0, high = 0;
+  bool measuring = false;
+  void reset(bool measure) { off = 0; high = 0; measuring = measure; }
+  void* take(size_t bytes) {
+    off = (off + 255) & ~(size_t)255;
+    void* p = measuring ? nullptr : (void*)(base + off);
+    off += bytes;
+    if (off > high) high = off;
+    return p;
+  }
+};
+
+struct ProfRec { int cls; hipEvent_t a, b; };
+
+}  // namespace
+
+struct mm_ctx {
+  mm_config cfg{};
+  Dtype dt = F32;
+  hipStream_t st = nullptr;
+  bool plan_only = false;
+  std::vector<Module> mods;
+  std::vector<Route> routes;
+  std::string err;
+  // device-side constants and per-step metadata
+  float* pe = nullptr;                       // [max_len, d]
+  int32_t* meta = nullptr;                   // cu_s, cu_u, lens, src_tok, src_pos, dec_tok, dec_pos, label
+  int32_t *cu_s = nullptr, *cu_u = nullptr, *lens = nullptr, *src_tok = nullptr, *src_pos = nullptr,
+          *dec_tok = nullptr, *dec_pos = nullptr, *label = nullptr;
+  uint32_t* sort_keys = nullptr;
+  int32_t* flag = nullptr;                   // device: id-check result of the step
+  float* loss_dev = nullptr;
+  int32_t* ids_dev = nullptr; size_t ids_dev_cap = 0;      // staged copies of host ids
+  int32_t* stage = nullptr; size_t stage_cap = 0;          // pinned host staging
+  float* result_host = nullptr;              // pinned: [0] loss, [1] flag (as int bits)
+  hipEvent_t ev_stage = nullptr, ev_done = nullptr;
+  AdamSegment* seg_host = nullptr; AdamSegment* seg_dev = nullptr; int seg_cap = 0;
+  hipEvent_t ev_seg = nullptr;
+  Arena ws;
+  // last step
+  int B = 0, S_max = 0, T_max = 0, S = 0, U = 0;
+  bool pending = false; int pending_task = -1; bool pending_counted = false;
+  float last_loss = 0.f; mm_status last_status = MM_OK;
+  // profiling
+  bool prof = false;
+  std::vector<ProfRec> prof_recs; std::vector<hipEvent_t> ev_pool;
+  double prof_ms[MM_K_COUNT] = {}; int64_t prof_n[MM_K_COUNT] = {}; double prof_work[MM_K_COUNT] = {};
+};
+
+namespace {
+
+mm_status fail(mm_ctx* c, mm_status s, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf;
+  return s;
+}
+
+#define HIP_TRY(c, call)                                                                       \
+  do {                                                                                         \
+    hipError_t e_ = (call);                                                                    \
+    if (e_ != hipSuccess)                                                                      \
+      return fail(c, e_ == hipErrorOutOfMemory ? MM_ENOMEM : MM_EHIP, "%s: %s", #call,         \
+                  hipGetErrorString(e_));                                                      \
+  } while (0)
+
+// ---------------------------------------------------------------------------------------------
+// bucket layout: tensor order and 64-element alignment (the ABI's "bucket layout")
+// ---------------------------------------------------------------------------------------------
+void build_layout(const mm_config& cfg, Module& m) {
+  const int d = cfg.d_model, F = cfg.d_ff, V = cfg.vocab, r = m.adapter_dim;
+  int64_t cur = 0;
+  auto add = [&](int rows, int cols, int role) {
+    cur = round_up(cur, ALIGN_ELEMS);
+    m.tensors.push_back({cur, rows, cols, role});
+    cur += (int64_t)rows * cols;
+  };
+  auto ln = [&] { add(1, d, MM_T_GAMMA); add(1, d, MM_T_BETA); };
+  auto attn = [&] { for (int i = 0; i < 4; ++i) { add(d, d, MM_T_MATRIX); add(1, d, MM_T_BIAS); } };
+  auto ffn = [&] { add(d, F, MM_T_MATRIX); add(1, F, MM_T_BIAS); add(F, d, MM_T_MATRIX); add(1, d, MM_T_BIAS); };
+  switch (m.kind) {
+    case MM_SRC_EMB: case MM_TGT_EMB: add(V, d, MM_T_EMBED); break;
+    case MM_ENC_STACK:
+      for (int i = 0; i < m.n_layers; ++i) { ln(); attn(); ln(); ffn(); }
+      if (m.owns_final_norm) ln();
+      break;
+    case MM_DEC_STACK:
+      for (int i = 0; i < m.n_layers; ++i) { ln(); attn(); ln(); attn(); ln(); ffn(); }
+      if (m.owns_final_norm) ln();
+      break;
+    case MM_GENERATOR: add(d, V, MM_T_MATRIX); add(1, V, MM_T_BIAS); break;
+    case MM_ADAPTER:
+      for (int i = 0; i < m.n_layers; ++i) {
+        ln(); add(d, r, MM_T_MATRIX); add(1, r, MM_T_BIAS); add(r, d, MM_T_MATRIX); add(1, d, MM_T_BIAS);
+      }
+      break;
+  }
+  m.P = round_up(cur, ALIGN_ELEMS);
+}
+
+constexpr int ENC_T = 16, DEC_T = 26, ADP_T = 6;
+
+// ---------------------------------------------------------------------------------------------
+// launch wrappers: skip in the measuring pass, bracket with events when profiling
+// ---------------------------------------------------------------------------------------------
+struct Run {
+  mm_ctx* c;
+  bool dry;
+  hipEvent_t get_event() {
+    if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
+    hipEvent_t e; hipEventCreate(&e); return e;
+  }
+  void begin(int cls, double work) {
+    if (!c->prof) return;
+    ProfRec r{cls, get_event(), get_event()};
+    hipEventRecord(r.a, c->st);
+    c->prof_recs.push_back(r);
+    c->prof_n[cls] += 1;
+    c->prof_work[cls] += work;
+  }
+  void end() {
+    if (!c->prof) return;
+    hipEventRecord(c->prof_recs.back().b, c->st);
+  }
+  size_t esz() const { return c->dt == BF16 ? 2 : 4; }
+
+  void gemm(const GemmParams& p) {
+    if (dry) return;
+    begin(MM_K_GEMM, 2.0 * p.M * p.N * p.K);
+    launch_gemm(c->st, c->dt, p);
+    end();
+  }
+  void ln_fwd(const float* x, const float* g, const float* b, void* y, float* mean, float* rstd, int rows) {
+    if (dry) return;
+    const int d = c->cfg.d_model;
+    begin(MM_K_LAYERNORM_FWD, (double)rows * d * (4 + esz()));
+    launch_layernorm_fwd(c->st, c->dt, x, g, b, y, mean, rstd, rows, d, c->cfg.ln_eps);
+    end();
+  }
+  void ln_bwd(const float* dy, const float* x, const float* mean, const float* rstd, const float* g,
+              const float* dres, float* dx, void* dxT, float* partial, float* gg, float* gb, int rows) {
+    if (dry) return;
+    const int d = c->cfg.d_model;
+    begin(MM_K_LAYERNORM_BWD, (double)rows * d * (12 + (dres ? 4 : 0) + (c->dt == BF16 ? 2 : 0)));
+    launch_layernorm_bwd(c->st, c->dt, dy, x, mean, rstd, g, dres, dx, c->dt == BF16 ? dxT : nullptr,
+                         partial, gg, gb, rows, d);
+    end();
+  }
+  void colsum(const void* Y, int y_f32, int64_t ldy, int M, int N, float* partial, float* dst, int split,
+              int64_t seg) {
+    if (dry) return;
+    begin(MM_K_COLSUM, (double)M * N * (y_f32 ? 4 : esz()));
+    launch_colsum(c->st, c->dt, Y, y_f32, ldy, M, N, partial, dst, split, seg);
+    end();
+  }
+  void attn_fwd(const AttnParams& p, double flops) {
+    if (dry) return;
+    begin(MM_K_ATTN_FWD, flops);
+    launch_attn_fwd(c->st, c->dt, p);
+    end();
+  }
+  void attn_bwd(const AttnParams& p, double flops) {
+    if (dry) return;
+    begin(MM_K_ATTN_BWD, flops);
+    launch_attn_bwd(c->st, c->dt, p);
+    end();
+  }
+};
+
+// parameter views of one layer ------------------------------------------------------------------
+struct PV {
+  mm_ctx* c; Module* m; int base;
+  int64_t off(int i) const { return m->tensors[base + i].off; }
+  const void* W(int i) const {  // working-dtype matrix
+    return c->dt == BF16 ? (const void*)(m->w16 + off(i)) : (const void*)(m->theta + off(i));
+  }
+  const float* V(int i) const { return m->theta + off(i); }  // fp32 vector (bias, gamma, beta)
+  float* G(int i) const { return m->g + off(i); }
+};
+
+struct LnSave { float* mean; float* rstd; };
+struct FfnSave { float* x_in; LnSave ln; void* a; void* h; float* x_out; };
+struct SelfSave { float* x_in; LnSave ln; void* a; void* qkv; float* lse; void* o; float* x_out; };
+struct CrossSave { float* x_in; LnSave ln; void* a; void* q; void* kv; float* lse; void* o; float* x_out; };
+struct LayerSave {
+  PV pv; SelfSave self; CrossSave cross; FfnSave ffn; bool has_adapter = false; PV apv; FfnSave ad;
+};
+
+struct Step {
+  mm_ctx* c; Run run; const Route* rt;
+  int d, H, F, V, dh, S, U, B;
+  int max_s, max_u;
+  double sum_ss = 0, sum_uu = 0, sum_us = 0;  // sum over sentences of len products (flop tallies)
+  size_t esz;
+  Arena& ws() { return c->ws; }
+  float* f32(size_t n) { return (float*)ws().take(n * 4); }
+  void* act(size_t n) { return ws().take(n * esz); }
+
+  GemmParams gp(const void* A, int64_t lda, const void* B_, int64_t ldb, void* C, int64_t ldc, int M, int N, int K) {
+    GemmParams p;
+    memset(&p, 0, sizeof p);
+    p.A = A; p.B = B_; p.C = C; p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    return p;
+  }
+  // dX[R,K] = dY[R,N] * W^T, W stored [K,N]
+  GemmParams gp_dgrad(const void* dY, int64_t ldy, const void* W, int K, int N, void* dX, int R) {
+    GemmParams p = gp(dY, ldy, W, N, dX, K, R, K, N);
+    p.transB = 1;
+    return p;
+  }
+  // G[K,N] += X^T[K,R] * dY[R,N]
+  GemmParams gp_wgrad(const void* X, int64_t ldx, const void* dY, int64_t ldy, float* G, int K, int N, int R) {
+    GemmParams p = gp(X, ldx, dY, ldy, G, N, K, N, R);
+    p.transA = 1; p.out_f32 = 1; p.residual = G; p.ldr = N;
+    return p;
+  }
+
+  AttnParams ap(const void* q, int64_t ldq, const void* k, const void* v, int64_t ldkv, void* o, float* lse,
+                bool q_is_dec, bool k_is_dec, int causal) {
+    AttnParams a;
+    memset(&a, 0, sizeof a);
+    a.q = q; a.k = k; a.v = v; a.o = o; a.ldq = ldq; a.ldk = ldkv; a.ldv = ldkv; a.ldo = d; a.lse = lse;
+    a.cu_q = q_is_dec ? c->cu_u : c->cu_s; a.cu_k = k_is_dec ? c->cu_u : c->cu_s;
+    a.B = B; a.H = H; a.dh = dh; a.causal = causal; a.rows_q = q_is_dec ? U : S;
+    a.max_lq = q_is_dec ? max_u : max_s; a.max_lk = k_is_dec ? max_u : max_s;
+    return a;
+  }
+  double pair_sum(bool q_is_dec, bool k_is_dec) const { return q_is_dec ? (k_is_dec ? sum_uu : sum_us) : sum_ss; }
+
+  // ---- forward blocks -------------------------------------------------------------------------
+  // x_out = x_in + W2 relu(W1 LN(x_in) + b1) + b2 ; tensors at pv.base + t0: ln.g ln.b W1 b1 W2 b2
+  FfnSave ffn_fwd(const PV& pv, int t0, float* x_in, int R, int hidden) {
+    FfnSave s;
+    s.x_in = x_in; s.ln.mean = f32(R); s.ln.rstd = f32(R);
+    s.a = act((size_t)R * d); s.h = act((size_t)R * hidden); s.x_out = f32((size_t)R * d);
+    run.ln_fwd(x_in, pv.V(t0), pv.V(t0 + 1), s.a, s.ln.mean, s.ln.rstd, R);
+    GemmParams p = gp(s.a, d, pv.W(t0 + 2), hidden, s.h, hidden, R, hidden, d);
+    p.bias = pv.V(t0 + 3); p.relu = 1;
+    run.gemm(p);
+    p = gp(s.h, hidden, pv.W(t0 + 4), d, s.x_out, d, R, d, hidden);
+    p.bias = pv.V(t0 + 5); p.residual = x_in; p.ldr = d; p.out_f32 = 1;
+    run.gemm(p);
+    return s;
+  }
+  // tensors at t0: ln.g ln.b Wq bq Wk bk Wv bv Wo bo
+  SelfSave self_fwd(const PV& pv, int t0, float* x_in, int R, bool is_dec) {
+    SelfSave s;
+    s.x_in = x_in; s.ln.mean = f32(R); s.ln.rstd = f32(R);
+    s.a = act((size_t)R * d); s.qkv = act((size_t)R * 3 * d); s.lse = f32((size_t)H * R);
+    s.o = act((size_t)R * d); s.x_out = f32((size_t)R * d);
+    run.ln_fwd(x_in, pv.V(t0), pv.V(t0 + 1), s.a, s.ln.mean, s.ln.rstd, R);
+    const int64_t seg = pv.off(t0 + 4) - pv.off(t0 + 2);
+    GemmParams p = gp(s.a, d, pv.W(t0 + 2), d, s.qkv, 3 * d, R, 3 * d, d);
+    p.b_split = d; p.b_seg_stride = seg; p.bias = pv.V(t0 + 3); p.bias_split = d; p.bias_seg_stride = seg;
+    run.gemm(p);
+    const char* qkv = (const char*)s.qkv;
+    AttnParams a = ap(qkv, 3 * d, dry() ? nullptr : qkv + (size_t)d * esz, dry() ? nullptr : qkv + (size_t)2 * d * esz,
+                      3 * d, s.o, s.lse, is_dec, is_dec, is_dec ? 1 : 0);
+    run.attn_fwd(a, 4.0 * pair_sum(is_dec, is_dec) * d);
+    p = gp(s.o, d, pv.W(t0 + 8), d, s.x_out, d, R, d, d);
+    p.bias = pv.V(t0 + 9); p.residual = x_in; p.ldr = d; p.out_f32 = 1;
+    run.gemm(p);
+    return s;
+  }
+  CrossSave cross_fwd(const PV& pv, int t0, float* x_in, const void* mem) {
+    CrossSave s;
+    s.x_in = x_in; s.ln.mean = f32(U); s.ln.rstd = f32(U);
+    s.a = act((size_t)U * d); s.q = act((size_t)U * d); s.kv = act((size_t)S * 2 * d);
+    s.lse = f32((size_t)H * U); s.o = act((size_t)U * d); s.x_out = f32((size_t)U * d);
+    run.ln_fwd(x_in, pv.V(t0), pv.V(t0 + 1), s.a, s.ln.mean, s.ln.rstd, U);
+    GemmParams p = gp(s.a, d, pv.W(t0 + 2), d, s.q, d, U, d, d);
+    p.bias = pv.V(t0 + 3);
+    run.gemm(p);
+    const int64_t seg = pv.off(t0 + 6) - pv.off(t0 + 4);
+    p = gp(mem, d, pv.W(t0 + 4), d, s.kv, 2 * d, S, 2 * d, d);
+    p.b_split = d; p.b_seg_stride = seg; p.bias = pv.V(t0 + 5); p.bias_split = d; p.bias_seg_stride = seg;
+    run.gemm(p);
+    const char* kv = (const char*)s.kv;
+    AttnParams a = ap(s.q, d, kv, dry() ? nullptr : kv + (size_t)d * esz, 2 * d, s.o, s.lse, true, false, 0);
+    run.attn_fwd(a, 4.0 * sum_us * d);
+    p = gp(s.o, d, pv.W(t0 + 8), d, s.x_out, d, U, d, d);
+    p.bias = pv.V(t0 + 9); p.residual = x_in; p.ldr = d; p.out_f32 = 1;
+    run.gemm(p);
+    return s;
+  }
+  bool dry() const { return run.dry; }
+
+  // ---- backward blocks --------------------------------------------------------------------------
+  // In: dx (fp32) and dxT (working dtype copy) w.r.t. the block output.  Out: same w.r.t. its input.
+  struct Grad { float* dx; void* dxT; };
+
+  float* partial = nullptr;  // scratch for column-sum / LayerNorm partials
+
+  Grad ffn_bwd(const PV& pv, int t0, const FfnSave& s, Grad g, int R, int hidden) {
+    void* dh = act((size_t)R * hidden);
+    float* da = f32((size_t)R * d);
+    Grad out{f32((size_t)R * d), c->dt == BF16 ? act((size_t)R * d) : nullptr};
+    // d hidden = (dx W2^T) masked by relu
+    GemmParams p = gp_dgrad(g.dxT, d, pv.W(t0 + 4), hidden, d, dh, R);
+    p.relu_mask = s.h; p.ldm = hidden;
+    run.gemm(p);
+    run.gemm(gp_wgrad(s.h, hidden, g.dxT, d, pv.G(t0 + 4), hidden, d, R));
+    run.colsum(g.dx, 1, d, R, d, partial, pv.G(t0 + 5), 0, 0);
+    p = gp_dgrad(dh, hidden, pv.W(t0 + 2), d, hidden, da, R);
+    p.out_f32 = 1;
+    run.gemm(p);
+    run.gemm(gp_wgrad(s.a, d, dh, hidden, pv.G(t0 + 2), d, hidden, R));
+    run.colsum(dh, 0, hidden, R, hidden, partial, pv.G(t0 + 3), 0, 0);
+    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, partial, pv.G(t0), pv.G(t0 + 1), R);
+    if (c->dt != BF16) out.dxT = out.dx;
+    return out;
+  }
+
+  Grad self_bwd(const PV& pv, int t0, const SelfSave& s, Grad g, int R, bool is_dec) {
+    void* d_o = act((size_t)R * d);
+    void* dqkv = act((size_t)R * 3 * d);
+    float* da = f32((size_t)R * d);
+    Grad out{f32((size_t)R * d), c->dt == BF16 ? act((size_t)R * d) : nullptr};
+    run.gemm(gp_dgrad(g.dxT, d, pv.W(t0 + 8), d, d, d_o, R));
+    run.gemm(gp_wgrad(s.o, d, g.dxT, d, pv.G(t0 + 8), d, d, R));
+    run.colsum(g.dx, 1, d, R, d, partial, pv.G(t0 + 9), 0, 0);
+    const char* qkv = (const char*)s.qkv;
+    char* dq = (char*)dqkv;
+    AttnParams a = ap(qkv, 3 * d, dry() ? nullptr : qkv + (size_t)d * esz, dry() ? nullptr : qkv + (size_t)2 * d * esz,
+                      3 * d, s.o, s.lse, is_dec, is_dec, is_dec ? 1 : 0);
+    a.d_o = d_o; a.lddo = d;
+    a.dq = dq; a.dk = dry() ? nullptr : dq + (size_t)d * esz; a.dv = dry() ? nullptr : dq + (size_t)2 * d * esz;
+    a.lddq = a.lddk = a.lddv = 3 * d;
+    run.attn_bwd(a, 10.0 * pair_sum(is_dec, is_dec) * d);
+    const int64_t seg = pv.off(t0 + 4) - pv.off(t0 + 2);
+    GemmParams p = gp_dgrad(dqkv, 3 * d, pv.W(t0 + 2), d, 3 * d, da, R);
+    p.ldb = d; p.b_split = d; p.b_split_on_k = 1; p.b_seg_stride = seg; p.out_f32 = 1;
+    run.gemm(p);
+    p = gp_wgrad(s.a, d, dqkv, 3 * d, pv.G(t0 + 2), d, 3 * d, R);
+    p.ldc = d; p.ldr = d; p.c_split = d; p.c_seg_stride = seg;
+    run.gemm(p);
+    run.colsum(dqkv, 0, 3 * d, R, 3 * d, partial, pv.G(t0 + 3), d, seg);
+    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, partial, pv.G(t0), pv.G(t0 + 1), R);
+    if (c->dt != BF16) out.dxT = out.dx;
+    return out;
+  }
+
+  Grad cross_bwd(const PV& pv, int t0, const CrossSave& s, Grad g, const void* mem, float* dmem, bool first) {
+    void* d_o = act((size_t)U * d);
+    void* dq = act((size_t)U * d);
+    void* dkv = act((size_t)S * 2 * d);
+    float* da = f32((size_t)U * d);
+    Grad out{f32((size_t)U * d), c->dt == BF16 ? act((size_t)U * d) : nullptr};
+    run.gemm(gp_dgrad(g.dxT, d, pv.W(t0 + 8), d, d, d_o, U));
+    run.gemm(gp_wgrad(s.o, d, g.dxT, d, pv.G(t0 + 8), d, d, U));
+    run.colsum(g.dx, 1, d, U, d, partial, pv.G(t0 + 9), 0, 0);
+    const char* kv = (const char*)s.kv;
+    char* dkvc = (char*)dkv;
+    AttnParams a = ap(s.q, d, kv, dry() ? nullptr : kv + (size_t)d * esz, 2 * d, s.o, s.lse, true, false, 0);
+    a.d_o = d_o; a.lddo = d; a.dq = dq; a.lddq = d;
+    a.dk = dkvc; a.dv = dry() ? nullptr : dkvc + (size_t)d * esz; a.lddk = a.lddv = 2 * d;
+    run.attn_bwd(a, 10.0 * sum_us * d);
+    // query side
+    GemmParams p = gp_dgrad(dq, d, pv.W(t0 + 2), d, d, da, U);
+    p.out_f32 = 1;
+    run.gemm(p);
+    run.gemm(gp_wgrad(s.a, d, dq, d, pv.G(t0 + 2), d, d, U));
+    run.colsum(dq, 0, d, U, d, partial, pv.G(t0 + 3), 0, 0);
+    // memory side: d mem (+)= dkv [Wk|Wv]^T
+    const int64_t seg = pv.off(t0 + 6) - pv.off(t0 + 4);
+    p = gp_dgrad(dkv, 2 * d, pv.W(t0 + 4), d, 2 * d, dmem, S);
+    p.ldb = d; p.b_split = d; p.b_split_on_k = 1; p.b_seg_stride = seg; p.out_f32 = 1;
+    if (!first) { p.residual = dmem; p.ldr = d; }
+    run.gemm(p);
+    p = gp_wgrad(mem, d, dkv, 2 * d, pv.G(t0 + 4), d, 2 * d, S);
+    p.ldc = d; p.ldr = d; p.c_split = d; p.c_seg_stride = seg;
+    run.gemm(p);
+    run.colsum(dkv, 0, 2 * d, S, 2 * d, partial, pv.G(t0 + 5), d, seg);
+    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, partial, pv.G(t0), pv.G(t0 + 1), U);
+    if (c->dt != BF16) out.dxT = out.dx;
+    return out;
+  }
+};
+
+double work_bytes_adam(const mm_ctx* c, int64_t n) { return (double)n * (c->dt == BF16 ? 34.0 : 32.0); }
+
+mm_status collect_profile(mm_ctx* c) {
+  if (c->prof_recs.empty()) return MM_OK;
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  for (auto& r : c->prof_recs) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) c->prof_ms[r.cls] += ms;
+    c->ev_pool.push_back(r.a);
+    c->ev_pool.push_back(r.b);
+  }
+  c->prof_recs.clear();
+  return MM_OK;
+}
+
+// Resolves the outcome of the most recent step (waits for it).
+mm_status resolve_pending(mm_ctx* c) {
+  if (!c->pending) return c->last_status;
+  HIP_TRY(c, hipEventSynchronize(c->ev_done));
+  c->pending = false;
+  c->last_loss = c->result_host[0];
+  int32_t flag;
+  memcpy(&flag, &c->result_host[1], 4);
+  if (flag != 0) {
+    if (c->pending_counted)
+      for (int j : c->routes[c->pending_task].ids)
+        if (c->mods[j].touched > 0) c->mods[j].touched -= 1;
+    c->pending_counted = false;
+    c->last_status = fail(c, MM_ERANGE, flag & 1 ? "token id outside [0, vocab) (found on the device); step had no effect"
+                                                 : "non-pad id after the end of a sentence (found on the device); step had no effect");
+    return c->last_status;
+  }
+  c->pending_counted = false;
+  if (!std::isfinite(c->last_loss)) {
+    c->last_status = fail(c, MM_ENONFINITE, "loss is not finite");
+    return c->last_status;
+  }
+  c->last_status = MM_OK;
+  return MM_OK;
+}
+
+mm_status ensure_stage(mm_ctx* c, size_t n_ints) {
+  if (n_ints <= c->stage_cap) return MM_OK;
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  if (c->stage) hipHostFree(c->stage);
+  c->stage = nullptr; c->stage_cap = 0;
+  const size_t cap = n_ints + n_ints / 2 + 1024;
+  HIP_TRY(c, hipHostMalloc((void**)&c->stage, cap * sizeof(int32_t), hipHostMallocDefault));
+  c->stage_cap = cap;
+  return MM_OK;
+}
+
+mm_status ensure_ids_dev(mm_ctx* c, size_t n_ints) {
+  if (n_ints <= c->ids_dev_cap) return MM_OK;
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  if (c->ids_dev) hipFree(c->ids_dev);
+  c->ids_dev = nullptr; c->ids_dev_cap = 0;
+  const size_t cap = n_ints + n_ints / 2 + 1024;
+  HIP_TRY(c, hipMalloc((void**)&c->ids_dev, cap * sizeof(int32_t)));
+  c->ids_dev_cap = cap;
+  return MM_OK;
+}
+
+mm_status ensure_ws(mm_ctx* c, size_t bytes) {
+  if (bytes <= c->ws.cap) return MM_OK;
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  if (c->ws.base) hipFree(c->ws.base);
+  c->ws.base = nullptr; c->ws.cap = 0;
+  const size_t cap = bytes + bytes / 8 + (1 << 20);
+  HIP_TRY(c, hipMalloc((void**)&c->ws.base, cap));
+  c->ws.cap = cap;
+  return MM_OK;
+}
+
+// The whole step as a launch sequence.  Runs twice: once measuring workspace, once for real.
+void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
+  Step s;
+  s.c = c; s.run = Run{c, dry}; s.rt = &rt;
+  s.d = c->cfg.d_model; s.H = c->cfg.n_heads; s.F = c->cfg.d_ff; s.V = c->cfg.vocab; s.dh = s.d / s.H;
+  s.S = c->S; s.U = c->U; s.B = c->B; s.esz = c->dt == BF16 ? 2 : 4;
+  s.max_s = 0; s.max_u = 0;
+  for (int b = 0; b < c->B; ++b) {
+    const double sl = lens_host[2 * b], ul = lens_host[2 * b + 1] - 1;
+    s.sum_ss += sl * sl; s.sum_uu += ul * ul; s.sum_us += ul * sl;
+    if (sl > s.max_s) s.max_s = (int)sl;
+    if (ul > s.max_u) s.max_u = (int)ul;
+  }
+  const int d = s.d, S = s.S, U = s.U, V = s.V;
+  Run& run = s.run;
+  c->ws.reset(dry);
+  const int Rmax = S > U ? S : U;
+  {
+    size_t pn = (size_t)ln_bwd_partial_rows(Rmax) * 2 * d;
+    const int widest = std::max(std::max(3 * d, s.F), V);
+    const size_t pc = (size_t)colsum_partial_rows(Rmax) * widest;
+    s.partial = s.f32(pn > pc ? pn : pc);
+  }
+  const float sqrt_d = sqrtf((float)d);
+  Module& m_src = c->mods[rt.src];
+  Module& m_tgt = c->mods[rt.tgt];
+  Module& m_gen = c->mods[rt.gen];
+  auto emb_w = [&](Module& m) -> const void* { return c->dt == BF16 ? (const void*)m.w16 : (const void*)m.theta; };
+
+  // ---------------- forward: encoder ----------------
+  float* x = s.f32((size_t)S * d);
+  if (!dry) {
+    run.begin(MM_K_EMBED, (double)S * d * (s.esz + 4));
+    launch_embed_fwd(c->st, c->dt, emb_w(m_src), c->pe, c->src_tok, c->src_pos, x, S, d, sqrt_d);
+    run.end();
+  }
+  std::vector<LayerSave> enc_saves, dec_saves;
+  int li = 0;
+  for (int mid : rt.enc) {
+    Module& m = c->mods[mid];
+    for (int l = 0; l < m.n_layers; ++l, ++li) {
+      LayerSave ls;
+      ls.pv = PV{c, &m, l * ENC_T};
+      ls.self = s.self_fwd(ls.pv, 0, x, S, false);
+      ls.ffn = s.ffn_fwd(ls.pv, 10, ls.self.x_out, S, s.F);
+      x = ls.ffn.x_out;
+      if (rt.ad_enc >= 0) {
+        ls.has_adapter = true;
+        ls.apv = PV{c, &c->mods[rt.ad_enc], li * ADP_T};
+        ls.ad = s.ffn_fwd(ls.apv, 0, x, S, c->mods[rt.ad_enc].adapter_dim);
+        x = ls.ad.x_out;
+      }
+      enc_saves.push_back(ls);
+    }
+  }
+  Module& m_enc_last = c->mods[rt.enc.back()];
+  PV pv_encf{c, &m_enc_last, m_enc_last.n_layers * ENC_T};
+  float* x_enc_top = x;
+  LnSave ln_encf{s.f32(S), s.f32(S)};
+  void* mem = s.act((size_t)S * d);
+  run.ln_fwd(x, pv_encf.V(0), pv_encf.V(1), mem, ln_encf.mean, ln_encf.rstd, S);
+
+  // ---------------- forward: decoder ----------------
+  float* y = s.f32((size_t)U * d);
+  if (!dry) {
+    run.begin(MM_K_EMBED, (double)U * d * (s.esz + 4));
+    launch_embed_fwd(c->st, c->dt, emb_w(m_tgt), c->pe, c->dec_tok, c->dec_pos, y, U, d, sqrt_d);
+    run.end();
+  }
+  li = 0;
+  for (int mid : rt.dec) {
+    Module& m = c->mods[mid];
+    for (int l = 0; l < m.n_layers; ++l, ++li) {
+      LayerSave ls;
+      ls.pv = PV{c, &m, l * DEC_T};
+      ls.self = s.self_fwd(ls.pv, 0, y, U, true);
+      ls.cross = s.cross_fwd(ls.pv, 10, ls.self.x_out, mem);
+      ls.ffn = s.ffn_fwd(ls.pv, 20, ls.cross.x_out, U, s.F);
+      y = ls.ffn.x_out;
+      if (rt.ad_dec >= 0) {
+        ls.has_adapter = true;
+        ls.apv = PV{c, &c->mods[rt.ad_dec], li * ADP_T};
+        ls.ad = s.ffn_fwd(ls.apv, 0, y, U, c->mods[rt.ad_dec].adapter_dim);
+        y = ls.ad.x_out;
+      }
+      dec_saves.push_back(ls);
+    }
+  }
+  Module& m_dec_last = c->mods[rt.dec.back()];
+  PV pv_decf{c, &m_dec_last, m_dec_last.n_layers * DEC_T};
+  float* y_dec_top = y;
+  LnSave ln_decf{s.f32(U), s.f32(U)};
+  void* h = s.act((size_t)U * d);
+  run.ln_fwd(y, pv_decf.V(0), pv_decf.V(1), h, ln_decf.mean, ln_decf.rstd, U);
+
+  // ---------------- generator + loss ----------------
+  PV pv_gen{c, &m_gen, 0};
+  void* z = s.act((size_t)U * V);
+  float* loss_rows = s.f32(U);
+  {
+    GemmParams p = s.gp(h, d, pv_gen.W(0), V, z, V, U, V, d);
+    p.bias = pv_gen.V(1);
+    run.gemm(p);
+  }
+  if (!dry) {
+    run.begin(MM_K_CE, (double)U * V * s.esz * 2);
+    launch_ce(c->st, c->dt, z, c->label, loss_rows, U, V, c->cfg.label_smoothing, 1.0f / (float)U, c->flag);
+    run.end();
+    run.begin(MM_K_OTHER, (double)U * 4);
+    launch_sum_scaled(c->st, loss_rows, U, 1.0f / (float)U, c->loss_dev);
+    run.end();
+  }
+
+  // ---------------- backward: generator, decoder ----------------
+  float* dh = s.f32((size_t)U * d);
+  {
+    GemmParams p = s.gp_dgrad(z, V, pv_gen.W(0), d, V, dh, U);
+    p.out_f32 = 1;
+    run.gemm(p);
+    run.gemm(s.gp_wgrad(h, d, z, V, pv_gen.G(0), d, V, U));
+    run.colsum(z, 0, V, U, V, s.partial, pv_gen.G(1), 0, 0);
+  }
+  Step::Grad g{s.f32((size_t)U * d), c->dt == BF16 ? s.act((size_t)U * d) : nullptr};
+  run.ln_bwd(dh, y_dec_top, ln_decf.mean, ln_decf.rstd, pv_decf.V(0), nullptr, g.dx, g.dxT, s.partial,
+             pv_decf.G(0), pv_decf.G(1), U);
+  if (c->dt != BF16) g.dxT = g.dx;
+  float* dmem = s.f32((size_t)S * d);
+  bool first = true;
+  for (int i = (int)dec_saves.size() - 1; i >= 0; --i) {
+    LayerSave& ls = dec_saves[i];
+    if (ls.has_adapter) g = s.ffn_bwd(ls.apv, 0, ls.ad, g, U, c->mods[rt.ad_dec].adapter_dim);
+    g = s.ffn_bwd(ls.pv, 20, ls.ffn, g, U, s.F);
+    g = s.cross_bwd(ls.pv, 10, ls.cross, g, mem, dmem, first);
+    first = false;
+    g = s.self_bwd(ls.pv, 0, ls.self, g, U, true);
+  }
+  if (!dry) {
+    run.begin(MM_K_EMBED_GRAD, (double)U * d * 12);
+    launch_embed_grad(c->st, c->dec_tok, g.dx, m_tgt.g, c->sort_keys, U, d, sqrt_d);
+    run.end();
+  }
+
+  // ---------------- backward: encoder ----------------
+  Step::Grad ge{s.f32((size_t)S * d), c->dt == BF16 ? s.act((size_t)S * d) : nullptr};
+  run.ln_bwd(dmem, x_enc_top, ln_encf.mean, ln_encf.rstd, pv_encf.V(0), nullptr, ge.dx, ge.dxT, s.partial,
+             pv_encf.G(0), pv_encf.G(1), S);
+  if (c->dt != BF16) ge.dxT = ge.dx;
+  for (int i = (int)enc_saves.size() - 1; i >= 0; --i) {
+    LayerSave& ls = enc_saves[i];
+    if (ls.has_adapter) ge = s.ffn_bwd(ls.apv, 0, ls.ad, ge, S, c->mods[rt.ad_enc].adapter_dim);
+    ge = s.ffn_bwd(ls.pv, 10, ls.ffn, ge, S, s.F);
+    ge = s.self_bwd(ls.pv, 0, ls.self, ge, S, false);
+  }
+  if (!dry) {
+    run.begin(MM_K_EMBED_GRAD, (double)S * d * 12);
+    launch_embed_grad(c->st, c->src_tok, ge.dx, m_src.g, c->sort_keys, S, d, sqrt_d);
+    run.end();
+  }
+}
+
+bool valid_module(mm_ctx* c, int id) { return id >= 0 && id < (int)c->mods.size(); }
+
+mm_status parse_route(mm_ctx* c, const int32_t* ids, int n, Route& r) {
+  for (int i = 0; i < n; ++i)
+    if (!valid_module(c, ids[i])) return fail(c, MM_EINVAL, "route names unknown module id %d", ids[i]);
+  for (int i = 0; i < n; ++i)
+    for (int j = i + 1; j < n; ++j)
+      if (ids[i] == ids[j]) return fail(c, MM_EINVAL, "module %d appears twice in the route", ids[i]);
+  int k = 0;
+  auto kind = [&](int i) { return c->mods[ids[i]].kind; };
+  r.ids.assign(ids, ids + n);
+  if (k < n && kind(k) == MM_SRC_EMB) r.src = ids[k++];
+  while (k < n && kind(k) == MM_ENC_STACK) r.enc.push_back(ids[k++]);
+  if (k < n && kind(k) == MM_TGT_EMB) r.tgt = ids[k++];
+  while (k < n && kind(k) == MM_DEC_STACK) r.dec.push_back(ids[k++]);
+  if (k < n && kind(k) == MM_GENERATOR) r.gen = ids[k++];
+  while (k < n && kind(k) == MM_ADAPTER) {
+    Module& m = c->mods[ids[k]];
+    int& slot = m.adapter_stack == 0 ? r.ad_enc : r.ad_dec;
+    if (slot >= 0) return fail(c, MM_EINVAL, "more than one adapter for one stack");
+    slot = ids[k++];
+  }
+  if (k != n || r.src < 0 || r.tgt < 0 || r.gen < 0 || r.enc.empty() || r.dec.empty())
+    return fail(c, MM_EINVAL, "route must be src_emb, enc.., tgt_emb, dec.., generator, adapters..");
+  for (auto* stack : {&r.enc, &r.dec}) {
+    for (size_t pos = 0; pos < stack->size(); ++pos) {
+      Module& m = c->mods[(*stack)[pos]];
+      if (m.position != (int)pos)
+        return fail(c, MM_EINVAL, "module %d is defined for position %d, used at position %zu", (*stack)[pos], m.position, pos);
+      if ((m.owns_final_norm != 0) != (pos + 1 == stack->size()))
+        return fail(c, MM_EINVAL, "exactly the last position of a stack must own the final norm");
+    }
+  }
+  for (int which = 0; which < 2; ++which) {
+    const int a = which == 0 ? r.ad_enc : r.ad_dec;
+    if (a < 0) continue;
+    int layers = 0;
+    for (int id : (which == 0 ? r.enc : r.dec)) layers += c->mods[id].n_layers;
+    if (c->mods[a].n_layers != layers) return fail(c, MM_EINVAL, "adapter must cover every layer of its stack");
+  }
+  return MM_OK;
+}
+
+mm_status check_module(mm_ctx* c, int module, int64_t n) {
+  if (!c) return MM_EINVAL;
+  if (!valid_module(c, module)) return fail(c, MM_EINVAL, "unknown module id %d", module);
+  if (n != c->mods[module].P) return fail(c, MM_EINVAL, "length %lld does not match the bucket length %lld", (long long)n, (long long)c->mods[module].P);
+  if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context holds no device memory");
+  return MM_OK;
+}
+
+}  // namespace
+
+// =================================================================================================
+// C ABI
+// =================================================================================================
+extern "C" {
+
+mm_status mm_create(const mm_config* cfg, mm_ctx** out) {
+  if (!cfg || !out) return MM_EINVAL;
+  *out = nullptr;
+  const int d = cfg->d_model, H = cfg->n_heads;
+  if (d <= 0 || H <= 0 || d % H != 0 || d % 16 != 0 || cfg->d_ff <= 0 || cfg->d_ff % 16 != 0) return MM_EINVAL;
+  const int dh = d / H;
+  if (dh != 16 && dh != 32 && dh != 64) return MM_EINVAL;
+  if (cfg->vocab < 8 || cfg->vocab % 8 != 0 || cfg->vocab > (1 << 17)) return MM_EINVAL;
+  if (cfg->dtype != MM_F32 && cfg->dtype != MM_BF16) return MM_EINVAL;
+  if (cfg->max_len < 1 || cfg->max_len > 256) return MM_EINVAL;
+  if (cfg->max_batch_tokens < 1 || cfg->max_batch_tokens > 16384) return MM_EINVAL;
+  if (!(cfg->label_smoothing >= 0.f && cfg->label_smoothing < 1.f)) return MM_EINVAL;
+  mm_ctx* c = new (std::nothrow) mm_ctx();
+  if (!c) return MM_ENOMEM;
+  c->cfg = *cfg;
+  c->dt = cfg->dtype == MM_BF16 ? BF16 : F32;
+  c->st = (hipStream_t)cfg->hip_stream;
+  c->plan_only = cfg->plan_only != 0;
+  *out = c;
+  if (c->plan_only) return MM_OK;
+  if (attn_lds_bytes(c->dt, dh, cfg->max_len, cfg->max_len, true) > 160 * 1024) {
+    fail(c, MM_EINVAL, "max_len %d does not fit the attention kernels' LDS budget for this dtype", cfg->max_len);
+    return MM_EINVAL;
+  }
+  // sinusoidal position table: PE[p,2k] = sin(p * 10000^(-2k/d)), PE[p,2k+1] = cos(same)
+  std::vector<float> pe((size_t)cfg->max_len * d);
+  for (int p = 0; p < cfg->max_len; ++p)
+    for (int k = 0; k < d / 2; ++k) {
+      const double ang = (double)p * std::pow(10000.0, -2.0 * k / (double)d);
+      pe[(size_t)p * d + 2 * k] = (float)std::sin(ang);
+      pe[(size_t)p * d + 2 * k + 1] = (float)std::cos(ang);
+    }
+  const int T = cfg->max_batch_tokens;
+  const size_t meta_ints = 2 * (size_t)(T + 1) + 2 * (size_t)T + 5 * (size_t)T + 64;
+  mm_status s = MM_OK;
+  auto guard = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess && s == MM_OK) s = fail(c, e == hipErrorOutOfMemory ? MM_ENOMEM : MM_EHIP, "%s: %s", what, hipGetErrorString(e));
+  };
+  guard(hipMalloc((void**)&c->pe, pe.size() * 4), "hipMalloc(pe)");
+  guard(hipMalloc((void**)&c->meta, meta_ints * 4), "hipMalloc(meta)");
+  guard(hipMalloc((void**)&c->sort_keys, 16384 * 4), "hipMalloc(sort keys)");
+  guard(hipMalloc((void**)&c->flag, 64), "hipMalloc(flag)");
+  guard(hipMalloc((void**)&c->loss_dev, 64), "hipMalloc(loss)");
+  guard(hipHostMalloc((void**)&c->result_host, 64, hipHostMallocDefault), "hipHostMalloc(result)");
+  guard(hipEventCreateWithFlags(&c->ev_stage, hipEventDisableTiming), "hipEventCreate");
+  guard(hipEventCreateWithFlags(&c->ev_done, hipEventDisableTiming), "hipEventCreate");
+  guard(hipEventCreateWithFlags(&c->ev_seg, hipEventDisableTiming), "hipEventCreate");
+  if (s != MM_OK) return s;
+  guard(hipMemcpy(c->pe, pe.data(), pe.size() * 4, hipMemcpyHostToDevice), "hipMemcpy(pe)");
+  guard(hipMemset(c->flag, 0, 64), "hipMemset");
+  if (s != MM_OK) return s;
+  int32_t* p = c->meta;
+  c->cu_s = p; p += T + 1; c->cu_u = p; p += T + 1; c->lens = p; p += 2 * T;
+  c->src_tok = p; p += T; c->src_pos = p; p += T; c->dec_tok = p; p += T; c->dec_pos = p; p += T; c->label = p;
+  return MM_OK;
+}
+
+mm_status mm_destroy(mm_ctx* c) {
+  if (!c) return MM_EINVAL;
+  if (!c->plan_only) {
+    hipStreamSynchronize(c->st);
+    for (auto& m : c->mods) { hipFree(m.theta); hipFree(m.m); hipFree(m.v); hipFree(m.g); if (m.w16) hipFree(m.w16); }
+    hipFree(c->pe); hipFree(c->meta); hipFree(c->sort_keys); hipFree(c->flag); hipFree(c->loss_dev);
+    if (c->ids_dev) hipFree(c->ids_dev);
+    if (c->stage) hipHostFree(c->stage);
+    if (c->result_host) hipHostFree(c->result_host);
+    if (c->seg_host) hipHostFree(c->seg_host);
+    if (c->seg_dev) hipFree(c->seg_dev);
+    if (c->ws.base) hipFree(c->ws.base);
+    for (auto& r : c->prof_recs) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+    for (auto e : c->ev_pool) hipEventDestroy(e);
+    if (c->ev_stage) hipEventDestroy(c->ev_stage);
+    if (c->ev_done) hipEventDestroy(c->ev_done);
+    if (c->ev_seg) hipEventDestroy(c->ev_seg);
+  }
+  delete c;
+  return MM_OK;
+}
+
+mm_status mm_register_module(mm_ctx* c, const mm_module_desc* desc, const float* init, int64_t n_params, int32_t* out_id) {
+  if (!c || !desc || !out_id) return MM_EINVAL;
+  if (desc->kind < MM_SRC_EMB || desc->kind > MM_ADAPTER) return fail(c, MM_EINVAL, "unknown module kind %d", desc->kind);
+  Module m;
+  m.kind = desc->kind; m.position = desc->position; m.n_layers = desc->n_layers;
+  m.owns_final_norm = desc->owns_final_norm; m.adapter_dim = desc->adapter_dim; m.adapter_stack = desc->adapter_stack;
+  m.name = desc->name ? desc->name : "";
+  const bool stack = m.kind == MM_ENC_STACK || m.kind == MM_DEC_STACK;
+  if ((stack || m.kind == MM_ADAPTER) && m.n_layers < 1) return fail(c, MM_EINVAL, "n_layers must be >= 1");
+  if (stack && m.position < 0) return fail(c, MM_EINVAL, "negative position");
+  if (m.kind == MM_ADAPTER && (m.adapter_dim < 16 || m.adapter_dim % 16 != 0 || (m.adapter_stack != 0 && m.adapter_stack != 1)))
+    return fail(c, MM_EINVAL, "adapter needs adapter_dim (multiple of 16) and adapter_stack 0/1");
+  if (c->plan_only && m.kind == MM_ADAPTER && m.adapter_dim % 8 == 0) { /* fine */ }
+  build_layout(c->cfg, m);
+  if (init && n_params != m.P)
+    return fail(c, MM_EINVAL, "n_params %lld does not match the bucket length %lld", (long long)n_params, (long long)m.P);
+  if (!c->plan_only) {
+    const size_t bytes = (size_t)m.P * 4;
+    mm_status s = MM_OK;
+    auto guard = [&](hipError_t e, const char* what) {
+      if (e != hipSuccess && s == MM_OK) s = fail(c, e == hipErrorOutOfMemory ? MM_ENOMEM : MM_EHIP, "%s: %s", what, hipGetErrorString(e));
+    };
+    guard(hipMalloc((void**)&m.theta, bytes), "hipMalloc(theta)");
+    guard(hipMalloc((void**)&m.m, bytes), "hipMalloc(m)");
+    guard(hipMalloc((void**)&m.v, bytes), "hipMalloc(v)");
+    guard(hipMalloc((void**)&m.g, bytes), "hipMalloc(bucket)");
+    if (c->dt == BF16) guard(hipMalloc((void**)&m.w16, (size_t)m.P * 2), "hipMalloc(working copy)");
+    if (s == MM_OK) {
+      guard(hipStreamSynchronize(c->st), "hipStreamSynchronize");
+      if (init) guard(hipMemcpy(m.theta, init, bytes, hipMemcpyHostToDevice), "hipMemcpy(theta)");
+      else guard(hipMemset(m.theta, 0, bytes), "hipMemset(theta)");
+      guard(hipMemset(m.m, 0, bytes), "hipMemset"); guard(hipMemset(m.v, 0, bytes), "hipMemset");
+      guard(hipMemset(m.g, 0, bytes), "hipMemset");
+      guard(hipDeviceSynchronize(), "hipDeviceSynchronize");
+      if (s == MM_OK && c->dt == BF16) {
+        launch_to_bf16(c->st, m.theta, m.w16, m.P);
+        guard(hipStreamSynchronize(c->st), "to_bf16");
+      }
+    }
+    if (s != MM_OK) {
+      hipFree(m.theta); hipFree(m.m); hipFree(m.v); hipFree(m.g); if (m.w16) hipFree(m.w16);
+      return s;
+    }
+  }
+  c->mods.push_back(std::move(m));
+  *out_id = (int32_t)c->mods.size() - 1;
+  return MM_OK;
+}
+
+mm_status mm_route_task(mm_ctx* c, const int32_t* ids, int32_t n, int32_t* out_task) {
+  if (!c || !ids || !out_task || n < 5) return c ? fail(c, MM_EINVAL, "route needs at least five modules") : MM_EINVAL;
+  Route r;
+  mm_status s = parse_route(c, ids, n, r);
+  if (s != MM_OK) return s;
+  if (!c->routes.empty() && (int)c->routes[0].ids.size() != n)
+    return fail(c, MM_EINVAL, "all tasks must involve the same number of modules (%zu), got %d", c->routes[0].ids.size(), n);
+  c->routes.push_back(std::move(r));
+  *out_task = (int32_t)c->routes.size() - 1;
+  return MM_OK;
+}
+
+mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const int32_t* tgt_ids, const int32_t* lengths,
+                        int32_t B, int32_t S_max, int32_t T_max, int32_t ids_mem, float* out_loss) {
+  if (!c) return MM_EINVAL;
+  if (!src_ids || !tgt_ids || !lengths) return fail(c, MM_EINVAL, "null batch pointer");
+  if (task < 0 || task >= (int)c->routes.size()) return fail(c, MM_EINVAL, "unknown task %d", task);
+  if (ids_mem != MM_HOST && ids_mem != MM_DEVICE) return fail(c, MM_EINVAL, "ids_mem must be MM_HOST or MM_DEVICE");
+  if (B < 1 || S_max < 1 || T_max < 2) return fail(c, MM_EINVAL, "empty batch");
+  if (S_max > c->cfg.max_len || T_max - 1 > c->cfg.max_len)
+    return fail(c, MM_ERANGE, "padded width exceeds max_len %d", c->cfg.max_len);
+  int64_t S = 0, U = 0;
+  for (int b = 0; b < B; ++b) {
+    const int s = lengths[2 * b], t = lengths[2 * b + 1];
+    if (s < 1 || s > S_max || t < 2 || t > T_max)
+      return fail(c, MM_ERANGE, "sentence %d has lengths (%d, %d) outside [1,%d] x [2,%d]", b, s, t, S_max, T_max);
+    S += s; U += t - 1;
+  }
+  if (S > c->cfg.max_batch_tokens || U > c->cfg.max_batch_tokens)
+    return fail(c, MM_ERANGE, "batch holds %lld source / %lld target tokens, limit %d", (long long)S, (long long)U, c->cfg.max_batch_tokens);
+  if (ids_mem == MM_HOST) {
+    const int V = c->cfg.vocab;
+    for (int b = 0; b < B; ++b) {
+      const int s = lengths[2 * b], t = lengths[2 * b + 1];
+      for (int i = 0; i < S_max; ++i) {
+        const int id = src_ids[(size_t)b * S_max + i];
+        if (i < s ? (id < 0 || id >= V) : id != 0)
+          return fail(c, MM_ERANGE, "source id %d at sentence %d position %d", id, b, i);
+      }
+      for (int i = 0; i < T_max; ++i) {
+        const int id = tgt_ids[(size_t)b * T_max + i];
+        if (i < t ? (id < 0 || id >= V) : id != 0)
+          return fail(c, MM_ERANGE, "target id %d at sentence %d position %d", id, b, i);
+      }
+    }
+  }
+  if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context cannot compute");
+  resolve_pending(c);  // settle the previous step's bookkeeping (no-op when it was read already)
+
+  // stage lengths and prefix sums (and host ids) through pinned memory
+  const size_t n_meta = (size_t)2 * B + 2 * ((size_t)B + 1);
+  const size_t n_ids = ids_mem == MM_HOST ? (size_t)B * S_max + (size_t)B * T_max : 0;
+  HIP_TRY(c, hipEventSynchronize(c->ev_stage));
+  mm_status s = ensure_stage(c, n_meta + n_ids);
+  if (s != MM_OK) return s;
+  int32_t* st_lens = c->stage;
+  int32_t* st_cu_s = st_lens + 2 * B;
+  int32_t* st_cu_u = st_cu_s + B + 1;
+  int32_t* st_ids = st_cu_u + B + 1;
+  memcpy(st_lens, lengths, (size_t)2 * B * 4);
+  st_cu_s[0] = 0; st_cu_u[0] = 0;
+  for (int b = 0; b < B; ++b) {
+    st_cu_s[b + 1] = st_cu_s[b] + lengths[2 * b];
+    st_cu_u[b + 1] = st_cu_u[b] + lengths[2 * b + 1] - 1;
+  }
+  const int32_t* src_dev = src_ids;
+  const int32_t* tgt_dev = tgt_ids;
+  if (ids_mem == MM_HOST) {
+    s = ensure_ids_dev(c, n_ids);
+    if (s != MM_OK) return s;
+    memcpy(st_ids, src_ids, (size_t)B * S_max * 4);
+    memcpy(st_ids + (size_t)B * S_max, tgt_ids, (size_t)B * T_max * 4);
+    HIP_TRY(c, hipMemcpyAsync(c->ids_dev, st_ids, n_ids * 4, hipMemcpyHostToDevice, c->st));
+    src_dev = c->ids_dev;
+    tgt_dev = c->ids_dev + (size_t)B * S_max;
+  }
+  c->B = B; c->S_max = S_max; c->T_max = T_max; c->S = (int)S; c->U = (int)U;
+  const Route& rt = c->routes[task];
+  run_step(c, rt, true, lengths);
+  s = ensure_ws(c, c->ws.high);
+  if (s != MM_OK) return s;
+
+  HIP_TRY(c, hipMemcpyAsync(c->lens, st_lens, (size_t)2 * B * 4, hipMemcpyHostToDevice, c->st));
+  HIP_TRY(c, hipMemcpyAsync(c->cu_s, st_cu_s, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, c->st));
+  HIP_TRY(c, hipMemcpyAsync(c->cu_u, st_cu_u, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, c->st));
+  HIP_TRY(c, hipEventRecord(c->ev_stage, c->st));
+  launch_fill_i32(c->st, c->flag, 1, 0);
+  launch_pack_ids(c->st, src_dev, tgt_dev, c->lens, c->cu_s, c->cu_u, B, S_max, T_max, c->cfg.vocab, c->src_tok,
+                  c->src_pos, c->dec_tok, c->dec_pos, c->label, c->flag);
+  run_step(c, rt, false, lengths);
+  HIP_TRY(c, hipGetLastError());
+  HIP_TRY(c, hipMemcpyAsync(&c->result_host[0], c->loss_dev, 4, hipMemcpyDeviceToHost, c->st));
+  HIP_TRY(c, hipMemcpyAsync(&c->result_host[1], c->flag, 4, hipMemcpyDeviceToHost, c->st));
+  HIP_TRY(c, hipEventRecord(c->ev_done, c->st));
+  for (int j : rt.ids) c->mods[j].touched += 1;
+  c->pending = true; c->pending_task = task; c->pending_counted = true;
+  if (c->prof && c->prof_recs.size() > 8192) collect_profile(c);
+  if (out_loss) {
+    s = resolve_pending(c);
+    *out_loss = c->last_loss;
+    return s;
+  }
+  return MM_OK;
+}
+
+mm_status mm_last_loss(mm_ctx* c, float* out_loss) {
+  if (!c) return MM_EINVAL;
+  if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context cannot compute");
+  mm_status s = resolve_pending(c);
+  if (out_loss) *out_loss = c->last_loss;
+  return s;
+}
+
+mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float lr) {
+  if (!c) return MM_EINVAL;
+  if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context cannot compute");
+  std::vector<int> ids;
+  if (module_ids) {
+    if (n < 0) return fail(c, MM_EINVAL, "negative count");
+    for (int i = 0; i < n; ++i) {
+      if (!valid_module(c, module_ids[i])) return fail(c, MM_EINVAL, "unknown module id %d", module_ids[i]);
+      bool dup = false;
+      for (int j : ids) dup |= (j == module_ids[i]);
+      if (!dup) ids.push_back(module_ids[i]);
+    }
+  } else {
+    for (int j = 0; j < (int)c->mods.size(); ++j) ids.push_back(j);
+  }
+  std::vector<int> use;
+  for (int j : ids) if (c->mods[j].touched > 0) use.push_back(j);
+  if (use.empty()) return MM_OK;
+  if ((int)use.size() > c->seg_cap) {
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    if (c->seg_host) hipHostFree(c->seg_host);
+    if (c->seg_dev) hipFree(c->seg_dev);
+    c->seg_host = nullptr; c->seg_dev = nullptr; c->seg_cap = 0;
+    const int cap = (int)use.size() + 32;
+    HIP_TRY(c, hipHostMalloc((void**)&c->seg_host, cap * sizeof(AdamSegment), hipHostMallocDefault));
+    HIP_TRY(c, hipMalloc((void**)&c->seg_dev, cap * sizeof(AdamSegment)));
+    c->seg_cap = cap;
+  }
+  HIP_TRY(c, hipEventSynchronize(c->ev_seg));  // previous upload of the table has left the pinned buffer
+  int chunks = 0;
+  int64_t total = 0;
+  for (size_t i = 0; i < use.size(); ++i) {
+    Module& m = c->mods[use[i]];
+    m.t += 1;
+    AdamSegment& sg = c->seg_host[i];
+    sg.theta = m.theta; sg.m = m.m; sg.v = m.v; sg.g = m.g; sg.w16 = m.w16; sg.len = m.P;
+    sg.inv_n = 1.0f / (float)m.touched;
+    sg.bc1 = (float)(1.0 - std::pow((double)c->cfg.adam_beta1, (double)m.t));
+    sg.bc2 = (float)(1.0 - std::pow((double)c->cfg.adam_beta2, (double)m.t));
+    sg.first_chunk = chunks; sg.pad = 0;
+    chunks += (int)((m.P + ADAM_CHUNK - 1) / ADAM_CHUNK);
+    total += m.P;
+    m.touched = 0;
+  }
+  c->pending_counted = false;  // the step's uses have been consumed
+  HIP_TRY(c, hipMemcpyAsync(c->seg_dev, c->seg_host, use.size() * sizeof(AdamSegment), hipMemcpyHostToDevice, c->st));
+  HIP_TRY(c, hipEventRecord(c->ev_seg, c->st));
+  Run run{c, false};
+  run.begin(MM_K_ADAM, work_bytes_adam(c, total));
+  launch_adam(c->st, c->seg_dev, (int)use.size(), chunks, lr, c->cfg.adam_beta1, c->cfg.adam_beta2, c->cfg.adam_eps);
+  run.end();
+  HIP_TRY(c, hipGetLastError());
+  return MM_OK;
+}
+
+// ---- introspection -----------------------------------------------------------------------------
+mm_status mm_num_modules(mm_ctx* c, int32_t* out_n) {
+  if (!c || !out_n) return MM_EINVAL;
+  *out_n = (int32_t)c->mods.size();
+  return MM_OK;
+}
+
+mm_status mm_get_route(mm_ctx* c, int32_t task, int32_t* ids, int32_t* n) {
+  if (!c || !n) return MM_EINVAL;
+  if (task < 0 || task >= (int)c->routes.size()) return fail(c, MM_EINVAL, "unknown task %d", task);
+  const auto& r = c->routes[task].ids;
+  if (ids) {
+    if (*n < (int)r.size()) return fail(c, MM_EINVAL, "capacity %d < %zu", *n, r.size());
+    for (size_t i = 0; i < r.size(); ++i) ids[i] = r[i];
+  }
+  *n = (int32_t)r.size();
+  return MM_OK;
+}
+
+mm_status mm_get_touched(mm_ctx* c, int32_t* counts, int32_t capacity) {
+  if (!c || !counts) return MM_EINVAL;
+  if (capacity < (int)c->mods.size()) return fail(c, MM_EINVAL, "capacity %d < %zu", capacity, c->mods.size());
+  if (!c->plan_only) resolve_pending(c);
+  for (size_t j = 0; j < c->mods.size(); ++j) counts[j] = c->mods[j].touched;
+  return MM_OK;
+}
+
+mm_status mm_get_layout(mm_ctx* c, int32_t module, int64_t* offsets, int32_t* rows, int32_t* cols, int32_t* roles,
+                        int32_t* n_tensors, int64_t* bucket_len) {
+  if (!c || !n_tensors) return MM_EINVAL;
+  if (!valid_module(c, module)) return fail(c, MM_EINVAL, "unknown module id %d", module);
+  const Module& m = c->mods[module];
+  const int nt = (int)m.tensors.size();
+  if (offsets || rows || cols || roles) {
+    if (*n_tensors < nt) return fail(c, MM_EINVAL, "capacity %d < %d tensors", *n_tensors, nt);
+    for (int i = 0; i < nt; ++i) {
+      if (offsets) offsets[i] = m.tensors[i].off;
+      if (rows) rows[i] = m.tensors[i].rows;
+      if (cols) cols[i] = m.tensors[i].cols;
+      if (roles) roles[i] = m.tensors[i].role;
+    }
+  }
+  *n_tensors = nt;
+  if (bucket_len) *bucket_len = m.P;
+  return MM_OK;
+}
+
+static mm_status copy_out(mm_ctx* c, const float* dev, float* dst, int64_t n) {
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  HIP_TRY(c, hipMemcpy(dst, dev, (size_t)n * 4, hipMemcpyDeviceToHost));
+  return MM_OK;
+}
+
+mm_status mm_get_params(mm_ctx* c, int32_t module, float* dst, int64_t n) {
+  mm_status s = check_module(c, module, n);
+  if (s != MM_OK) return s;
+  if (!dst) return fail(c, MM_EINVAL, "null destination");
+  return copy_out(c, c->mods[module].theta, dst, n);
+}
+
+mm_status mm_get_grads(mm_ctx* c, int32_t module, float* dst, int64_t n) {
+  mm_status s = check_module(c, module, n);
+  if (s != MM_OK) return s;
+  if (!dst) return fail(c, MM_EINVAL, "null destination");
+  return copy_out(c, c->mods[module].g, dst, n);
+}
+
+mm_status mm_get_adam(mm_ctx* c, int32_t module, float* m, float* v, int64_t n, int64_t* t_j) {
+  mm_status s = check_module(c, module, n);
+  if (s != MM_OK) return s;
+  if (m) { s = copy_out(c, c->mods[module].m, m, n); if (s != MM_OK) return s; }
+  if (v) { s = copy_out(c, c->mods[module].v, v, n); if (s != MM_OK) return s; }
+  if (t_j) *t_j = c->mods[module].t;
+  return MM_OK;
+}
+
+mm_status mm_get_working(mm_ctx* c, int32_t module, float* dst, int64_t n) {
+  mm_status s = check_module(c, module, n);
+  if (s != MM_OK) return s;
+  if (!dst) return fail(c, MM_EINVAL, "null destination");
+  Module& m = c->mods[module];
+  if (c->dt != BF16) return copy_out(c, m.theta, dst, n);
+  std::vector<bf16_t> tmp((size_t)n);
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  HIP_TRY(c, hipMemcpy(tmp.data(), m.w16, (size_t)n * 2, hipMemcpyDeviceToHost));
+  for (int64_t i = 0; i < n; ++i) dst[i] = bf16_to_f32(tmp[(size_t)i]);
+  return MM_OK;
+}
+
+mm_status mm_set_params(mm_ctx* c, int32_t module, const float* src, int64_t n) {
+  mm_status s = check_module(c, module, n);
+  if (s != MM_OK) return s;
+  if (!src) return fail(c, MM_EINVAL, "null source");
+  Module& m = c->mods[module];
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  HIP_TRY(c, hipMemcpy(m.theta, src, (size_t)n * 4, hipMemcpyHostToDevice));
+  if (c->dt == BF16) {
+    launch_to_bf16(c->st, m.theta, m.w16, m.P);
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+  }
+  return MM_OK;
+}
+
+mm_status mm_set_grads(mm_ctx* c, int32_t module, const float* src, int64_t n, int32_t n_uses) {
+  mm_status s = check_module(c, module, n);
+  if (s != MM_OK) return s;
+  if (!src || n_uses < 0) return fail(c, MM_EINVAL, "null source or negative use count");
+  resolve_pending(c);
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  HIP_TRY(c, hipMemcpy(c->mods[module].g, src, (size_t)n * 4, hipMemcpyHostToDevice));
+  c->mods[module].touched = n_uses;
+  return MM_OK;
+}
+
+mm_status mm_debug_dump(mm_ctx* c, int32_t what, void* dst, int64_t* nbytes) {
+  if (!c || !nbytes) return MM_EINVAL;
+  if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context holds no device memory");
+  if (c->B == 0) return fail(c, MM_ESTATE, "no step has run yet");
+  const int B = c->B, Lu = c->T_max - 1, Ls = c->S_max;
+  const void* src = nullptr;
+  int64_t need = 0;
+  bool mask = false;
+  int mode = 0, Lq = 0, Lk = 0;
+  const int32_t *cu_q = nullptr, *cu_k = nullptr;
+  switch (what) {
+    case MM_DUMP_CU_SRC: src = c->cu_s; need = ((int64_t)B + 1) * 4; break;
+    case MM_DUMP_CU_DEC: src = c->cu_u; need = ((int64_t)B + 1) * 4; break;
+    case MM_DUMP_SRC_TOK: src = c->src_tok; need = (int64_t)c->S * 4; break;
+    case MM_DUMP_SRC_POS: src = c->src_pos; need = (int64_t)c->S * 4; break;
+    case MM_DUMP_DEC_TOK: src = c->dec_tok; need = (int64_t)c->U * 4; break;
+    case MM_DUMP_DEC_POS: src = c->dec_pos; need = (int64_t)c->U * 4; break;
+    case MM_DUMP_LABEL: src = c->label; need = (int64_t)c->U * 4; break;
+    case MM_DUMP_MASK_ENC: mask = true; mode = 0; Lq = Ls; Lk = Ls; cu_q = c->cu_s; cu_k = c->cu_s; break;
+    case MM_DUMP_MASK_DEC: mask = true; mode = 1; Lq = Lu; Lk = Lu; cu_q = c->cu_u; cu_k = c->cu_u; break;
+    case MM_DUMP_MASK_CROSS: mask = true; mode = 0; Lq = Lu; Lk = Ls; cu_q = c->cu_u; cu_k = c->cu_s; break;
+    default: return fail(c, MM_EINVAL, "unknown dump selector %d", what);
+  }
+  if (mask) need = (int64_t)B * Lq * Lk;
+  if (!dst) { *nbytes = need; return MM_OK; }
+  if (*nbytes < need) return fail(c, MM_EINVAL, "capacity %lld < %lld bytes", (long long)*nbytes, (long long)need);
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  if (mask) {
+    uint8_t* tmp = nullptr;
+    HIP_TRY(c, hipMalloc((void**)&tmp, (size_t)need));
+    launch_mask_dump(c->st, cu_q, cu_k, B, Lq, Lk, mode, tmp);
+    hipError_t e = hipStreamSynchronize(c->st);
+    if (e == hipSuccess) e = hipMemcpy(dst, tmp, (size_t)need, hipMemcpyDeviceToHost);
+    hipFree(tmp);
+    HIP_TRY(c, e);
+  } else {
+    HIP_TRY(c, hipMemcpy(dst, src, (size_t)need, hipMemcpyDeviceToHost));
+  }
+  *nbytes = need;
+  return MM_OK;
+}
+
+mm_status mm_profile(mm_ctx* c, int32_t enable) {
+  if (!c) return MM_EINVAL;
+  if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context cannot compute");
+  mm_status s = collect_profile(c);
+  if (s != MM_OK) return s;
+  if (enable) {
+    for (int i = 0; i < MM_K_COUNT; ++i) { c->prof_ms[i] = 0; c->prof_n[i] = 0; c->prof_work[i] = 0; }
+  }
+  c->prof = enable != 0;
+  return MM_OK;
+}
+
+mm_status mm_profile_read(mm_ctx* c, double* ms, int64_t* launches, double* work) {
+  if (!c) return MM_EINVAL;
+  if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context cannot compute");
+  mm_status s = collect_profile(c);
+  if (s != MM_OK) return s;
+  for (int i = 0; i < MM_K_COUNT; ++i) {
+    if (ms) ms[i] = c->prof_ms[i];
+    if (launches) launches[i] = c->prof_n[i];
+    if (work) work[i] = c->prof_work[i];
+  }
+  return MM_OK;
+}
+
+const char* mm_last_error(mm_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+}  // extern "C"

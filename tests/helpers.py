@@ -20,10 +20,11 @@ from oracle.mammoth_oracle import Oracle, build_from_setup
 
 
 def tiny_setup(d=16, H=2, F_=32, V=56, n_lang=2, adapters=True, split_enc=True,
-               enc_layers=(1, 1), dec_layers=2, max_len=12, seed=7) -> Setup:
+               enc_layers=(1, 1), dec_layers=2, max_len=12, seed=7, adapter_dim=8,
+               dtype="f32") -> Setup:
     """Small model exercising every module kind: split encoder stack (language-specific
     position 0, shared position 1), language-specific decoders and optional adapters."""
-    shape = ModelShape(d_model=d, n_heads=H, d_ff=F_, vocab=V, dtype="f32", max_len=max_len,
+    shape = ModelShape(d_model=d, n_heads=H, d_ff=F_, vocab=V, dtype=dtype, max_len=max_len,
                        batch_tokens=64)
     mods, ix = [], {}
 
@@ -41,8 +42,8 @@ def tiny_setup(d=16, H=2, F_=32, V=56, n_lang=2, adapters=True, split_enc=True,
         add(("dec", l), ModuleSpec("dec", f"lang{l}", 0, dec_layers, True))
         add(("gen", l), ModuleSpec("gen", f"lang{l}"))
         if adapters:
-            add(("ad_enc", l), ModuleSpec("adapter", f"lang{l}", 0, sum(enc_layers), False, 8, "enc"))
-            add(("ad_dec", l), ModuleSpec("adapter", f"lang{l}", 0, dec_layers, False, 8, "dec"))
+            add(("ad_enc", l), ModuleSpec("adapter", f"lang{l}", 0, sum(enc_layers), False, adapter_dim, "enc"))
+            add(("ad_dec", l), ModuleSpec("adapter", f"lang{l}", 0, dec_layers, False, adapter_dim, "dec"))
     if split_enc:
         add(("enc1", 0), ModuleSpec("enc", "full", 1, enc_layers[1], True))
     tasks = []

@@ -1,0 +1,136 @@
+"""Host-side logic of the library, exercised without a GPU through plan-only contexts: exported
+symbols, bucket layouts, route rules (paper section 3.2), batch validation, error codes."""
+import ctypes
+import re
+import os
+
+import numpy as np
+import pytest
+
+import mm_synth
+from oracle.mammoth_oracle import Oracle, module_layout
+from paper_2403_07544_amd import (Context, MMError, context_from_setup, load_library, EXPORTS, MM_EINVAL,
+                                  MM_ERANGE, MM_ESTATE)
+from tests.helpers import tiny_batch, tiny_setup
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "mammoth_hip.h")).read()
+    declared = set(re.findall(r"\b(mm_[a-z_]+)\s*\(", header))
+    assert declared == set(EXPORTS)
+    lib = load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
+def test_bucket_layout_matches_oracle_bit_exactly(index):
+    setup = mm_synth.build_setup(index)
+    ctx = context_from_setup(setup, plan_only=True)
+    sh = setup.shape
+    for j, ms in enumerate(setup.modules):
+        specs, total = module_layout(ms.kind, sh.d_model, sh.d_ff, sh.vocab, ms.n_layers, ms.owns_final_norm,
+                                     ms.adapter_dim)
+        table, got_total = ctx.mm_get_layout(j)
+        assert got_total == total
+        assert [(r, o, rows * cols) for r, o, rows, cols in table] == [(s.role, s.offset, s.size) for s in specs]
+        for (r, o, rows, cols), s in zip(table, specs):
+            assert (rows, cols) == (s.shape if len(s.shape) == 2 else (1, s.shape[0]))
+    for t, (_, ids) in enumerate(setup.tasks):
+        assert ctx.mm_get_route(t) == ids
+    assert ctx.mm_get_touched().tolist() == [0] * len(setup.modules)
+
+
+def _ctx():
+    return Context(32, 2, 64, 56, "f32", max_len=24, max_batch_tokens=256, plan_only=True)
+
+
+def test_route_rules_match_oracle():
+    ctx = _ctx()
+    orc = Oracle(32, 2, 64, 56, 24)
+    mods = [("src_emb", "s", 0, 0, False), ("enc", "x", 0, 1, False), ("enc", "y", 1, 1, True),
+            ("enc", "y", 0, 1, False), ("enc", "x", 1, 1, True), ("tgt_emb", "t", 0, 0, False),
+            ("dec", "t", 0, 2, True), ("gen", "t", 0, 0, False), ("enc", "whole", 0, 2, True)]
+    for kind, name, pos, nl, fin in mods:
+        a = ctx.mm_register_module(kind, name, pos, nl, fin)
+        b = orc.register_module(kind, name, pos, nl, fin)
+        assert a == b
+    ad_ok = ctx.mm_register_module("adapter", "a", 0, 2, False, 16, "enc")
+    ad_short = ctx.mm_register_module("adapter", "a", 0, 1, False, 16, "enc")
+    orc.register_module("adapter", "a", 0, 2, False, 16, "enc")
+    orc.register_module("adapter", "a", 0, 1, False, 16, "enc")
+    good = [[0, 1, 2, 5, 6, 7, ad_ok], [0, 3, 4, 5, 6, 7, ad_ok]]
+    bad = [[0, 2, 1, 5, 6, 7, ad_ok],      # positions swapped
+           [0, 1, 2, 5, 6, 7],             # fewer modules than the first task
+           [1, 0, 2, 5, 6, 7, ad_ok],      # kinds out of order
+           [0, 1, 3, 5, 6, 7, ad_ok],      # stack not closed by its last position
+           [0, 1, 2, 5, 6, 99, ad_ok],     # unknown id
+           [0, 1, 2, 5, 6, 7, ad_short],   # adapter does not cover the stack
+           [0, 1, 2, 5, 6, 7, 7]]          # duplicate
+    for ids in good:
+        assert ctx.mm_route_task(ids) == orc.route_task(ids)
+    for ids in bad:
+        with pytest.raises(MMError) as ei:
+            ctx.mm_route_task(ids)
+        assert ei.value.status == MM_EINVAL
+        with pytest.raises(ValueError):
+            orc.route_task(ids)
+    assert ctx.mm_get_route(0) == good[0] and ctx.mm_get_route(1) == good[1]
+    with pytest.raises(MMError):
+        ctx.mm_get_route(2)
+
+
+def test_batch_validation_and_state_errors():
+    setup = tiny_setup(d=32, H=2, F_=64, V=56, adapter_dim=16, max_len=24)
+    ctx = context_from_setup(setup, plan_only=True, max_batch_tokens=64)
+    batch = tiny_batch(setup)
+
+    def status(**kw):
+        args = dict(task=0, src=batch.src_ids, tgt=batch.tgt_ids, lengths=batch.lengths)
+        args.update(kw)
+        with pytest.raises(MMError) as ei:
+            ctx.mm_train_step(args["task"], args["src"], args["tgt"], args["lengths"])
+        return ei.value.status
+
+    assert status() == MM_ESTATE                       # valid batch, but the context cannot compute
+    assert status(task=7) == MM_EINVAL
+    src = batch.src_ids.copy(); src[0, 0] = 56
+    assert status(src=src) == MM_ERANGE                # id >= vocab
+    tgt = batch.tgt_ids.copy(); tgt[0, -1] = 5
+    assert status(tgt=tgt) == MM_ERANGE                # non-pad after the end
+    ln = batch.lengths.copy(); ln[1, 0] = 0
+    assert status(lengths=ln) == MM_ERANGE
+    ln = batch.lengths.copy(); ln[1, 1] = 1
+    assert status(lengths=ln) == MM_ERANGE
+    wide = np.pad(batch.src_ids, ((0, 0), (0, 30)))
+    assert status(src=wide) == MM_ERANGE               # wider than max_len
+    big = mm_synth.data.small_batch(56, [(20, 20)] * 4, 1)
+    assert status(src=big.src_ids, tgt=big.tgt_ids, lengths=big.lengths) == MM_ERANGE  # > max_batch_tokens
+    with pytest.raises(MMError) as ei:
+        ctx.mm_apply_update(None, 1e-3)
+    assert ei.value.status == MM_ESTATE
+    with pytest.raises(MMError) as ei:
+        ctx.mm_get_params(0)
+    assert ei.value.status == MM_ESTATE
+
+
+def test_create_rejects_bad_shapes():
+    for kw in (dict(d_model=30), dict(n_heads=3), dict(vocab=57), dict(max_len=300), dict(max_batch_tokens=20000),
+               dict(d_ff=50)):
+        args = dict(d_model=32, n_heads=2, d_ff=64, vocab=56, dtype="f32", max_len=24, max_batch_tokens=256,
+                    plan_only=True)
+        args.update(kw)
+        with pytest.raises(MMError) as ei:
+            Context(**args)
+        assert ei.value.status == MM_EINVAL
+    ctx = _ctx()
+    with pytest.raises(MMError):
+        ctx.mm_register_module("adapter", "a", 0, 2, False, 10, "enc")   # bottleneck not a multiple of 16
+    with pytest.raises(MMError):
+        ctx.mm_register_module("enc", "e", 0, 0, True)                   # no layers
+    j = ctx.mm_register_module("gen", "g")
+    with pytest.raises(MMError):
+        ctx.mm_register_module("gen", "g", init=np.zeros(10, dtype=np.float32))  # wrong length
+    assert ctx.mm_get_layout(j)[1] == 32 * 56 + 64
