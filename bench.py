@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Throughput of the routed training step (mm_train_step + mm_apply_update) on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch of the chosen set-up: route,
+embedding + positions, encoder and decoder forward, generator, label-smoothed cross-entropy,
+full backward into the per-module buckets, and the Adam update of the touched modules.  Token
+ids are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_FLOPS = 2.5e15   # MI355X dense bf16 MFMA
+PEAK_F32_FLOPS = 157.3e12  # fp32 vector
+PEAK_HBM = 8.0e12
+
+
+def cpu_baseline(setup, batch, target_tokens=768):
+    """The CPU oracle (fp64 numpy, as it stands) on the first sentences of one batch."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    import mm_synth
+    from oracle.mammoth_oracle import build_from_setup
+
+    n, tok = 0, 0
+    while n < len(batch.lengths) and tok < target_tokens:
+        tok += int(batch.lengths[n, 1]) - 1
+        n += 1
+    lengths = batch.lengths[:n]
+    src = batch.src_ids[:n, :int(lengths[:, 0].max())]
+    tgt = batch.tgt_ids[:n, :int(lengths[:, 1].max())]
+    orc = build_from_setup(setup, dtype=np.float64, fill_params=mm_synth.fill_params)
+    t0 = time.perf_counter()
+    orc.train_step(0, src, tgt, lengths)
+    orc.apply_update(None, setup.shape.lr)
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": tok / dt, "unit": "target tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"fwd+bwd+Adam of the fp64 numpy oracle on the first {n} sentence pairs "
+                      f"({tok} target tokens) of one batch, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the path's cross-GPU gradient exchange is "
+              "design only); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import mm_synth
+    from paper_2403_07544_amd import context_from_setup
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    setup = mm_synth.build_setup(args.config)
+    sh = setup.shape
+    n_steps = args.warmup + args.steps
+    batches = mm_synth.make_batches(setup)
+    directions = mm_synth.sample_directions(setup, n_steps)
+    ctx = context_from_setup(setup, fill_params=mm_synth.fill_params)
+
+    # inputs resident in HBM before timing
+    dev = []
+    for k in range(n_steps):
+        b = batches[k % len(batches)]
+        dev.append((torch.tensor(b.src_ids, dtype=torch.int32, device="cuda"),
+                    torch.tensor(b.tgt_ids, dtype=torch.int32, device="cuda"), b.lengths, b))
+    torch.cuda.synchronize()
+
+    def run(lo, hi):
+        toks = 0
+        loss = 0.0
+        for k in range(lo, hi):
+            src, tgt, lengths, b = dev[k]
+            loss = ctx.mm_train_step(int(directions[k]), src, tgt, lengths)
+            ctx.mm_apply_update(None, sh.lr)
+            toks += b.n_tgt_tokens
+        return toks, loss
+
+    run(0, args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tokens, last_loss = run(args.warmup, n_steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    src_tokens = sum(dev[k][3].n_src_tokens for k in range(args.warmup, n_steps))
+
+    # per-kernel-class timing with HIP events on the library's stream, same steps again
+    ctx.mm_profile(True)
+    run(args.warmup, n_steps)
+    prof = ctx.mm_profile_read()
+    ctx.mm_profile(False)
+    g = prof["gemm"]
+    peak = PEAK_BF16_FLOPS if sh.dtype == "bf16" else PEAK_F32_FLOPS
+    achieved = g["work"] / (g["ms"] * 1e-3) if g["ms"] > 0 else 0.0
+    roofline = {"bound": "mfma" if sh.dtype == "bf16" else "alu", "kernel": "gemm (all projection, FFN, "
+                "generator, input- and weight-gradient products)", "achieved": achieved / 1e12,
+                "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "avg_launch_us": 1e3 * g["ms"] / max(1, g["launches"]), "launches_per_step": g["launches"] / args.steps}
+    classes = {}
+    for name, r in prof.items():
+        if r["launches"] == 0:
+            continue
+        rate = r["work"] / (r["ms"] * 1e-3) if r["ms"] > 0 else 0.0
+        flop_bound = name in ("gemm", "attn_fwd", "attn_bwd")
+        classes[name] = {"ms_per_step": r["ms"] / args.steps, "launches_per_step": r["launches"] / args.steps,
+                         ("tflops" if flop_bound else "gbps"): rate / (1e12 if flop_bound else 1e9),
+                         "frac_of_peak": rate / (peak if flop_bound else PEAK_HBM)}
+
+    out = {
+        "metric": "training tokens/s per MI355X (fwd+bwd+update), modular Transformer-base",
+        "value": tokens / elapsed, "unit": "target tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}]: {setup.title}; d={sh.d_model} heads={sh.n_heads} "
+                               f"ffn={sh.d_ff} vocab={sh.vocab}, {len(setup.modules)} modules resident, "
+                               f"{len(setup.tasks)} task(s), ~{sh.batch_tokens}-token length-bucketed batches",
+                   "target_tokens_per_step": tokens / args.steps, "source_tokens_per_step": src_tokens / args.steps,
+                   "src_plus_tgt_tokens_per_s": (tokens + src_tokens) / elapsed, "last_loss": last_loss},
+        "roofline": roofline,
+        "kernel_classes": classes,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(setup, dev[args.warmup][3])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

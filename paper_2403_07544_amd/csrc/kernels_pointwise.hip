@@ -452,6 +452,9 @@ __global__ void __launch_bounds__(1024) sum_scaled_kernel(const float* __restric
 // ----------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict__ segs, int n_segs,
                                                    float lr, float beta1, float beta2, float eps) {
+  // every product and sum below is rounded on its own (no fused multiply-add), so the update is
+  // the same fp32 operation sequence as the textbook formulas written one operation at a time
+#pragma clang fp contract(off)
   // find the segment of this chunk (n_segs is small)
   int lo = 0, hi = n_segs - 1;
   const int chunk = blockIdx.x;
@@ -471,7 +474,7 @@ __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict
     float* gp = &g.x; float* tp = &th.x; float* mp = &m.x; float* vp = &v.x;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float ge = gp[e] * sg.inv_n;
+      const float ge = gp[e] / sg.n_uses;
       mp[e] = beta1 * mp[e] + omb1 * ge;
       vp[e] = beta2 * vp[e] + omb2 * ge * ge;
       const float mh = mp[e] / sg.bc1, vh = vp[e] / sg.bc2;

@@ -129,7 +129,7 @@ void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float
 struct AdamSegment {
   float* theta; float* m; float* v; float* g; bf16_t* w16;  // w16 null in fp32 contexts
   int64_t len;                                               // multiple of 64
-  float inv_n, bc1, bc2;                                     // 1/n_j, 1-beta1^t, 1-beta2^t
+  float n_uses, bc1, bc2;                                    // n_j, 1-beta1^t, 1-beta2^t
   int32_t first_chunk;                                       // running chunk index of this segment
   int32_t pad;
 };

@@ -989,7 +989,7 @@ mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float
     m.t += 1;
     AdamSegment& sg = c->seg_host[i];
     sg.theta = m.theta; sg.m = m.m; sg.v = m.v; sg.g = m.g; sg.w16 = m.w16; sg.len = m.P;
-    sg.inv_n = 1.0f / (float)m.touched;
+    sg.n_uses = (float)m.touched;
     sg.bc1 = (float)(1.0 - std::pow((double)c->cfg.adam_beta1, (double)m.t));
     sg.bc2 = (float)(1.0 - std::pow((double)c->cfg.adam_beta2, (double)m.t));
     sg.first_chunk = chunks; sg.pad = 0;
