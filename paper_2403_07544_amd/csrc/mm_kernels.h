@@ -55,6 +55,8 @@ struct GemmParams {
   int out_f32;            // 1: C is fp32; 0: C has the working dtype
 };
 void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p);
+// Same contract, always the plain FMA kernel (cross-check of the MFMA path).
+void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p);
 
 // ---------------------------------------------------------------------------------------------
 // token bookkeeping
