@@ -227,6 +227,191 @@ __global__ void __launch_bounds__(256) attn_bwd_kernel(const AttnParams p) {
   }
 }
 
+
+// =================================================================================================
+// bf16 MFMA attention for head size 64.
+//
+// A wavefront owns 32 queries and keeps the whole score row of each in registers, so the softmax
+// is the plain one (row maximum, exponentials, one division), not an online rescaling.  Scores
+// are computed transposed, S^T = K Q^T (keys x queries): in the 32x32 accumulator layout a lane
+// then holds, for ITS query (lane % 32), 16 of every 32 keys; the other 16 sit in lane ^ 32.  Row
+// statistics are a register reduction plus one exchange with lane ^ 32.  The probabilities are
+// already laid out as the B operand of O^T = V^T P^T: accumulator registers 8s..8s+7 of a key
+// tile are the eight k-slots of MFMA step s.  Their key order within a block of 16 is
+// 0-3, 8-11 (lanes 0-31) and 4-7, 12-15 (lanes 32-63); the transposed V tile in LDS stores keys
+// in that same order, so no cross-lane shuffle is needed between the two products.
+// =================================================================================================
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+__device__ __forceinline__ int swz64(int row) { return ((row >> 1) & 7) ^ ((row >> 4) & 3); }
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+// natural tile: [rows][64] bf16, 128-byte rows, 16-byte chunk c of row r in slot c ^ swz64(r)
+__device__ __forceinline__ void load_natural(unsigned char* lds, const bf16_t* g, int64_t ld, int row0, int len,
+                                             int rows_pad, int tid) {
+  for (int q = tid; q < rows_pad * 8; q += 256) {
+    const int row = q >> 3, c = q & 7;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (row < len) v = *reinterpret_cast<const uint4*>(g + (int64_t)(row0 + row) * ld + c * 8);
+    *reinterpret_cast<uint4*>(lds + row * 128 + ((c ^ swz64(row)) << 4)) = v;
+  }
+}
+// transposed tile: [64 columns][rows_pad + 8] bf16; within each block of 16 source rows the four
+// row-quads are stored in the order 0,2,1,3 (the k-slot order described above)
+__device__ __forceinline__ void load_transposed(unsigned char* lds, const bf16_t* g, int64_t ld, int row0, int len,
+                                                int rows_pad, int tid) {
+  const int stride = (rows_pad + 8) * 2;
+  for (int q = tid; q < (rows_pad >> 2) * 8; q += 256) {
+    const int cg = q & 7, tq = q >> 3;
+    uint4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = tq * 4 + j;
+      v[j] = make_uint4(0, 0, 0, 0);
+      if (row < len) v[j] = *reinterpret_cast<const uint4*>(g + (int64_t)(row0 + row) * ld + cg * 8);
+    }
+    const int qd = tq & 3;
+    const int pos = (tq >> 2) * 16 + (((qd & 1) << 1) | (qd >> 1)) * 4;
+    const uint32_t* w0 = &v[0].x; const uint32_t* w1 = &v[1].x; const uint32_t* w2 = &v[2].x; const uint32_t* w3 = &v[3].x;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      uint2 o;
+      if (e & 1) {
+        o.x = (w0[e >> 1] >> 16) | (w1[e >> 1] & 0xffff0000u);
+        o.y = (w2[e >> 1] >> 16) | (w3[e >> 1] & 0xffff0000u);
+      } else {
+        o.x = (w0[e >> 1] & 0xffffu) | (w1[e >> 1] << 16);
+        o.y = (w2[e >> 1] & 0xffffu) | (w3[e >> 1] << 16);
+      }
+      *reinterpret_cast<uint2*>(lds + (cg * 8 + e) * stride + pos * 2) = o;
+    }
+  }
+}
+__device__ __forceinline__ bf16x8_t frag_natural(const unsigned char* lds, int row, int chunk) {
+  return *reinterpret_cast<const bf16x8_t*>(lds + row * 128 + ((chunk ^ swz64(row)) << 4));
+}
+__device__ __forceinline__ bf16x8_t frag_transposed(const unsigned char* lds, int stride, int col, int pos) {
+  return *reinterpret_cast<const bf16x8_t*>(lds + col * stride + pos * 2);
+}
+__device__ __forceinline__ bf16x8_t frag_global(const bf16_t* g) {
+  return *reinterpret_cast<const bf16x8_t*>(g);
+}
+__device__ __forceinline__ bf16x8_t frag_from_regs(const float* v) {
+  union { uint32_t u[4]; bf16x8_t f; } c;
+  c.u[0] = pack_bf16(v[0], v[1]); c.u[1] = pack_bf16(v[2], v[3]);
+  c.u[2] = pack_bf16(v[4], v[5]); c.u[3] = pack_bf16(v[6], v[7]);
+  return c.f;
+}
+
+template <int NKT>
+__global__ void __launch_bounds__(256) attn_fwd_mfma_kernel(const AttnParams p) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int b = blockIdx.x / p.H, h = blockIdx.x % p.H;
+  const int q0 = p.cu_q[b], lq = p.cu_q[b + 1] - q0;
+  const int k0 = p.cu_k[b], lk = p.cu_k[b + 1] - k0;
+  const int nkt = (lk + 31) >> 5, Lp = nkt * 32;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lcol = lane & 31, hh = lane >> 5;
+  unsigned char* Kn = smem_raw;
+  unsigned char* Vt = Kn + Lp * 128;
+  const int vstride = (Lp + 8) * 2;
+  const bf16_t* qg = (const bf16_t*)p.q + h * 64;
+  load_natural(Kn, (const bf16_t*)p.k + h * 64, p.ldk, k0, lk, Lp, tid);
+  load_transposed(Vt, (const bf16_t*)p.v + h * 64, p.ldv, k0, lk, Lp, tid);
+  __syncthreads();
+  const float scale = 0.125f;  // 1 / sqrt(64)
+  const int nqt = (lq + 31) >> 5;
+  for (int qt = wave; qt < nqt; qt += 4) {
+    const int ql = qt * 32 + lcol;
+    const bool valid_q = ql < lq;
+    const int64_t grow = q0 + (valid_q ? ql : lq - 1);
+    bf16x8_t qf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) qf[s] = frag_global(qg + grow * p.ldq + (2 * s + hh) * 8);
+    const int kt_end = p.causal ? min(nkt, qt + 1) : nkt;
+    f32x16_t sc[NKT];
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sc[kt][r] = 0.f;
+      if (kt < kt_end) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Kn, kt * 32 + lcol, 2 * s + hh), qf[s], sc[kt], 0, 0, 0);
+      }
+    }
+    // softmax over keys: registers, then the other half of the keys in lane ^ 32
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt) {
+      if (kt < kt_end) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          const bool ok = !attn_blocked(ql, key, lk, p.causal);
+          sc[kt][r] = ok ? sc[kt][r] * scale : -INFINITY;
+          mx = fmaxf(mx, sc[kt][r]);
+        }
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+    float sum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt) {
+      if (kt < kt_end) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float e = (sc[kt][r] == -INFINITY) ? 0.f : __expf(sc[kt][r] - mx);
+          sc[kt][r] = e;
+          sum += e;
+        }
+      }
+    }
+    sum += __shfl_xor(sum, 32, WAVE);
+    const float inv = 1.0f / sum;
+    if (valid_q && hh == 0) p.lse[(int64_t)h * p.rows_q + q0 + ql] = mx + __logf(sum);
+    f32x16_t oc[2];
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oc[ct][r] = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt) {
+      if (kt < kt_end) {
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          float pv[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pv[e] = sc[kt][8 * s2 + e] * inv;
+          const bf16x8_t pf = frag_from_regs(pv);
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct)
+            oc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_transposed(Vt, vstride, ct * 32 + lcol, kt * 32 + s2 * 16 + hh * 8), pf, oc[ct], 0, 0, 0);
+        }
+      }
+    }
+    if (valid_q) {
+      bf16_t* og = (bf16_t*)p.o + grow * p.ldo + h * 64;
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          uint2 o;
+          o.x = pack_bf16(oc[ct][4 * g4 + 0], oc[ct][4 * g4 + 1]);
+          o.y = pack_bf16(oc[ct][4 * g4 + 2], oc[ct][4 * g4 + 3]);
+          *reinterpret_cast<uint2*>(og + ct * 32 + 8 * g4 + 4 * hh) = o;
+        }
+    }
+  }
+}
+
+inline size_t mfma_fwd_lds(int max_lk) {
+  const int Lp = ((max_lk + 31) / 32) * 32;
+  return (size_t)Lp * 128 + (size_t)64 * (Lp + 8) * 2;
+}
+
 template <typename T>
 size_t lds_bytes_t(int dh, int max_lq, int max_lk, bool backward) {
   const size_t ldr = dh + row_pad<T>();
@@ -243,7 +428,23 @@ size_t attn_lds_bytes(Dtype dt, int dh, int max_lq, int max_lk, bool backward) {
                     : lds_bytes_t<float>(dh, max_lq, max_lk, backward);
 }
 
+static bool mfma_ok(Dtype dt, const AttnParams& p) {
+  return dt == BF16 && p.dh == 64 && p.max_lk <= 256 && p.max_lq <= 256 && p.ldq % 8 == 0 && p.ldk % 8 == 0 &&
+         p.ldv % 8 == 0 && p.ldo % 4 == 0;
+}
+
 void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p) {
+  if (mfma_ok(dt, p)) {
+    const size_t lds = mfma_fwd_lds(p.max_lk);
+    if (p.max_lk <= 128) {
+      hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      attn_fwd_mfma_kernel<4><<<p.B * p.H, 256, lds, st>>>(p);
+    } else {
+      hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      attn_fwd_mfma_kernel<8><<<p.B * p.H, 256, lds, st>>>(p);
+    }
+    return;
+  }
   const size_t lds = attn_lds_bytes(dt, p.dh, p.max_lq, p.max_lk, false);
   if (dt == BF16) {
     hipFuncSetAttribute((const void*)attn_fwd_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -339,15 +339,36 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(
   }
 }
 
-// dst[seg(n)] += sum_p partial[p * pstride + n]   (one thread per column, fixed order over p)
-__global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_partial, int64_t pstride,
-                                       int N, float* __restrict__ dst, int split, int64_t seg_stride) {
-  const int n = blockIdx.x * blockDim.x + threadIdx.x;
-  if (n >= N) return;
-  float s = 0.f;
-  for (int p = 0; p < n_partial; ++p) s += partial[(int64_t)p * pstride + n];
-  float* o = split ? dst + (int64_t)(n / split) * seg_stride + (n % split) : dst + n;
-  *o += s;
+// dst[seg(n)] += sum_p partial[p * pstride + n] for n < N.  64 columns per workgroup; the four
+// wavefronts each take every fourth partial row (loads independent, coalesced over columns) and
+// are combined in a fixed order.  Columns n >= n_first go to dst2 (index n - n_first) instead.
+__global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partial, int n_partial,
+                                                              int64_t pstride, int N, float* __restrict__ dst,
+                                                              int split, int64_t seg_stride, float* __restrict__ dst2,
+                                                              int n_first) {
+  __shared__ float red[4][64];
+  const int c = threadIdx.x & 63, r = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + c;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (n < N) {
+    int p = r;
+    for (; p + 12 < n_partial; p += 16) {
+      s0 += partial[(int64_t)p * pstride + n];
+      s1 += partial[(int64_t)(p + 4) * pstride + n];
+      s2 += partial[(int64_t)(p + 8) * pstride + n];
+      s3 += partial[(int64_t)(p + 12) * pstride + n];
+    }
+    for (; p < n_partial; p += 4) s0 += partial[(int64_t)p * pstride + n];
+  }
+  red[r][c] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (r == 0 && n < N) {
+    const float s = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+    float* o;
+    if (dst2 && n >= n_first) o = dst2 + (n - n_first);
+    else o = split ? dst + (int64_t)(n / split) * seg_stride + (n % split) : dst + n;
+    *o += s;
+  }
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -564,7 +585,7 @@ void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float*
 
 int ln_bwd_partial_rows(int rows) {
   const int want = (rows + 3) / 4;
-  return want < 512 ? want : 512;
+  return want < 256 ? want : 256;
 }
 
 void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float* x, const float* mean,
@@ -578,14 +599,13 @@ void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float
     MM_LN_DISPATCH(layernorm_bwd_kernel, float, dy, x, mean, rstd, gamma, dres, dx_out, (float*)nullptr,
                    partial, rows, d)
   }
-  const int g2 = (d + 255) / 256;
-  reduce_partials_kernel<<<g2, 256, 0, st>>>(partial, grid, 2 * (int64_t)d, d, dgamma, 0, 0);
-  reduce_partials_kernel<<<g2, 256, 0, st>>>(partial + d, grid, 2 * (int64_t)d, d, dbeta, 0, 0);
+  reduce_partials_kernel<<<(2 * d + 63) / 64, 256, 0, st>>>(partial, grid, 2 * (int64_t)d, 2 * d, dgamma, 0, 0,
+                                                            dbeta, d);
 }
 
 int colsum_partial_rows(int M) {
   int chunks = (M + 127) / 128;
-  return chunks < 64 ? chunks : 64;
+  return chunks < 32 ? chunks : 32;
 }
 
 void launch_colsum(hipStream_t st, Dtype dt, const void* Y, int y_f32, int64_t ldy, int M, int N,
@@ -597,7 +617,7 @@ void launch_colsum(hipStream_t st, Dtype dt, const void* Y, int y_f32, int64_t l
     colsum_kernel<float><<<grid, 256, 0, st>>>((const float*)Y, ldy, M, N, rows_per_chunk, partial);
   else
     colsum_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)Y, ldy, M, N, rows_per_chunk, partial);
-  reduce_partials_kernel<<<(N + 255) / 256, 256, 0, st>>>(partial, chunks, N, N, dst, split, seg_stride);
+  reduce_partials_kernel<<<(N + 63) / 64, 256, 0, st>>>(partial, chunks, N, N, dst, split, seg_stride, nullptr, 0);
 }
 
 void launch_ce(hipStream_t st, Dtype dt, void* z, const int32_t* label, float* loss_rows, int U, int V,
