@@ -412,6 +412,206 @@ inline size_t mfma_fwd_lds(int max_lk) {
   return (size_t)Lp * 128 + (size_t)64 * (Lp + 8) * 2;
 }
 
+// Backward with the same layouts.  Phase A: a wavefront owns 32 queries and walks the key tiles:
+// S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D) * scale, dQ^T += K^T dS^T.  Phase B: a
+// wavefront owns 32 keys and walks the query tiles: S = Q K^T, dP = dO V^T, then
+// dV^T += dO^T P and dK^T += Q^T dS.  Each phase keeps its A operands in LDS (natural and
+// transposed tiles) and takes its B operands straight from global memory (its own 32 rows) or
+// from the accumulators of the previous product.
+__global__ void __launch_bounds__(256) attn_bwd_mfma_kernel(const AttnParams p) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int b = blockIdx.x / p.H, h = blockIdx.x % p.H;
+  const int q0 = p.cu_q[b], lq = p.cu_q[b + 1] - q0;
+  const int k0 = p.cu_k[b], lk = p.cu_k[b + 1] - k0;
+  const int nkt = (lk + 31) >> 5, Lkp = nkt * 32;
+  const int nqt = (lq + 31) >> 5, Lqp = nqt * 32;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lcol = lane & 31, hh = lane >> 5;
+  float* Dd = reinterpret_cast<float*>(smem_raw);   // [max_lq padded to 32]
+  float* Ls = Dd + (((p.max_lq + 31) >> 5) << 5);
+  unsigned char* tiles = reinterpret_cast<unsigned char*>(Ls + (((p.max_lq + 31) >> 5) << 5));
+  const bf16_t* qg = (const bf16_t*)p.q + h * 64;
+  const bf16_t* kg = (const bf16_t*)p.k + h * 64;
+  const bf16_t* vg = (const bf16_t*)p.v + h * 64;
+  const bf16_t* og = (const bf16_t*)p.o + h * 64;
+  const bf16_t* dog = (const bf16_t*)p.d_o + h * 64;
+  const float scale = 0.125f;
+
+  // D_i = sum_c dO[i][c] O[i][c]; one lane handles one 16-byte chunk, eight lanes one row
+  for (int q = tid; q < Lqp * 8; q += 256) {
+    const int row = q >> 3, c = q & 7;
+    float part = 0.f;
+    if (row < lq) {
+      const uint4 a = *reinterpret_cast<const uint4*>(dog + (int64_t)(q0 + row) * p.lddo + c * 8);
+      const uint4 o = *reinterpret_cast<const uint4*>(og + (int64_t)(q0 + row) * p.ldo + c * 8);
+      const uint32_t* aw = &a.x; const uint32_t* ow = &o.x;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        part += __uint_as_float(aw[e] << 16) * __uint_as_float(ow[e] << 16);
+        part += __uint_as_float(aw[e] & 0xffff0000u) * __uint_as_float(ow[e] & 0xffff0000u);
+      }
+    }
+    part += __shfl_xor(part, 1, WAVE);
+    part += __shfl_xor(part, 2, WAVE);
+    part += __shfl_xor(part, 4, WAVE);
+    if (c == 0) {
+      Dd[row] = part;
+      Ls[row] = row < lq ? p.lse[(int64_t)h * p.rows_q + q0 + row] : 0.f;
+    }
+  }
+
+  // ---------------- phase A: dQ ----------------
+  {
+    unsigned char* Kn = tiles;
+    unsigned char* Vn = Kn + Lkp * 128;
+    unsigned char* Kt = Vn + Lkp * 128;
+    const int tstride = (Lkp + 8) * 2;
+    load_natural(Kn, kg, p.ldk, k0, lk, Lkp, tid);
+    load_natural(Vn, vg, p.ldv, k0, lk, Lkp, tid);
+    load_transposed(Kt, kg, p.ldk, k0, lk, Lkp, tid);
+    __syncthreads();
+    for (int qt = wave; qt < nqt; qt += 4) {
+      const int ql = qt * 32 + lcol;
+      const bool valid_q = ql < lq;
+      const int64_t grow = q0 + (valid_q ? ql : lq - 1);
+      bf16x8_t qf[4], dof[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        qf[s] = frag_global(qg + grow * p.ldq + (2 * s + hh) * 8);
+        dof[s] = frag_global(dog + grow * p.lddo + (2 * s + hh) * 8);
+      }
+      const float Lq_ = Ls[qt * 32 + lcol], Dq = Dd[qt * 32 + lcol];
+      f32x16_t dq[2];
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dq[ct][r] = 0.f;
+      const int kt_end = p.causal ? min(nkt, qt + 1) : nkt;
+      for (int kt = 0; kt < kt_end; ++kt) {
+        f32x16_t sc, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Kn, kt * 32 + lcol, 2 * s + hh), qf[s], sc, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Vn, kt * 32 + lcol, 2 * s + hh), dof[s], dp, 0, 0, 0);
+        }
+        float ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          const bool ok = !attn_blocked(ql, key, lk, p.causal);
+          const float pr = ok ? __expf(sc[r] * scale - Lq_) : 0.f;
+          ds[r] = pr * (dp[r] - Dq) * scale;
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8_t dsf = frag_from_regs(&ds[8 * s2]);
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct)
+            dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_transposed(Kt, tstride, ct * 32 + lcol, kt * 32 + s2 * 16 + hh * 8), dsf, dq[ct], 0, 0, 0);
+        }
+      }
+      if (valid_q) {
+        bf16_t* dst = (bf16_t*)p.dq + grow * p.lddq + h * 64;
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int g4 = 0; g4 < 4; ++g4) {
+            uint2 o;
+            o.x = pack_bf16(dq[ct][4 * g4 + 0], dq[ct][4 * g4 + 1]);
+            o.y = pack_bf16(dq[ct][4 * g4 + 2], dq[ct][4 * g4 + 3]);
+            *reinterpret_cast<uint2*>(dst + ct * 32 + 8 * g4 + 4 * hh) = o;
+          }
+      }
+    }
+  }
+  __syncthreads();
+  // ---------------- phase B: dK, dV ----------------
+  {
+    unsigned char* Qn = tiles;
+    unsigned char* dOn = Qn + Lqp * 128;
+    unsigned char* Qt = dOn + Lqp * 128;
+    const int tstride = (Lqp + 8) * 2;
+    unsigned char* dOt = Qt + 64 * tstride;
+    load_natural(Qn, qg, p.ldq, q0, lq, Lqp, tid);
+    load_natural(dOn, dog, p.lddo, q0, lq, Lqp, tid);
+    load_transposed(Qt, qg, p.ldq, q0, lq, Lqp, tid);
+    load_transposed(dOt, dog, p.lddo, q0, lq, Lqp, tid);
+    __syncthreads();
+    for (int kt = wave; kt < nkt; kt += 4) {
+      const int kl = kt * 32 + lcol;
+      const bool valid_k = kl < lk;
+      const int64_t grow = k0 + (valid_k ? kl : lk - 1);
+      bf16x8_t kf[4], vf[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        kf[s] = frag_global(kg + grow * p.ldk + (2 * s + hh) * 8);
+        vf[s] = frag_global(vg + grow * p.ldv + (2 * s + hh) * 8);
+      }
+      f32x16_t dk[2], dv[2];
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { dk[ct][r] = 0.f; dv[ct][r] = 0.f; }
+      const int qt_begin = p.causal ? kt : 0;
+      for (int qt = qt_begin; qt < nqt; ++qt) {
+        f32x16_t sc, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Qn, qt * 32 + lcol, 2 * s + hh), kf[s], sc, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(dOn, qt * 32 + lcol, 2 * s + hh), vf[s], dp, 0, 0, 0);
+        }
+        float pr[16], ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qi = qt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          const bool ok = qi < lq && !attn_blocked(qi, kl, lk, p.causal);
+          pr[r] = ok ? __expf(sc[r] * scale - Ls[qi]) : 0.f;
+          ds[r] = pr[r] * (dp[r] - Dd[qi]) * scale;
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8_t pf = frag_from_regs(&pr[8 * s2]);
+          const bf16x8_t dsf = frag_from_regs(&ds[8 * s2]);
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct) {
+            dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_transposed(dOt, tstride, ct * 32 + lcol, qt * 32 + s2 * 16 + hh * 8), pf, dv[ct], 0, 0, 0);
+            dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_transposed(Qt, tstride, ct * 32 + lcol, qt * 32 + s2 * 16 + hh * 8), dsf, dk[ct], 0, 0, 0);
+          }
+        }
+      }
+      if (valid_k) {
+        bf16_t* dkd = (bf16_t*)p.dk + grow * p.lddk + h * 64;
+        bf16_t* dvd = (bf16_t*)p.dv + grow * p.lddv + h * 64;
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int g4 = 0; g4 < 4; ++g4) {
+            uint2 o;
+            o.x = pack_bf16(dk[ct][4 * g4 + 0], dk[ct][4 * g4 + 1]);
+            o.y = pack_bf16(dk[ct][4 * g4 + 2], dk[ct][4 * g4 + 3]);
+            *reinterpret_cast<uint2*>(dkd + ct * 32 + 8 * g4 + 4 * hh) = o;
+            o.x = pack_bf16(dv[ct][4 * g4 + 0], dv[ct][4 * g4 + 1]);
+            o.y = pack_bf16(dv[ct][4 * g4 + 2], dv[ct][4 * g4 + 3]);
+            *reinterpret_cast<uint2*>(dvd + ct * 32 + 8 * g4 + 4 * hh) = o;
+          }
+      }
+    }
+  }
+}
+
+inline size_t mfma_bwd_lds(int max_lq, int max_lk) {
+  const size_t Lq = ((max_lq + 31) / 32) * 32, Lk = ((max_lk + 31) / 32) * 32;
+  const size_t a = 2 * Lk * 128 + 64 * (Lk + 8) * 2;
+  const size_t bq = 2 * Lq * 128 + 2 * 64 * (Lq + 8) * 2;
+  return 2 * Lq * sizeof(float) + (a > bq ? a : bq);
+}
+
 template <typename T>
 size_t lds_bytes_t(int dh, int max_lq, int max_lk, bool backward) {
   const size_t ldr = dh + row_pad<T>();
@@ -456,6 +656,12 @@ void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p) {
 }
 
 void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p) {
+  if (mfma_ok(dt, p) && p.lddo % 8 == 0 && p.lddq % 4 == 0 && p.lddk % 4 == 0 && p.lddv % 4 == 0) {
+    const size_t lds = mfma_bwd_lds(p.max_lq, p.max_lk);
+    hipFuncSetAttribute((const void*)attn_bwd_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attn_bwd_mfma_kernel<<<p.B * p.H, 256, lds, st>>>(p);
+    return;
+  }
   const size_t lds = attn_lds_bytes(dt, p.dh, p.max_lq, p.max_lk, true);
   if (dt == BF16) {
     hipFuncSetAttribute((const void*)attn_bwd_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
