@@ -207,15 +207,16 @@ struct TileLoader {
   }
 };
 
-template <int BM, int BN, int WM, int WN, bool KCA, bool KCB>
-__global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
+// CS: also produce the column sums of B over the whole K range (the bias gradient that goes with a
+// weight gradient: dW = X^T dY, db = column sums of dY).  Only the tiles of the first tile row do
+// it, from the registers the transposing loader has just filled (4 k x 8 columns per thread).
+template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, bool CS = false>
+__device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0, const int n0, unsigned char* lds) {
   static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts");
   constexpr int MT = WM / 32, NT = WN / 32;
-  extern __shared__ __align__(16) unsigned char lds[];
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave / (BN / WN), wn = wave % (BN / WN);
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
 
   TileLoader<BM, KCA> la;
   la.base = (const bf16_t*)p.A; la.ld = p.lda; la.row0 = m0; la.row_lim = p.M; la.K = p.K;
@@ -232,9 +233,28 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const bool do_cs = CS && p.colsum_dst != nullptr && m0 == 0;
+  auto add_colsum = [&]() {
+    if (CS && !KCB && BN == 128) {
+      if (do_cs) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t* w = &lb.v[j].x;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            cs[2 * e] += __uint_as_float(w[e] << 16);
+            cs[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+          }
+        }
+      }
+    }
+  };
+
   const int nk = (p.K + BK - 1) / BK;
   la.load(0, tid);
   lb.load(0, tid);
+  add_colsum();
   la.store(lds, tid);
   lb.store(lds + A_BYTES, tid);
   __syncthreads();
@@ -245,6 +265,7 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
     if (kt + 1 < nk) {
       la.load((kt + 1) * BK, tid);
       lb.load((kt + 1) * BK, tid);
+      add_colsum();
     }
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
@@ -272,6 +293,27 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
       lb.store(dA + A_BYTES, tid);
     }
     __syncthreads();
+  }
+
+  if (CS && !KCB && BN == 128) {
+    if (do_cs) {  // uniform over the workgroup; LDS is free after the loop's last barrier
+      float* red = reinterpret_cast<float*>(lds);  // [16 k-groups][128 columns]
+      const int cg = tid & 15, kq = tid >> 4;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[kq * 128 + cg * 8 + e] = cs[e];
+      __syncthreads();
+      if (tid < 128) {
+        const int n = n0 + tid;
+        if (n < p.N) {
+          float t = 0.f;
+#pragma unroll
+          for (int g = 0; g < 16; ++g) t += red[g * 128 + tid];
+          int64_t idx = n;
+          if (p.c_split) { const int sg = n / p.c_split; idx = (int64_t)sg * p.c_seg_stride + (n - sg * p.c_split); }
+          p.colsum_dst[idx] += t;
+        }
+      }
+    }
   }
 
   // epilogue: lane holds column n = .. + lane%32 and rows 8*(r/4) + 4*(lane/32) + r%4 of each tile
@@ -304,6 +346,41 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
       }
     }
   }
+}
+
+template <int BM, int BN, int WM, int WN, bool KCA, bool KCB>
+__global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB>(p, blockIdx.y * BM, blockIdx.x * BN, lds);
+}
+
+// Many independent problems of one layout in one launch: workgroup -> (problem, tile) through a
+// prefix table of tile counts.  Used for the weight-gradient products of a whole step, each of
+// which alone has too few output tiles to fill 256 compute units.
+template <int BM, int BN, int WM, int WN, bool KCA, bool KCB>
+__global__ void __launch_bounds__(256) gemm_mfma_grouped_kernel(const GemmParams* __restrict__ table,
+                                                                const int32_t* __restrict__ tile_start,
+                                                                int n_problems) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  __shared__ GemmParams prm;
+  __shared__ int local_tile;
+  if (threadIdx.x == 0) {
+    int lo = 0, hi = n_problems - 1;
+    const int t = blockIdx.x;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (tile_start[mid] <= t) lo = mid; else hi = mid - 1;
+    }
+    prm = table[lo];
+    local_tile = t - tile_start[lo];
+  }
+  __syncthreads();
+  const int tiles_n = (prm.N + BN - 1) / BN;
+  // consecutive workgroups walk down M first: they share the same columns of B (dY)
+  const int tiles_m = (prm.M + BM - 1) / BM;
+  const int tm = local_tile % tiles_m, tn = local_tile / tiles_m;
+  (void)tiles_n;
+  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, true>(prm, tm * BM, tn * BN, lds);
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -341,6 +418,26 @@ bool mfma_eligible(const GemmParams& p) {
 }
 
 }  // namespace
+
+bool gemm_groupable(Dtype dt, const GemmParams& p) {
+  return dt == BF16 && p.transA == 1 && p.transB == 0 && mfma_eligible(p);
+}
+
+int gemm_grouped_tiles(const GemmParams& p) { return ((p.M + 127) / 128) * ((p.N + 127) / 128); }
+
+void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const int32_t* tile_start_dev,
+                            int n_problems, int total_tiles) {
+  if (n_problems <= 0 || total_tiles <= 0) return;
+  constexpr int LDS = 2 * (128 + 128) * 128;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipFuncSetAttribute((const void*)gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false>,
+                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    attr_set = true;
+  }
+  gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false><<<total_tiles, 256, LDS, st>>>(table_dev, tile_start_dev,
+                                                                                          n_problems);
+}
 
 void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p) {
   if (p.M <= 0 || p.N <= 0) return;

@@ -53,8 +53,17 @@ struct GemmParams {
   const float* residual;  // fp32 [M,N], row stride ldr, same segmentation as C: added last
   int64_t ldr;
   int out_f32;            // 1: C is fp32; 0: C has the working dtype
+  float* colsum_dst;      // grouped weight-gradient launch only: [N] (segmented like C) += column
+                          // sums of B over K, i.e. the bias gradient belonging to this product
 };
 void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p);
+// Weight-gradient products (transA = 1, transB = 0) of a whole step in one launch.  table_dev and
+// tile_start_dev are device arrays of n_problems entries; tile_start is the running sum of
+// gemm_grouped_tiles() and total_tiles its total.  Every problem must satisfy gemm_groupable().
+bool gemm_groupable(Dtype dt, const GemmParams& p);
+int gemm_grouped_tiles(const GemmParams& p);
+void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const int32_t* tile_start_dev,
+                            int n_problems, int total_tiles);
 // Same contract, always the plain FMA kernel (cross-check of the MFMA path).
 void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p);
 

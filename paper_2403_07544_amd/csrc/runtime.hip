@@ -76,6 +76,10 @@ struct mm_ctx {
   hipEvent_t ev_stage = nullptr, ev_done = nullptr;
   AdamSegment* seg_host = nullptr; AdamSegment* seg_dev = nullptr; int seg_cap = 0;
   hipEvent_t ev_seg = nullptr;
+  // table of the step's deferred weight-gradient products (pinned host copy, device copy)
+  GemmParams* gtab_host = nullptr; GemmParams* gtab_dev = nullptr;
+  int32_t* gstart_host = nullptr; int32_t* gstart_dev = nullptr;
+  hipEvent_t ev_gtab = nullptr;
   Arena ws;
   // last step
   int B = 0, S_max = 0, T_max = 0, S = 0, U = 0;
@@ -142,6 +146,7 @@ void build_layout(const mm_config& cfg, Module& m) {
 }
 
 constexpr int ENC_T = 16, DEC_T = 26, ADP_T = 6;
+constexpr int MAX_GROUPED = 1024;
 
 // ---------------------------------------------------------------------------------------------
 // launch wrappers: skip in the measuring pass, bracket with events when profiling
@@ -334,6 +339,43 @@ struct Step {
 
   float* partial = nullptr;  // scratch for column-sum / LayerNorm partials
 
+  // Weight-gradient products are independent of everything later in the step (their operands are
+  // saved activations and gradients that stay in the workspace), and each alone has too few
+  // output tiles for 256 compute units: they are collected and run as one grouped launch.
+  std::vector<GemmParams> deferred;
+  // p: the weight-gradient product dW += X^T dY.  gb: the bias gradient that goes with it
+  // (db += column sums of dY, segmented like dW); Yf32: an fp32 version of dY if one exists.
+  void wgrad(GemmParams p, float* gb, const float* Yf32) {
+    if (dry()) return;
+    if ((int)deferred.size() < MAX_GROUPED && gemm_groupable(c->dt, p)) {
+      p.colsum_dst = gb;
+      deferred.push_back(p);
+      return;
+    }
+    run.gemm(p);
+    if (Yf32) run.colsum(Yf32, 1, p.ldb, p.K, p.N, partial, gb, p.c_split, p.c_seg_stride);
+    else run.colsum(p.B, 0, p.ldb, p.K, p.N, partial, gb, p.c_split, p.c_seg_stride);
+  }
+  void flush_wgrads() {
+    if (deferred.empty()) return;
+    hipEventSynchronize(c->ev_gtab);  // the previous step's upload has left the pinned table
+    int tiles = 0;
+    double flops = 0;
+    for (size_t i = 0; i < deferred.size(); ++i) {
+      c->gtab_host[i] = deferred[i];
+      c->gstart_host[i] = tiles;
+      tiles += gemm_grouped_tiles(deferred[i]);
+      flops += 2.0 * deferred[i].M * deferred[i].N * deferred[i].K;
+    }
+    hipMemcpyAsync(c->gtab_dev, c->gtab_host, deferred.size() * sizeof(GemmParams), hipMemcpyHostToDevice, c->st);
+    hipMemcpyAsync(c->gstart_dev, c->gstart_host, deferred.size() * sizeof(int32_t), hipMemcpyHostToDevice, c->st);
+    hipEventRecord(c->ev_gtab, c->st);
+    run.begin(MM_K_GEMM, flops);
+    launch_gemm_grouped_tn(c->st, c->gtab_dev, c->gstart_dev, (int)deferred.size(), tiles);
+    run.end();
+    deferred.clear();
+  }
+
   Grad ffn_bwd(const PV& pv, int t0, const FfnSave& s, Grad g, int R, int hidden) {
     void* dh = act((size_t)R * hidden);
     float* da = f32((size_t)R * d);
@@ -342,13 +384,11 @@ struct Step {
     GemmParams p = gp_dgrad(g.dxT, d, pv.W(t0 + 4), hidden, d, dh, R);
     p.relu_mask = s.h; p.ldm = hidden;
     run.gemm(p);
-    run.gemm(gp_wgrad(s.h, hidden, g.dxT, d, pv.G(t0 + 4), hidden, d, R));
-    run.colsum(g.dx, 1, d, R, d, partial, pv.G(t0 + 5), 0, 0);
+    wgrad(gp_wgrad(s.h, hidden, g.dxT, d, pv.G(t0 + 4), hidden, d, R), pv.G(t0 + 5), g.dx);
     p = gp_dgrad(dh, hidden, pv.W(t0 + 2), d, hidden, da, R);
     p.out_f32 = 1;
     run.gemm(p);
-    run.gemm(gp_wgrad(s.a, d, dh, hidden, pv.G(t0 + 2), d, hidden, R));
-    run.colsum(dh, 0, hidden, R, hidden, partial, pv.G(t0 + 3), 0, 0);
+    wgrad(gp_wgrad(s.a, d, dh, hidden, pv.G(t0 + 2), d, hidden, R), pv.G(t0 + 3), nullptr);
     run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, partial, pv.G(t0), pv.G(t0 + 1), R);
     if (c->dt != BF16) out.dxT = out.dx;
     return out;
@@ -360,8 +400,7 @@ struct Step {
     float* da = f32((size_t)R * d);
     Grad out{f32((size_t)R * d), c->dt == BF16 ? act((size_t)R * d) : nullptr};
     run.gemm(gp_dgrad(g.dxT, d, pv.W(t0 + 8), d, d, d_o, R));
-    run.gemm(gp_wgrad(s.o, d, g.dxT, d, pv.G(t0 + 8), d, d, R));
-    run.colsum(g.dx, 1, d, R, d, partial, pv.G(t0 + 9), 0, 0);
+    wgrad(gp_wgrad(s.o, d, g.dxT, d, pv.G(t0 + 8), d, d, R), pv.G(t0 + 9), g.dx);
     const char* qkv = (const char*)s.qkv;
     char* dq = (char*)dqkv;
     AttnParams a = ap(qkv, 3 * d, dry() ? nullptr : qkv + (size_t)d * esz, dry() ? nullptr : qkv + (size_t)2 * d * esz,
@@ -376,8 +415,7 @@ struct Step {
     run.gemm(p);
     p = gp_wgrad(s.a, d, dqkv, 3 * d, pv.G(t0 + 2), d, 3 * d, R);
     p.ldc = d; p.ldr = d; p.c_split = d; p.c_seg_stride = seg;
-    run.gemm(p);
-    run.colsum(dqkv, 0, 3 * d, R, 3 * d, partial, pv.G(t0 + 3), d, seg);
+    wgrad(p, pv.G(t0 + 3), nullptr);
     run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, partial, pv.G(t0), pv.G(t0 + 1), R);
     if (c->dt != BF16) out.dxT = out.dx;
     return out;
@@ -390,8 +428,7 @@ struct Step {
     float* da = f32((size_t)U * d);
     Grad out{f32((size_t)U * d), c->dt == BF16 ? act((size_t)U * d) : nullptr};
     run.gemm(gp_dgrad(g.dxT, d, pv.W(t0 + 8), d, d, d_o, U));
-    run.gemm(gp_wgrad(s.o, d, g.dxT, d, pv.G(t0 + 8), d, d, U));
-    run.colsum(g.dx, 1, d, U, d, partial, pv.G(t0 + 9), 0, 0);
+    wgrad(gp_wgrad(s.o, d, g.dxT, d, pv.G(t0 + 8), d, d, U), pv.G(t0 + 9), g.dx);
     const char* kv = (const char*)s.kv;
     char* dkvc = (char*)dkv;
     AttnParams a = ap(s.q, d, kv, dry() ? nullptr : kv + (size_t)d * esz, 2 * d, s.o, s.lse, true, false, 0);
@@ -402,8 +439,7 @@ struct Step {
     GemmParams p = gp_dgrad(dq, d, pv.W(t0 + 2), d, d, da, U);
     p.out_f32 = 1;
     run.gemm(p);
-    run.gemm(gp_wgrad(s.a, d, dq, d, pv.G(t0 + 2), d, d, U));
-    run.colsum(dq, 0, d, U, d, partial, pv.G(t0 + 3), 0, 0);
+    wgrad(gp_wgrad(s.a, d, dq, d, pv.G(t0 + 2), d, d, U), pv.G(t0 + 3), nullptr);
     // memory side: d mem (+)= dkv [Wk|Wv]^T
     const int64_t seg = pv.off(t0 + 6) - pv.off(t0 + 4);
     p = gp_dgrad(dkv, 2 * d, pv.W(t0 + 4), d, 2 * d, dmem, S);
@@ -412,8 +448,7 @@ struct Step {
     run.gemm(p);
     p = gp_wgrad(mem, d, dkv, 2 * d, pv.G(t0 + 4), d, 2 * d, S);
     p.ldc = d; p.ldr = d; p.c_split = d; p.c_seg_stride = seg;
-    run.gemm(p);
-    run.colsum(dkv, 0, 2 * d, S, 2 * d, partial, pv.G(t0 + 5), d, seg);
+    wgrad(p, pv.G(t0 + 5), nullptr);
     run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, partial, pv.G(t0), pv.G(t0 + 1), U);
     if (c->dt != BF16) out.dxT = out.dx;
     return out;
@@ -613,8 +648,7 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
     GemmParams p = s.gp_dgrad(z, V, pv_gen.W(0), d, V, dh, U);
     p.out_f32 = 1;
     run.gemm(p);
-    run.gemm(s.gp_wgrad(h, d, z, V, pv_gen.G(0), d, V, U));
-    run.colsum(z, 0, V, U, V, s.partial, pv_gen.G(1), 0, 0);
+    s.wgrad(s.gp_wgrad(h, d, z, V, pv_gen.G(0), d, V, U), pv_gen.G(1), nullptr);
   }
   Step::Grad g{s.f32((size_t)U * d), c->dt == BF16 ? s.act((size_t)U * d) : nullptr};
   run.ln_bwd(dh, y_dec_top, ln_decf.mean, ln_decf.rstd, pv_decf.V(0), nullptr, g.dx, g.dxT, s.partial,
@@ -652,6 +686,7 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
     launch_embed_grad(c->st, c->src_tok, ge.dx, m_src.g, c->sort_keys, S, d, sqrt_d);
     run.end();
   }
+  s.flush_wgrads();
 }
 
 bool valid_module(mm_ctx* c, int id) { return id >= 0 && id < (int)c->mods.size(); }
@@ -759,6 +794,11 @@ mm_status mm_create(const mm_config* cfg, mm_ctx** out) {
   guard(hipEventCreateWithFlags(&c->ev_stage, hipEventDisableTiming), "hipEventCreate");
   guard(hipEventCreateWithFlags(&c->ev_done, hipEventDisableTiming), "hipEventCreate");
   guard(hipEventCreateWithFlags(&c->ev_seg, hipEventDisableTiming), "hipEventCreate");
+  guard(hipEventCreateWithFlags(&c->ev_gtab, hipEventDisableTiming), "hipEventCreate");
+  guard(hipHostMalloc((void**)&c->gtab_host, MAX_GROUPED * sizeof(GemmParams), hipHostMallocDefault), "hipHostMalloc(table)");
+  guard(hipHostMalloc((void**)&c->gstart_host, MAX_GROUPED * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(table)");
+  guard(hipMalloc((void**)&c->gtab_dev, MAX_GROUPED * sizeof(GemmParams)), "hipMalloc(table)");
+  guard(hipMalloc((void**)&c->gstart_dev, MAX_GROUPED * sizeof(int32_t)), "hipMalloc(table)");
   if (s != MM_OK) return s;
   guard(hipMemcpy(c->pe, pe.data(), pe.size() * 4, hipMemcpyHostToDevice), "hipMemcpy(pe)");
   guard(hipMemset(c->flag, 0, 64), "hipMemset");
@@ -786,6 +826,11 @@ mm_status mm_destroy(mm_ctx* c) {
     if (c->ev_stage) hipEventDestroy(c->ev_stage);
     if (c->ev_done) hipEventDestroy(c->ev_done);
     if (c->ev_seg) hipEventDestroy(c->ev_seg);
+    if (c->ev_gtab) hipEventDestroy(c->ev_gtab);
+    if (c->gtab_host) hipHostFree(c->gtab_host);
+    if (c->gstart_host) hipHostFree(c->gstart_host);
+    if (c->gtab_dev) hipFree(c->gtab_dev);
+    if (c->gstart_dev) hipFree(c->gstart_dev);
   }
   delete c;
   return MM_OK;
