@@ -289,11 +289,13 @@ class Oracle:
 
     # ---- registry (section 3.2: position-specific modules, layers per position) ----------
     def register_module(self, kind, name="", position=0, n_layers=0, owns_final_norm=False,
-                        adapter_dim=0, stack="", init: Optional[np.ndarray] = None) -> int:
+                        adapter_dim=0, stack="", init: Optional[np.ndarray] = None,
+                        shell: bool = False) -> int:
         specs, total = module_layout(kind, self.d, self.F, self.V, n_layers, owns_final_norm,
                                      adapter_dim)
         mod = _Module(kind, name, position, n_layers, owns_final_norm, adapter_dim, stack,
-                      specs, total, self.dtype)
+                      specs, 0 if shell else total, self.dtype)
+        mod.total = total
         if init is not None:
             assert init.shape == (total,)
             mod.theta[:] = init
@@ -578,9 +580,11 @@ class Oracle:
 
 
 def build_from_setup(setup, dtype=np.float64, perturbed=False, keep_trace=False,
-                     fill_params=None):
+                     fill_params=None, needed=None):
     """Registers a set-up's modules and tasks; `fill_params` is the seeded initialiser
-    (role, offset, size table -> float32 vector) passed in by the caller."""
+    (role, offset, size table -> float32 vector) passed in by the caller.  `needed`: optional set
+    of module indices to materialise; the others are registered as empty shells (same ids and
+    routes, no arrays) so that a large set-up can be checked one task at a time."""
     sh = setup.shape
     orc = Oracle(sh.d_model, sh.n_heads, sh.d_ff, sh.vocab, sh.max_len, sh.label_smoothing,
                  sh.adam_beta1, sh.adam_beta2, sh.adam_eps, sh.ln_eps, dtype=dtype,
@@ -589,6 +593,10 @@ def build_from_setup(setup, dtype=np.float64, perturbed=False, keep_trace=False,
         specs, total = module_layout(ms.kind, sh.d_model, sh.d_ff, sh.vocab, ms.n_layers,
                                      ms.owns_final_norm, ms.adapter_dim)
         init = None
+        if needed is not None and k not in needed:
+            j = orc.register_module(ms.kind, ms.name, ms.position, ms.n_layers, ms.owns_final_norm,
+                                    ms.adapter_dim, ms.stack, None, shell=True)
+            continue
         if fill_params is not None:
             init = fill_params([(s.role, s.offset, s.size) for s in specs], total,
                                setup.weight_seed * 1000 + k, perturbed).astype(dtype)

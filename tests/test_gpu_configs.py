@@ -45,3 +45,57 @@ def test_config2_transformer_base_full_step():
         w = ctx.mm_get_working(j)
         assert np.abs(w - th1).max() <= np.abs(th1).max() * 2.0 ** -8
     assert ctx.mm_get_touched().sum() == 0
+
+
+def _modular_case(index, n_tasks, seed):
+    """All modules resident on the GPU; the oracle materialises only the modules of the sampled
+    tasks.  Steps of different tasks accumulate, then one update: touched-only bookkeeping."""
+    setup = mm_synth.build_setup(index)
+    rng = np.random.default_rng(seed)
+    tasks = [int(t) for t in rng.choice(len(setup.tasks), size=n_tasks, replace=False)]
+    needed = set()
+    for t in tasks:
+        needed |= set(setup.tasks[t][1])
+    batches = mm_synth.make_batches(setup, n_tasks)
+    say(f"[case] config {index}: tasks {[setup.tasks[t][0] for t in tasks]}, {len(setup.modules)} modules resident")
+    t0 = time.time()
+    from paper_2403_07544_amd import context_from_setup
+    from oracle.mammoth_oracle import build_from_setup
+    ctx = context_from_setup(setup, fill_params=mm_synth.fill_params)
+    orc = build_from_setup(setup, dtype=np.float64, fill_params=mm_synth.fill_params, needed=needed)
+    say(f"  built in {time.time() - t0:.1f}s")
+    probe = [j for j in range(len(setup.modules)) if j not in needed][:3]
+    before = {j: (ctx.mm_get_params(j), *ctx.mm_get_adam(j)) for j in probe}
+    for t, batch in zip(tasks, batches):
+        loss = ctx.mm_train_step(t, batch.src_ids, batch.tgt_ids, batch.lengths)
+        t0 = time.time()
+        ref = orc.train_step(t, batch.src_ids, batch.tgt_ids, batch.lengths)
+        say(f"  task {setup.tasks[t][0]}: S={batch.n_src_tokens} U={batch.n_tgt_tokens} loss {loss:.5f} oracle {ref:.5f} ({time.time() - t0:.1f}s)")
+        assert abs(loss - ref) <= 1e-2 * abs(ref)
+        check_integer_artefacts(ctx, orc, batch, t)
+    check_touched(ctx, orc)
+    worst = check_grads(ctx, orc, sorted(needed), label=f"config{index}", **BF16_TOL)
+    say(f"  worst tensor {worst}")
+    for j in probe:
+        assert not ctx.mm_get_grads(j).any()
+    ctx.mm_apply_update(None, setup.shape.lr)
+    for j in probe:                                   # unused modules: not a bit different
+        th, m, v, tj = before[j]
+        m2, v2, t2 = ctx.mm_get_adam(j)
+        assert np.array_equal(th, ctx.mm_get_params(j)) and np.array_equal(m, m2) and np.array_equal(v, v2) and t2 == tj == 0
+    for j in sorted(needed)[:4]:
+        assert ctx.mm_get_adam(j)[2] == 1 and not ctx.mm_get_grads(j).any()
+    assert ctx.mm_get_touched().sum() == 0
+    ctx.close()
+
+
+def test_config3_fully_modular_routing_and_buckets():
+    _modular_case(3, n_tasks=2, seed=1)
+
+
+def test_config4_partially_shared_with_adapters():
+    _modular_case(4, n_tasks=2, seed=2)
+
+
+def test_config5_transformer_big_one_task():
+    _modular_case(5, n_tasks=1, seed=3)
