@@ -115,83 +115,109 @@ __global__ void __launch_bounds__(256) gemm_simt_kernel(const GemmParams p) {
 // =================================================================================================
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) u32x4_t* global_u4_ptr;
 
 constexpr int BK = 64;
+
+// 16-byte load from global memory through an address the optimiser cannot reason about: the load
+// stays unconditional (no divergent branch around it), which keeps the count of outstanding loads
+// exact, so a wait for one K step's data does not drain the prefetched ones.
+__device__ __forceinline__ u32x4_t load16_global(const bf16_t* a) {
+  uint64_t addr = reinterpret_cast<uint64_t>(a);
+  asm volatile("" : "+v"(addr));
+  return *reinterpret_cast<global_u4_ptr>(addr);
+}
 
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row >> 4) & 3); }
 
 // Loads one operand tile (R rows x 64 k) from global memory into registers, then into LDS.
 // KC: operand is k-contiguous in memory (element (row,k) at base + row*ld + k), else
-// row-contiguous (element at base + k*ld + row).  split/seg_stride: see GemmParams.
+// row-contiguous (element at base + k*ld + row).  Everything that does not change from one K step
+// to the next (row pointers, bounds, LDS offsets, the segment a row belongs to) is worked out once
+// in init(); a K step costs one address add, one compare, one load and one LDS store per item.
 template <int R, bool KC>
 struct TileLoader {
   static constexpr int NL = KC ? R / 32 : (R >= 128 ? R / 128 : 1);  // work items per thread
-  uint4 v[KC ? NL : NL * 4];
-  const bf16_t* base; int64_t ld; int row0, row_lim, K;
-  int split, split_on_k; int64_t seg_stride;
+  static constexpr int NV = KC ? NL : NL * 4;                          // 16-byte registers per K step
+  const bf16_t* ptr[NL];      // item address at k = 0
+  int klim[NL];               // KC: item valid while k0 < klim; else: k row j valid while k0 + j < klim
+  int off[KC ? NL : NL * 8];  // LDS byte offsets inside the tile
+  int64_t ld;
+  int ksplit; int64_t seg_stride;  // KC only: segments along k (multiple of 64)
+  const bf16_t* safe;              // any valid address: out-of-range items read it and are zeroed
 
-  __device__ __forceinline__ void load(int k0, int tid) {
-    if (KC) {
+  __device__ __forceinline__ void init(const bf16_t* base, int64_t ld_, int row0, int row_lim, int K, int split,
+                                       int split_on_k, int64_t seg_stride_, int tid) {
+    ld = ld_;
+    safe = base;
+    ksplit = (KC && split && split_on_k) ? split : 0;
+    seg_stride = seg_stride_;
 #pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        const int q = tid + 256 * i, row = q >> 3, c = q & 7;
-        const int gr = row0 + row, k = k0 + c * 8;
-        uint4 val = make_uint4(0, 0, 0, 0);
-        if (gr < row_lim && k < K) {
-          const bf16_t* ptr = base;
-          int kl = k, rl = gr;
-          if (split) {
-            if (split_on_k) { const int sg = k / split; kl = k - sg * split; ptr += (int64_t)sg * seg_stride; }
-            else { const int sg = gr / split; rl = gr - sg * split; ptr += (int64_t)sg * seg_stride; }
-          }
-          val = *reinterpret_cast<const uint4*>(ptr + (int64_t)rl * ld + kl);
-        }
-        v[i] = val;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        const int q = tid + 256 * i;
+    for (int i = 0; i < NL; ++i) {
+      const int q = tid + 256 * i;
+      if (KC) {
+        const int row = q >> 3, c = q & 7;
+        const int gr = row0 + row;
+        const bf16_t* b = base;
+        int rl = gr;
+        if (split && !split_on_k) { const int sg = gr / split; rl = gr - sg * split; b += (int64_t)sg * seg_stride_; }
+        ptr[i] = b + (int64_t)rl * ld_ + c * 8;
+        klim[i] = gr < row_lim ? K - c * 8 : 0;
+        off[i] = row * 128 + ((c ^ swz(row)) << 4);
+      } else {
         const int cg = q % (R / 8), kq = q / (R / 8);
         const int gc = row0 + cg * 8;
-        const bf16_t* ptr = base;
+        const bf16_t* b = base;
         int cl = gc;
-        bool ok = gc < row_lim && kq < 16;
-        if (split && !split_on_k) { const int sg = gc / split; cl = gc - sg * split; ptr += (int64_t)sg * seg_stride; }
+        if (split && !split_on_k) { const int sg = gc / split; cl = gc - sg * split; b += (int64_t)sg * seg_stride_; }
+        ptr[i] = b + (int64_t)(kq * 4) * ld_ + cl;
+        klim[i] = (gc < row_lim && kq < 16) ? K - kq * 4 : 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int k = k0 + kq * 4 + j;
-          uint4 val = make_uint4(0, 0, 0, 0);
-          if (ok && k < K) {
-            const bf16_t* pk = ptr;
-            int kl = k;
-            if (split && split_on_k) { const int sg = k / split; kl = k - sg * split; pk += (int64_t)sg * seg_stride; }
-            val = *reinterpret_cast<const uint4*>(pk + (int64_t)kl * ld + cl);
-          }
-          v[i * 4 + j] = val;
+        for (int e = 0; e < 8; ++e) {
+          const int row = cg * 8 + e;
+          off[i * 8 + e] = kq < 16 ? row * 128 + (((kq >> 1) ^ swz(row)) << 4) + ((kq & 1) << 3) : -1;
         }
       }
     }
   }
 
-  __device__ __forceinline__ void store(unsigned char* lds, int tid) const {
+  __device__ __forceinline__ void load(int k0, u32x4_t (&v)[NV]) const {
     if (KC) {
+      int64_t koff = k0;
+      if (ksplit) { const int sg = k0 / ksplit; koff = (int64_t)sg * seg_stride + (k0 - sg * ksplit); }
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
-        const int q = tid + 256 * i, row = q >> 3, c = q & 7;
-        *reinterpret_cast<uint4*>(lds + row * 128 + ((c ^ swz(row)) << 4)) = v[i];
+        // no branch around the load: the compiler then counts outstanding loads exactly and the
+        // stores to LDS wait only for the K step they need, not for the prefetched ones
+        v[i] = load16_global(k0 < klim[i] ? ptr[i] + koff : safe);  // zeroed when stored if out of range
       }
     } else {
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
-        const int q = tid + 256 * i;
-        const int cg = q % (R / 8), kq = q / (R / 8);
-        if (kq >= 16) continue;
-        const uint32_t* w0 = &v[i * 4 + 0].x; const uint32_t* w1 = &v[i * 4 + 1].x;
-        const uint32_t* w2 = &v[i * 4 + 2].x; const uint32_t* w3 = &v[i * 4 + 3].x;
+        const bf16_t* p0 = ptr[i] + (int64_t)k0 * ld;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          v[i * 4 + j] = load16_global(k0 + j < klim[i] ? p0 + (int64_t)j * ld : safe);
+        }
+      }
+    }
+  }
+
+  // k0: the K step these registers were loaded for (items beyond the operand's extent become 0)
+  __device__ __forceinline__ void store(unsigned char* lds, int k0, const u32x4_t (&v)[NV]) const {
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
+    if (KC) {
+#pragma unroll
+      for (int i = 0; i < NL; ++i) *reinterpret_cast<u32x4_t*>(lds + off[i]) = k0 < klim[i] ? v[i] : zero;
+    } else {
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        if (off[i * 8] < 0) continue;
+        const u32x4_t w0 = k0 + 0 < klim[i] ? v[i * 4 + 0] : zero, w1 = k0 + 1 < klim[i] ? v[i * 4 + 1] : zero;
+        const u32x4_t w2 = k0 + 2 < klim[i] ? v[i * 4 + 2] : zero, w3 = k0 + 3 < klim[i] ? v[i * 4 + 3] : zero;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const int row = cg * 8 + e;
           uint2 o;
           if (e & 1) {
             o.x = (w0[e >> 1] >> 16) | (w1[e >> 1] & 0xffff0000u);
@@ -200,7 +226,7 @@ struct TileLoader {
             o.x = (w0[e >> 1] & 0xffffu) | (w1[e >> 1] << 16);
             o.y = (w2[e >> 1] & 0xffffu) | (w3[e >> 1] << 16);
           }
-          *reinterpret_cast<uint2*>(lds + row * 128 + (((kq >> 1) ^ swz(row)) << 4) + ((kq & 1) << 3)) = o;
+          *reinterpret_cast<uint2*>(lds + off[i * 8 + e]) = o;
         }
       }
     }
@@ -210,7 +236,8 @@ struct TileLoader {
 // CS: also produce the column sums of B over the whole K range (the bias gradient that goes with a
 // weight gradient: dW = X^T dY, db = column sums of dY).  Only the tiles of the first tile row do
 // it, from the registers the transposing loader has just filled (4 k x 8 columns per thread).
-template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, bool CS = false>
+// PF: K steps whose global loads are in flight ahead of the one being multiplied (register staged).
+template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF, bool CS = false>
 __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0, const int n0, unsigned char* lds) {
   static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts");
   constexpr int MT = WM / 32, NT = WN / 32;
@@ -219,11 +246,9 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   const int wm = wave / (BN / WN), wn = wave % (BN / WN);
 
   TileLoader<BM, KCA> la;
-  la.base = (const bf16_t*)p.A; la.ld = p.lda; la.row0 = m0; la.row_lim = p.M; la.K = p.K;
-  la.split = 0; la.split_on_k = 0; la.seg_stride = 0;
+  la.init((const bf16_t*)p.A, p.lda, m0, p.M, p.K, 0, 0, 0, tid);
   TileLoader<BN, KCB> lb;
-  lb.base = (const bf16_t*)p.B; lb.ld = p.ldb; lb.row0 = n0; lb.row_lim = p.N; lb.K = p.K;
-  lb.split = p.b_split; lb.split_on_k = p.b_split_on_k; lb.seg_stride = p.b_seg_stride;
+  lb.init((const bf16_t*)p.B, p.ldb, n0, p.N, p.K, p.b_split, p.b_split_on_k, p.b_seg_stride, tid);
 
   f32x16_t acc[MT][NT];
 #pragma unroll
@@ -235,16 +260,19 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
 
   float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const bool do_cs = CS && p.colsum_dst != nullptr && m0 == 0;
-  auto add_colsum = [&]() {
+  u32x4_t va[PF][TileLoader<BM, KCA>::NV];
+  u32x4_t vb[PF][TileLoader<BN, KCB>::NV];
+  auto add_colsum = [&](const u32x4_t (&v)[TileLoader<BN, KCB>::NV], int k0) {
     if (CS && !KCB && BN == 128) {
       if (do_cs) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const uint32_t* w = &lb.v[j].x;
+          if (k0 + j < lb.klim[0]) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            cs[2 * e] += __uint_as_float(w[e] << 16);
-            cs[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+            for (int e = 0; e < 4; ++e) {
+              cs[2 * e] += __uint_as_float(v[j][e] << 16);
+              cs[2 * e + 1] += __uint_as_float(v[j][e] & 0xffff0000u);
+            }
           }
         }
       }
@@ -252,48 +280,61 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   };
 
   const int nk = (p.K + BK - 1) / BK;
-  la.load(0, tid);
-  lb.load(0, tid);
-  add_colsum();
-  la.store(lds, tid);
-  lb.store(lds + A_BYTES, tid);
-  __syncthreads();
-  const int lrow = lane & 31, lhalf = lane >> 5;
-  for (int kt = 0; kt < nk; ++kt) {
-    const unsigned char* sA = lds + (kt & 1) * STAGE;
-    const unsigned char* sB = sA + A_BYTES;
-    if (kt + 1 < nk) {
-      la.load((kt + 1) * BK, tid);
-      lb.load((kt + 1) * BK, tid);
-      add_colsum();
+#pragma unroll
+  for (int u = 0; u < PF; ++u) {
+    if (u < nk) {
+      la.load(u * BK, va[u]);
+      lb.load(u * BK, vb[u]);
     }
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8_t af[MT], bfr[NT];
-      const int c = kk * 2 + lhalf;
-#pragma unroll
-      for (int i = 0; i < MT; ++i) {
-        const int row = wm * WM + i * 32 + lrow;
-        af[i] = *reinterpret_cast<const bf16x8_t*>(sA + row * 128 + ((c ^ swz(row)) << 4));
-      }
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const int row = wn * WN + j * 32 + lrow;
-        bfr[j] = *reinterpret_cast<const bf16x8_t*>(sB + row * 128 + ((c ^ swz(row)) << 4));
-      }
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      unsigned char* dA = lds + ((kt + 1) & 1) * STAGE;
-      la.store(dA, tid);
-      lb.store(dA + A_BYTES, tid);
-    }
-    __syncthreads();
   }
+  const int lrow = lane & 31, lhalf = lane >> 5;
+  int a_off[MT][BK / 16], b_off[NT][BK / 16];
+#pragma unroll
+  for (int kk = 0; kk < BK / 16; ++kk) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int row = wm * WM + i * 32 + lrow;
+      a_off[i][kk] = row * 128 + (((kk * 2 + lhalf) ^ swz(row)) << 4);
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int row = wn * WN + j * 32 + lrow;
+      b_off[j][kk] = row * 128 + (((kk * 2 + lhalf) ^ swz(row)) << 4);
+    }
+  }
+  for (int kt0 = 0; kt0 < nk; kt0 += PF) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int kt = kt0 + u;
+      if (kt >= nk) break;
+      unsigned char* sA = lds + (kt & 1) * STAGE;
+      unsigned char* sB = sA + A_BYTES;
+      // the stage written here was last read two steps ago; every wave has passed the barrier of
+      // the step in between, so nobody still reads it
+      la.store(sA, kt * BK, va[u]);
+      lb.store(sB, kt * BK, vb[u]);
+      add_colsum(vb[u], kt * BK);
+      if (kt + PF < nk) {
+        la.load((kt + PF) * BK, va[u]);
+        lb.load((kt + PF) * BK, vb[u]);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        bf16x8_t af[MT], bfr[NT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(sA + a_off[i][kk]);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(sB + b_off[j][kk]);
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+  __syncthreads();
 
   if (CS && !KCB && BN == 128) {
     if (do_cs) {  // uniform over the workgroup; LDS is free after the loop's last barrier
@@ -316,42 +357,82 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     }
   }
 
-  // epilogue: lane holds column n = .. + lane%32 and rows 8*(r/4) + 4*(lane/32) + r%4 of each tile
+  // Epilogue.  In the accumulator a lane holds one column (lane % 32) and rows
+  // 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 tile: storing from there would write 2- or 4-byte
+  // pieces.  Each wavefront instead passes 32 rows at a time through its own LDS patch and then
+  // handles 8 consecutive columns of one row per lane: bias, mask and residual are 16/32-byte
+  // loads and the result leaves as one 16-byte (bf16) or two 16-byte (fp32) stores.
+  constexpr int PW = WN + 4;                       // patch row stride in floats
+  float* patch = reinterpret_cast<float*>(lds) + wave * 32 * PW;   // (the loop's last barrier has passed)
+  static_assert(4 * 32 * PW * 4 <= 2 * STAGE, "epilogue patch fits the tile buffers");
+  if (CS && !KCB && BN == 128) __syncthreads();    // the column-sum scratch above used the same memory
 #pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    const int n = n0 + wn * WN + j * 32 + lrow;
-    if (n >= p.N) continue;
-    int64_t cbase = n; 
-    if (p.c_split) { const int sg = n / p.c_split; cbase = (int64_t)sg * p.c_seg_stride + (n - sg * p.c_split); }
-    float bias = 0.f;
-    if (p.bias) {
-      if (p.bias_split) { const int sg = n / p.bias_split; bias = p.bias[(int64_t)sg * p.bias_seg_stride + (n - sg * p.bias_split)]; }
-      else bias = p.bias[n];
-    }
+  for (int i = 0; i < MT; ++i) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-        if (m >= p.M) continue;
-        float v = acc[i][j][r] + bias;
-        if (p.relu) v = fmaxf(v, 0.f);
-        if (p.relu_mask) {
-          if (!(bf16_to_f32(((const bf16_t*)p.relu_mask)[(int64_t)m * p.ldm + n]) > 0.f)) v = 0.f;
+      for (int r = 0; r < 16; ++r)
+        patch[(8 * (r >> 2) + 4 * lhalf + (r & 3)) * PW + j * 32 + lrow] = acc[i][j][r];
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < WN / 16; ++it) {
+      const int q = lane + 64 * it;
+      const int row = q / (WN / 8), c8 = q % (WN / 8);
+      const int m = m0 + wm * WM + i * 32 + row;
+      const int n = n0 + wn * WN + c8 * 8;
+      if (m < p.M && n < p.N) {
+        const float4 lo = *reinterpret_cast<const float4*>(patch + row * PW + c8 * 8);
+        const float4 hi = *reinterpret_cast<const float4*>(patch + row * PW + c8 * 8 + 4);
+        float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        if (p.bias) {
+          const float* bp = p.bias + n;
+          if (p.bias_split) { const int sg = n / p.bias_split; bp = p.bias + (int64_t)sg * p.bias_seg_stride + (n - sg * p.bias_split); }
+          const float4 b0 = *reinterpret_cast<const float4*>(bp), b1 = *reinterpret_cast<const float4*>(bp + 4);
+          v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w; v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
         }
-        if (p.residual) v += p.residual[cbase + (int64_t)m * p.ldr];
+        if (p.relu) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+        }
+        if (p.relu_mask) {
+          const uint4 mk = *reinterpret_cast<const uint4*>((const bf16_t*)p.relu_mask + (int64_t)m * p.ldm + n);
+          const uint32_t* mw = &mk.x;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (!(__uint_as_float(mw[e] << 16) > 0.f)) v[2 * e] = 0.f;
+            if (!(__uint_as_float(mw[e] & 0xffff0000u) > 0.f)) v[2 * e + 1] = 0.f;
+          }
+        }
+        int64_t cbase = n;
+        if (p.c_split) { const int sg = n / p.c_split; cbase = (int64_t)sg * p.c_seg_stride + (n - sg * p.c_split); }
+        if (p.residual) {
+          const float* rp = p.residual + cbase + (int64_t)m * p.ldr;
+          const float4 r0 = *reinterpret_cast<const float4*>(rp), r1 = *reinterpret_cast<const float4*>(rp + 4);
+          v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w; v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
+        }
         const int64_t off = cbase + (int64_t)m * p.ldc;
-        if (p.out_f32) ((float*)p.C)[off] = v;
-        else ((bf16_t*)p.C)[off] = f32_to_bf16(v);
+        if (p.out_f32) {
+          float* cp = (float*)p.C + off;
+          *reinterpret_cast<float4*>(cp) = make_float4(v[0], v[1], v[2], v[3]);
+          *reinterpret_cast<float4*>(cp + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        } else {
+          uint4 o;
+          o.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+          o.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+          o.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
+          o.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+          *reinterpret_cast<uint4*>((bf16_t*)p.C + off) = o;
+        }
       }
     }
+    __syncthreads();
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool KCA, bool KCB>
+template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF>
 __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
-  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB>(p, blockIdx.y * BM, blockIdx.x * BN, lds);
+  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, PF>(p, blockIdx.y * BM, blockIdx.x * BN, lds);
 }
 
 // Many independent problems of one layout in one launch: workgroup -> (problem, tile) through a
@@ -380,10 +461,10 @@ __global__ void __launch_bounds__(256) gemm_mfma_grouped_kernel(const GemmParams
   const int tiles_m = (prm.M + BM - 1) / BM;
   const int tm = local_tile % tiles_m, tn = local_tile / tiles_m;
   (void)tiles_n;
-  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, true>(prm, tm * BM, tn * BN, lds);
+  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, 1, true>(prm, tm * BM, tn * BN, lds);
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int PF>
 void launch_mfma_cfg(hipStream_t st, const GemmParams& p) {
   dim3 grid((p.N + BN - 1) / BN, (p.M + BM - 1) / BM);
   constexpr int LDS = 2 * (BM + BN) * 128;
@@ -392,11 +473,11 @@ void launch_mfma_cfg(hipStream_t st, const GemmParams& p) {
   do {                                                                                              \
     static bool attr_set = false;                                                                   \
     if (!attr_set) {                                                                                \
-      hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, WM, WN, KA, KB>,                    \
+      hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF>,                \
                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);                         \
       attr_set = true;                                                                              \
     }                                                                                               \
-    gemm_mfma_kernel<BM, BN, WM, WN, KA, KB><<<grid, 256, LDS, st>>>(p);                            \
+    gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF><<<grid, 256, LDS, st>>>(p);                        \
   } while (0)
   if (kca && kcb) MM_GO(true, true);
   else if (kca && !kcb) MM_GO(true, false);
@@ -414,6 +495,13 @@ bool mfma_eligible(const GemmParams& p) {
   if (!p.transA ? p.K % 8 : p.M % 8) return false;       // A's contiguous extent
   if (p.transB ? p.K % 8 : p.N % 8) return false;        // B's contiguous extent
   if (p.b_split && (p.b_split % 8 || p.b_seg_stride % 8)) return false;
+  if (p.b_split && p.b_split_on_k && (!p.transB || p.b_split % 64)) return false;  // k segments: whole K steps
+  // the epilogue moves 8 columns at a time
+  if (p.N % 8 || p.ldc % 8 || !aligned16(p.C)) return false;
+  if (p.c_split && (p.c_split % 8 || p.c_seg_stride % 8)) return false;
+  if (p.bias && (!aligned16(p.bias) || (p.bias_split && (p.bias_split % 8 || p.bias_seg_stride % 4)))) return false;
+  if (p.residual && (!aligned16(p.residual) || p.ldr % 4)) return false;
+  if (p.relu_mask && (!aligned16(p.relu_mask) || p.ldm % 8)) return false;
   return true;
 }
 
@@ -439,6 +527,23 @@ void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const i
                                                                                           n_problems);
 }
 
+// Tuning hook: run one named tile configuration of the MFMA kernel.
+bool launch_gemm_variant(hipStream_t st, const GemmParams& p, int variant) {
+  if (!mfma_eligible(p)) return false;
+  switch (variant) {
+    case 0: launch_mfma_cfg<128, 128, 64, 64, 1>(st, p); return true;
+    case 1: launch_mfma_cfg<128, 128, 64, 64, 2>(st, p); return true;
+    case 2: launch_mfma_cfg<64, 64, 32, 32, 1>(st, p); return true;
+    case 3: launch_mfma_cfg<64, 64, 32, 32, 2>(st, p); return true;
+    case 4: launch_mfma_cfg<64, 64, 32, 32, 4>(st, p); return true;
+    case 5: launch_mfma_cfg<128, 64, 64, 32, 2>(st, p); return true;
+    case 6: launch_mfma_cfg<128, 64, 64, 32, 3>(st, p); return true;
+    case 7: launch_mfma_cfg<64, 128, 32, 64, 2>(st, p); return true;
+    case 8: launch_mfma_cfg<128, 128, 64, 64, 4>(st, p); return true;
+    default: return false;
+  }
+}
+
 void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p) {
   if (p.M <= 0 || p.N <= 0) return;
   dim3 grid((p.N + SB - 1) / SB, (p.M + SB - 1) / SB);
@@ -450,8 +555,8 @@ void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p) {
   if (p.M <= 0 || p.N <= 0) return;
   if (dt == BF16 && mfma_eligible(p)) {
     const long tiles_big = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
-    if (tiles_big >= 192) launch_mfma_cfg<128, 128, 64, 64>(st, p);
-    else launch_mfma_cfg<64, 64, 32, 32>(st, p);
+    if (tiles_big >= 192) launch_mfma_cfg<128, 128, 64, 64, 1>(st, p);
+    else launch_mfma_cfg<64, 64, 32, 32, 1>(st, p);
     return;
   }
   launch_gemm_simt(st, dt, p);

@@ -64,6 +64,8 @@ bool gemm_groupable(Dtype dt, const GemmParams& p);
 int gemm_grouped_tiles(const GemmParams& p);
 void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const int32_t* tile_start_dev,
                             int n_problems, int total_tiles);
+// Tuning hook: one named tile configuration of the MFMA kernel; false if the shape is not eligible.
+bool launch_gemm_variant(hipStream_t st, const GemmParams& p, int variant);
 // Same contract, always the plain FMA kernel (cross-check of the MFMA path).
 void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p);
 
