@@ -306,7 +306,7 @@ __device__ __forceinline__ bf16x8_t frag_from_regs(const float* v) {
 }
 
 template <int NKT>
-__global__ void __launch_bounds__(256) attn_fwd_mfma_kernel(const AttnParams p) {
+__global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int b = blockIdx.x / p.H, h = blockIdx.x % p.H;
   const int q0 = p.cu_q[b], lq = p.cu_q[b + 1] - q0;
@@ -418,7 +418,7 @@ inline size_t mfma_fwd_lds(int max_lk) {
 // dV^T += dO^T P and dK^T += Q^T dS.  Each phase keeps its A operands in LDS (natural and
 // transposed tiles) and takes its B operands straight from global memory (its own 32 rows) or
 // from the accumulators of the previous product.
-__global__ void __launch_bounds__(256) attn_bwd_mfma_kernel(const AttnParams p) {
+__global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int b = blockIdx.x / p.H, h = blockIdx.x % p.H;
   const int q0 = p.cu_q[b], lq = p.cu_q[b + 1] - q0;

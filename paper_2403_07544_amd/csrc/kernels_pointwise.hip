@@ -147,22 +147,58 @@ __global__ void __launch_bounds__(1024) sort_keys_kernel(const int32_t* __restri
   for (int i = threadIdx.x; i < n_pow2; i += blockDim.x) keys[i] = sk[i];
 }
 
+// Two passes so that the run of the most frequent token (hundreds of rows under a Zipf law) is not
+// one workgroup's serial loop.  Pass 1: runs are cut into chunks of EG_CHUNK sorted positions; the
+// workgroup at a chunk's first position adds the chunk's rows (4 waves, fixed order).  A run that
+// is a single chunk goes straight into the bucket; otherwise the chunk sum is parked in
+// partial[position].  Pass 2: the workgroup at a multi-chunk run's first position adds the run's
+// chunk sums in ascending order and updates the bucket.
+constexpr int EG_CHUNK = 32;
+
+template <int NV>
+__device__ __forceinline__ void eg_block_reduce(float4 (&acc)[NV], float (*red)[NV * 256], int wave, int lane) {
+  if (wave > 0) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      float* r = &red[wave - 1][v * 256 + (lane << 2)];
+      r[0] = acc[v].x; r[1] = acc[v].y; r[2] = acc[v].z; r[3] = acc[v].w;
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+      for (int w = 0; w < 3; ++w) {
+        const float* r = &red[w][v * 256 + (lane << 2)];
+        acc[v].x += r[0]; acc[v].y += r[1]; acc[v].z += r[2]; acc[v].w += r[3];
+      }
+  }
+}
+
 template <int NV>  // float4 chunks per lane: d <= NV * 256
-__global__ void __launch_bounds__(256) embed_grad_kernel(const uint32_t* __restrict__ keys,
-                                                         const float* __restrict__ dx,
-                                                         float* __restrict__ bucket, int rows, int d,
-                                                         float sqrt_d) {
+__global__ void __launch_bounds__(256) embed_grad_chunks_kernel(const uint32_t* __restrict__ keys,
+                                                                const float* __restrict__ dx,
+                                                                float* __restrict__ bucket,
+                                                                float* __restrict__ partial, int rows, int d,
+                                                                float sqrt_d) {
   const int p = blockIdx.x;
   const uint32_t token = keys[p] >> ROW_BITS;
-  if (p > 0 && (keys[p - 1] >> ROW_BITS) == token) return;  // not the head of a run
-  __shared__ int s_end;
+  __shared__ int s_before, s_end;
   __shared__ float red[3][NV * 256];
-  if (threadIdx.x == 0) s_end = rows;
+  if (threadIdx.x == 0) { s_before = -1; s_end = min(rows, p + EG_CHUNK); }
   __syncthreads();
-  for (int q = p + 1 + threadIdx.x; q < rows; q += blockDim.x)
-    if ((keys[q] >> ROW_BITS) != token) { atomicMin(&s_end, q); break; }
+  // last position before p holding another token (keys are sorted: the first mismatch going back)
+  for (int q = p - 1 - (int)threadIdx.x; q >= 0; q -= blockDim.x)
+    if ((keys[q] >> ROW_BITS) != token) { atomicMax(&s_before, q); break; }
+  if (threadIdx.x < EG_CHUNK) {
+    const int q = p + 1 + threadIdx.x;
+    if (q < rows && q < p + EG_CHUNK && (keys[q] >> ROW_BITS) != token) atomicMin(&s_end, q);
+  }
   __syncthreads();
+  const int run_start = s_before + 1;
+  if ((p - run_start) % EG_CHUNK != 0) return;  // not the first position of a chunk (uniform)
   const int end = s_end;
+  const bool whole_run = (p == run_start) && (end >= rows || (keys[end] >> ROW_BITS) != token);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   float4 acc[NV];
 #pragma unroll
@@ -178,27 +214,58 @@ __global__ void __launch_bounds__(256) embed_grad_kernel(const uint32_t* __restr
       }
     }
   }
-  if (wave > 0) {
-#pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      float* r = &red[wave - 1][v * 256 + (lane << 2)];
-      r[0] = acc[v].x; r[1] = acc[v].y; r[2] = acc[v].z; r[3] = acc[v].w;
-    }
-  }
-  __syncthreads();
+  eg_block_reduce<NV>(acc, red, wave, lane);
   if (wave == 0) {
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
       const int c = (lane << 2) + v * 256;
       if (c < d) {
-        float4 s = acc[v];
-        for (int w = 0; w < 3; ++w) {
-          const float* r = &red[w][v * 256 + (lane << 2)];
-          s.x += r[0]; s.y += r[1]; s.z += r[2]; s.w += r[3];
+        if (whole_run) {
+          float* dst = bucket + (int64_t)token * d + c;
+          float4 o = Io<float>::ld4(dst);
+          o.x += sqrt_d * acc[v].x; o.y += sqrt_d * acc[v].y; o.z += sqrt_d * acc[v].z; o.w += sqrt_d * acc[v].w;
+          Io<float>::st4(dst, o);
+        } else {
+          Io<float>::st4(partial + (int64_t)p * d + c, acc[v]);
         }
+      }
+    }
+  }
+}
+
+template <int NV>
+__global__ void __launch_bounds__(256) embed_grad_runs_kernel(const uint32_t* __restrict__ keys,
+                                                              const float* __restrict__ partial,
+                                                              float* __restrict__ bucket, int rows, int d,
+                                                              float sqrt_d) {
+  const int p = blockIdx.x;
+  const uint32_t token = keys[p] >> ROW_BITS;
+  if (p > 0 && (keys[p - 1] >> ROW_BITS) == token) return;                         // not a run head
+  if (p + EG_CHUNK >= rows || (keys[p + EG_CHUNK] >> ROW_BITS) != token) return;   // single chunk: done in pass 1
+  __shared__ float red[3][NV * 256];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float4 acc[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int q = p + wave * EG_CHUNK; q < rows && (keys[q] >> ROW_BITS) == token; q += 4 * EG_CHUNK) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int c = (lane << 2) + v * 256;
+      if (c < d) {
+        const float4 g = Io<float>::ld4(partial + (int64_t)q * d + c);
+        acc[v].x += g.x; acc[v].y += g.y; acc[v].z += g.z; acc[v].w += g.w;
+      }
+    }
+  }
+  eg_block_reduce<NV>(acc, red, wave, lane);
+  if (wave == 0) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int c = (lane << 2) + v * 256;
+      if (c < d) {
         float* dst = bucket + (int64_t)token * d + c;
         float4 o = Io<float>::ld4(dst);
-        o.x += sqrt_d * s.x; o.y += sqrt_d * s.y; o.z += sqrt_d * s.z; o.w += sqrt_d * s.w;
+        o.x += sqrt_d * acc[v].x; o.y += sqrt_d * acc[v].y; o.z += sqrt_d * acc[v].z; o.w += sqrt_d * acc[v].w;
         Io<float>::st4(dst, o);
       }
     }
@@ -367,6 +434,42 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
     float* o;
     if (dst2 && n >= n_first) o = dst2 + (n - n_first);
     else o = split ? dst + (int64_t)(n / split) * seg_stride + (n % split) : dst + n;
+    *o += s;
+  }
+}
+
+// All LayerNorm gain/shift gradients of a step in one launch: job j owns blocks
+// [first_block, first_block + ceil(2d/64)); each block reduces 64 columns of the job's partial
+// rows ([n_partial][2][d]) in the same fixed order as reduce_partials_kernel.
+__global__ void __launch_bounds__(256) ln_reduce_grouped_kernel(const LnReduceJob* __restrict__ jobs, int n_jobs) {
+  __shared__ float red[4][64];
+  int lo = 0, hi = n_jobs - 1;
+  const int blk = blockIdx.x;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (jobs[mid].first_block <= blk) lo = mid; else hi = mid - 1;
+  }
+  const LnReduceJob jb = jobs[lo];
+  const int c = threadIdx.x & 63, r = threadIdx.x >> 6;
+  const int n = (blk - jb.first_block) * 64 + c;
+  const int N = 2 * jb.d;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (n < N) {
+    const float* part = jb.partial + n;
+    int p = r;
+    for (; p + 12 < jb.n_partial; p += 16) {
+      s0 += part[(int64_t)p * N];
+      s1 += part[(int64_t)(p + 4) * N];
+      s2 += part[(int64_t)(p + 8) * N];
+      s3 += part[(int64_t)(p + 12) * N];
+    }
+    for (; p < jb.n_partial; p += 4) s0 += part[(int64_t)p * N];
+  }
+  red[r][c] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (r == 0 && n < N) {
+    const float s = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+    float* o = n < jb.d ? jb.dgamma + n : jb.dbeta + (n - jb.d);
     *o += s;
   }
 }
@@ -552,17 +655,24 @@ void launch_embed_fwd(hipStream_t st, Dtype dt, const void* E, const float* pe, 
     embed_fwd_kernel<float><<<grid, 256, 0, st>>>((const float*)E, pe, tok, pos, x, rows, d, sqrt_d);
 }
 
-void launch_embed_grad(hipStream_t st, const int32_t* tok, const float* dx, float* bucket, uint32_t* keys,
-                       int rows, int d, float sqrt_d) {
+void launch_sort_tokens(hipStream_t st, const int32_t* tok, int rows, uint32_t* keys) {
   int n_pow2 = 64;
   while (n_pow2 < rows) n_pow2 <<= 1;
   sort_keys_kernel<<<1, 1024, n_pow2 * sizeof(uint32_t), st>>>(tok, rows, n_pow2, keys);
+}
+
+void launch_embed_grad(hipStream_t st, const uint32_t* keys, const float* dx, float* bucket, float* partial,
+                       int rows, int d, float sqrt_d) {
+#define MM_EG(NV)                                                                                      \
+  embed_grad_chunks_kernel<NV><<<rows, 256, 0, st>>>(keys, dx, bucket, partial, rows, d, sqrt_d);        \
+  embed_grad_runs_kernel<NV><<<rows, 256, 0, st>>>(keys, partial, bucket, rows, d, sqrt_d);
   switch (nv_for(d)) {
-    case 1: embed_grad_kernel<1><<<rows, 256, 0, st>>>(keys, dx, bucket, rows, d, sqrt_d); break;
-    case 2: embed_grad_kernel<2><<<rows, 256, 0, st>>>(keys, dx, bucket, rows, d, sqrt_d); break;
-    case 4: embed_grad_kernel<4><<<rows, 256, 0, st>>>(keys, dx, bucket, rows, d, sqrt_d); break;
-    default: embed_grad_kernel<8><<<rows, 256, 0, st>>>(keys, dx, bucket, rows, d, sqrt_d); break;
+    case 1: MM_EG(1) break;
+    case 2: MM_EG(2) break;
+    case 4: MM_EG(4) break;
+    default: MM_EG(8) break;
   }
+#undef MM_EG
 }
 
 #define MM_LN_DISPATCH(KERNEL, T, ...)                                        \
@@ -585,12 +695,12 @@ void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float*
 
 int ln_bwd_partial_rows(int rows) {
   const int want = (rows + 3) / 4;
-  return want < 256 ? want : 256;
+  return want < 1024 ? want : 1024;
 }
 
 void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float* x, const float* mean,
                           const float* rstd, const float* gamma, const float* dres, float* dx_out,
-                          void* dxT_out, float* partial, float* dgamma, float* dbeta, int rows, int d) {
+                          void* dxT_out, float* partial, int rows, int d) {
   const int grid = ln_bwd_partial_rows(rows);
   if (dt == BF16) {
     MM_LN_DISPATCH(layernorm_bwd_kernel, bf16_t, dy, x, mean, rstd, gamma, dres, dx_out, (bf16_t*)dxT_out,
@@ -599,8 +709,10 @@ void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float
     MM_LN_DISPATCH(layernorm_bwd_kernel, float, dy, x, mean, rstd, gamma, dres, dx_out, (float*)nullptr,
                    partial, rows, d)
   }
-  reduce_partials_kernel<<<(2 * d + 63) / 64, 256, 0, st>>>(partial, grid, 2 * (int64_t)d, 2 * d, dgamma, 0, 0,
-                                                            dbeta, d);
+}
+
+void launch_ln_reduce_grouped(hipStream_t st, const LnReduceJob* jobs_dev, int n_jobs, int total_blocks) {
+  if (n_jobs > 0) ln_reduce_grouped_kernel<<<total_blocks, 256, 0, st>>>(jobs_dev, n_jobs);
 }
 
 int colsum_partial_rows(int M) {

@@ -84,10 +84,13 @@ void launch_mask_dump(hipStream_t st, const int32_t* cu_q, const int32_t* cu_k, 
 // x[row,:] = sqrt_d * E[tok[row],:] + pe[pos[row],:]   (multiply, then add; fp32 out)
 void launch_embed_fwd(hipStream_t st, Dtype dt, const void* E, const float* pe, const int32_t* tok,
                       const int32_t* pos, float* x, int rows, int d, float sqrt_d);
-// bucket[tok,:] += sqrt_d * sum over rows with that token of dx[row,:]; deterministic.
-// keys: scratch uint32 [pow2 >= rows].
-void launch_embed_grad(hipStream_t st, const int32_t* tok, const float* dx, float* bucket,
-                       uint32_t* keys, int rows, int d, float sqrt_d);
+// keys[i] = (token << 14 | row), sorted ascending; keys holds the next power of two >= rows entries
+// (at least 64).  Depends on the token ids only, so it can run ahead of the step on another stream.
+void launch_sort_tokens(hipStream_t st, const int32_t* tok, int rows, uint32_t* keys);
+// bucket[tok,:] += sqrt_d * sum over rows with that token of dx[row,:]; deterministic (fixed
+// summation order, no atomics).  partial: scratch float [rows, d].
+void launch_embed_grad(hipStream_t st, const uint32_t* keys, const float* dx, float* bucket,
+                       float* partial, int rows, int d, float sqrt_d);
 
 // ---------------------------------------------------------------------------------------------
 // LayerNorm over the last axis, one row per wavefront
@@ -95,13 +98,20 @@ void launch_embed_grad(hipStream_t st, const int32_t* tok, const float* dx, floa
 void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float* gamma,
                           const float* beta, void* y, float* mean, float* rstd, int rows, int d,
                           float eps);
-// dx_out = dres + LN'(dy);  dxT_out (working dtype, may be null) = same, rounded;
-// dgamma/dbeta (bucket slices) += column sums.  partial: scratch float [ln_bwd_partial_rows() * 2 * d].
+// dx_out = dres + LN'(dy);  dxT_out (working dtype, may be null) = same, rounded.
+// The column sums for the gain and shift gradients leave as ln_bwd_partial_rows(rows) partial
+// rows, partial[p][0][d] (gain) and partial[p][1][d] (shift); launch_ln_reduce_grouped adds them
+// into the buckets for many LayerNorms at once.
 int ln_bwd_partial_rows(int rows);
 void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float* x,
                           const float* mean, const float* rstd, const float* gamma,
                           const float* dres, float* dx_out, void* dxT_out, float* partial,
-                          float* dgamma, float* dbeta, int rows, int d);
+                          int rows, int d);
+struct LnReduceJob {
+  const float* partial; float* dgamma; float* dbeta;
+  int32_t n_partial, d, first_block, pad;   // first_block: running sum of ceil(2d/64)
+};
+void launch_ln_reduce_grouped(hipStream_t st, const LnReduceJob* jobs_dev, int n_jobs, int total_blocks);
 
 // dst[n] += sum_m Y[m,n]; Y is fp32 (y_f32=1) or working dtype; dst segmented like GemmParams C.
 int colsum_partial_rows(int M);

@@ -51,6 +51,7 @@ struct Arena {
 };
 
 struct ProfRec { int cls; hipEvent_t a, b; };
+constexpr int MAX_GROUPED_C = 1024;
 
 }  // namespace
 
@@ -67,7 +68,9 @@ struct mm_ctx {
   int32_t* meta = nullptr;                   // cu_s, cu_u, lens, src_tok, src_pos, dec_tok, dec_pos, label
   int32_t *cu_s = nullptr, *cu_u = nullptr, *lens = nullptr, *src_tok = nullptr, *src_pos = nullptr,
           *dec_tok = nullptr, *dec_pos = nullptr, *label = nullptr;
-  uint32_t* sort_keys = nullptr;
+  uint32_t* sort_keys = nullptr;              // [2][16384]: sorted (token,row) keys of source / decoder rows
+  hipStream_t aux = nullptr;                  // side stream: the token sorts run beside the forward pass
+  hipEvent_t ev_packed = nullptr, ev_sorted = nullptr;
   int32_t* flag = nullptr;                   // device: id-check result of the step
   float* loss_dev = nullptr;
   int32_t* ids_dev = nullptr; size_t ids_dev_cap = 0;      // staged copies of host ids
@@ -79,6 +82,7 @@ struct mm_ctx {
   // table of the step's deferred weight-gradient products (pinned host copy, device copy)
   GemmParams* gtab_host = nullptr; GemmParams* gtab_dev = nullptr;
   int32_t* gstart_host = nullptr; int32_t* gstart_dev = nullptr;
+  LnReduceJob* ljob_host = nullptr; LnReduceJob* ljob_dev = nullptr;
   hipEvent_t ev_gtab = nullptr;
   Arena ws;
   // last step
@@ -185,14 +189,37 @@ struct Run {
     launch_layernorm_fwd(c->st, c->dt, x, g, b, y, mean, rstd, rows, d, c->cfg.ln_eps);
     end();
   }
+  // The gain/shift gradient sums of all LayerNorms of the step are reduced in one launch at the end.
+  std::vector<LnReduceJob>* ln_jobs = nullptr;
   void ln_bwd(const float* dy, const float* x, const float* mean, const float* rstd, const float* g,
-              const float* dres, float* dx, void* dxT, float* partial, float* gg, float* gb, int rows) {
-    if (dry) return;
+              const float* dres, float* dx, void* dxT, float* gg, float* gb, int rows) {
     const int d = c->cfg.d_model;
+    const int n_partial = ln_bwd_partial_rows(rows);
+    float* partial = (float*)c->ws.take((size_t)n_partial * 2 * d * sizeof(float));
+    if (dry) return;
     begin(MM_K_LAYERNORM_BWD, (double)rows * d * (12 + (dres ? 4 : 0) + (c->dt == BF16 ? 2 : 0)));
     launch_layernorm_bwd(c->st, c->dt, dy, x, mean, rstd, g, dres, dx, c->dt == BF16 ? dxT : nullptr,
-                         partial, gg, gb, rows, d);
+                         partial, rows, d);
     end();
+    LnReduceJob jb;
+    jb.partial = partial; jb.dgamma = gg; jb.dbeta = gb; jb.n_partial = n_partial; jb.d = d;
+    jb.first_block = 0; jb.pad = 0;
+    ln_jobs->push_back(jb);
+  }
+  void flush_ln_jobs() {
+    if (dry || ln_jobs->empty()) return;
+    int blocks = 0;
+    size_t n = ln_jobs->size() < (size_t)MAX_GROUPED_C ? ln_jobs->size() : (size_t)MAX_GROUPED_C;
+    for (size_t i = 0; i < n; ++i) {
+      (*ln_jobs)[i].first_block = blocks;
+      blocks += (2 * (*ln_jobs)[i].d + 63) / 64;
+      c->ljob_host[i] = (*ln_jobs)[i];
+    }
+    hipMemcpyAsync(c->ljob_dev, c->ljob_host, n * sizeof(LnReduceJob), hipMemcpyHostToDevice, c->st);
+    begin(MM_K_LAYERNORM_BWD, 0.0);
+    launch_ln_reduce_grouped(c->st, c->ljob_dev, (int)n, blocks);
+    end();
+    ln_jobs->clear();
   }
   void colsum(const void* Y, int y_f32, int64_t ldy, int M, int N, float* partial, float* dst, int split,
               int64_t seg) {
@@ -389,7 +416,7 @@ struct Step {
     p.out_f32 = 1;
     run.gemm(p);
     wgrad(gp_wgrad(s.a, d, dh, hidden, pv.G(t0 + 2), d, hidden, R), pv.G(t0 + 3), nullptr);
-    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, partial, pv.G(t0), pv.G(t0 + 1), R);
+    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, pv.G(t0), pv.G(t0 + 1), R);
     if (c->dt != BF16) out.dxT = out.dx;
     return out;
   }
@@ -416,7 +443,7 @@ struct Step {
     p = gp_wgrad(s.a, d, dqkv, 3 * d, pv.G(t0 + 2), d, 3 * d, R);
     p.ldc = d; p.ldr = d; p.c_split = d; p.c_seg_stride = seg;
     wgrad(p, pv.G(t0 + 3), nullptr);
-    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, partial, pv.G(t0), pv.G(t0 + 1), R);
+    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, pv.G(t0), pv.G(t0 + 1), R);
     if (c->dt != BF16) out.dxT = out.dx;
     return out;
   }
@@ -449,7 +476,7 @@ struct Step {
     p = gp_wgrad(mem, d, dkv, 2 * d, pv.G(t0 + 4), d, 2 * d, S);
     p.ldc = d; p.ldr = d; p.c_split = d; p.c_seg_stride = seg;
     wgrad(p, pv.G(t0 + 5), nullptr);
-    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, partial, pv.G(t0), pv.G(t0 + 1), U);
+    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, pv.G(t0), pv.G(t0 + 1), U);
     if (c->dt != BF16) out.dxT = out.dx;
     return out;
   }
@@ -544,10 +571,12 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
   }
   const int d = s.d, S = s.S, U = s.U, V = s.V;
   Run& run = s.run;
+  std::vector<LnReduceJob> ln_jobs;
+  run.ln_jobs = &ln_jobs;
   c->ws.reset(dry);
   const int Rmax = S > U ? S : U;
   {
-    size_t pn = (size_t)ln_bwd_partial_rows(Rmax) * 2 * d;
+    size_t pn = 0;
     const int widest = std::max(std::max(3 * d, s.F), V);
     const size_t pc = (size_t)colsum_partial_rows(Rmax) * widest;
     s.partial = s.f32(pn > pc ? pn : pc);
@@ -651,7 +680,7 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
     s.wgrad(s.gp_wgrad(h, d, z, V, pv_gen.G(0), d, V, U), pv_gen.G(1), nullptr);
   }
   Step::Grad g{s.f32((size_t)U * d), c->dt == BF16 ? s.act((size_t)U * d) : nullptr};
-  run.ln_bwd(dh, y_dec_top, ln_decf.mean, ln_decf.rstd, pv_decf.V(0), nullptr, g.dx, g.dxT, s.partial,
+  run.ln_bwd(dh, y_dec_top, ln_decf.mean, ln_decf.rstd, pv_decf.V(0), nullptr, g.dx, g.dxT,
              pv_decf.G(0), pv_decf.G(1), U);
   if (c->dt != BF16) g.dxT = g.dx;
   float* dmem = s.f32((size_t)S * d);
@@ -664,15 +693,17 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
     first = false;
     g = s.self_bwd(ls.pv, 0, ls.self, g, U, true);
   }
+  float* eg_partial = s.f32((size_t)Rmax * d);
   if (!dry) {
+    hipStreamWaitEvent(c->st, c->ev_sorted, 0);  // the side stream's token sorts
     run.begin(MM_K_EMBED_GRAD, (double)U * d * 12);
-    launch_embed_grad(c->st, c->dec_tok, g.dx, m_tgt.g, c->sort_keys, U, d, sqrt_d);
+    launch_embed_grad(c->st, c->sort_keys + 16384, g.dx, m_tgt.g, eg_partial, U, d, sqrt_d);
     run.end();
   }
 
   // ---------------- backward: encoder ----------------
   Step::Grad ge{s.f32((size_t)S * d), c->dt == BF16 ? s.act((size_t)S * d) : nullptr};
-  run.ln_bwd(dmem, x_enc_top, ln_encf.mean, ln_encf.rstd, pv_encf.V(0), nullptr, ge.dx, ge.dxT, s.partial,
+  run.ln_bwd(dmem, x_enc_top, ln_encf.mean, ln_encf.rstd, pv_encf.V(0), nullptr, ge.dx, ge.dxT,
              pv_encf.G(0), pv_encf.G(1), S);
   if (c->dt != BF16) ge.dxT = ge.dx;
   for (int i = (int)enc_saves.size() - 1; i >= 0; --i) {
@@ -683,10 +714,11 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
   }
   if (!dry) {
     run.begin(MM_K_EMBED_GRAD, (double)S * d * 12);
-    launch_embed_grad(c->st, c->src_tok, ge.dx, m_src.g, c->sort_keys, S, d, sqrt_d);
+    launch_embed_grad(c->st, c->sort_keys, ge.dx, m_src.g, eg_partial, S, d, sqrt_d);
     run.end();
   }
   s.flush_wgrads();
+  s.run.flush_ln_jobs();
 }
 
 bool valid_module(mm_ctx* c, int id) { return id >= 0 && id < (int)c->mods.size(); }
@@ -787,7 +819,10 @@ mm_status mm_create(const mm_config* cfg, mm_ctx** out) {
   };
   guard(hipMalloc((void**)&c->pe, pe.size() * 4), "hipMalloc(pe)");
   guard(hipMalloc((void**)&c->meta, meta_ints * 4), "hipMalloc(meta)");
-  guard(hipMalloc((void**)&c->sort_keys, 16384 * 4), "hipMalloc(sort keys)");
+  guard(hipMalloc((void**)&c->sort_keys, 2 * 16384 * 4), "hipMalloc(sort keys)");
+  guard(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking), "hipStreamCreate");
+  guard(hipEventCreateWithFlags(&c->ev_packed, hipEventDisableTiming), "hipEventCreate");
+  guard(hipEventCreateWithFlags(&c->ev_sorted, hipEventDisableTiming), "hipEventCreate");
   guard(hipMalloc((void**)&c->flag, 64), "hipMalloc(flag)");
   guard(hipMalloc((void**)&c->loss_dev, 64), "hipMalloc(loss)");
   guard(hipHostMalloc((void**)&c->result_host, 64, hipHostMallocDefault), "hipHostMalloc(result)");
@@ -799,6 +834,8 @@ mm_status mm_create(const mm_config* cfg, mm_ctx** out) {
   guard(hipHostMalloc((void**)&c->gstart_host, MAX_GROUPED * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(table)");
   guard(hipMalloc((void**)&c->gtab_dev, MAX_GROUPED * sizeof(GemmParams)), "hipMalloc(table)");
   guard(hipMalloc((void**)&c->gstart_dev, MAX_GROUPED * sizeof(int32_t)), "hipMalloc(table)");
+  guard(hipHostMalloc((void**)&c->ljob_host, MAX_GROUPED_C * sizeof(LnReduceJob), hipHostMallocDefault), "hipHostMalloc(table)");
+  guard(hipMalloc((void**)&c->ljob_dev, MAX_GROUPED_C * sizeof(LnReduceJob)), "hipMalloc(table)");
   if (s != MM_OK) return s;
   guard(hipMemcpy(c->pe, pe.data(), pe.size() * 4, hipMemcpyHostToDevice), "hipMemcpy(pe)");
   guard(hipMemset(c->flag, 0, 64), "hipMemset");
@@ -827,10 +864,15 @@ mm_status mm_destroy(mm_ctx* c) {
     if (c->ev_done) hipEventDestroy(c->ev_done);
     if (c->ev_seg) hipEventDestroy(c->ev_seg);
     if (c->ev_gtab) hipEventDestroy(c->ev_gtab);
+    if (c->aux) { hipStreamSynchronize(c->aux); hipStreamDestroy(c->aux); }
+    if (c->ev_packed) hipEventDestroy(c->ev_packed);
+    if (c->ev_sorted) hipEventDestroy(c->ev_sorted);
     if (c->gtab_host) hipHostFree(c->gtab_host);
     if (c->gstart_host) hipHostFree(c->gstart_host);
     if (c->gtab_dev) hipFree(c->gtab_dev);
     if (c->gstart_dev) hipFree(c->gstart_dev);
+    if (c->ljob_host) hipHostFree(c->ljob_host);
+    if (c->ljob_dev) hipFree(c->ljob_dev);
   }
   delete c;
   return MM_OK;
@@ -974,6 +1016,12 @@ mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const i
   launch_fill_i32(c->st, c->flag, 1, 0);
   launch_pack_ids(c->st, src_dev, tgt_dev, c->lens, c->cu_s, c->cu_u, B, S_max, T_max, c->cfg.vocab, c->src_tok,
                   c->src_pos, c->dec_tok, c->dec_pos, c->label, c->flag);
+  // the two token sorts need only the packed ids: they run on the side stream during the forward pass
+  HIP_TRY(c, hipEventRecord(c->ev_packed, c->st));
+  HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_packed, 0));
+  launch_sort_tokens(c->aux, c->src_tok, (int)S, c->sort_keys);
+  launch_sort_tokens(c->aux, c->dec_tok, (int)U, c->sort_keys + 16384);
+  HIP_TRY(c, hipEventRecord(c->ev_sorted, c->aux));
   run_step(c, rt, false, lengths);
   HIP_TRY(c, hipGetLastError());
   HIP_TRY(c, hipMemcpyAsync(&c->result_host[0], c->loss_dev, 4, hipMemcpyDeviceToHost, c->st));
