@@ -7,6 +7,8 @@
 //   gemm_mfma_kernel : bf16 MFMA kernel, LDS-staged 128x128 or 64x64 tiles.
 #include "mm_kernels.h"
 
+#include <type_traits>
+
 namespace mm {
 namespace {
 
@@ -129,7 +131,14 @@ __device__ __forceinline__ u32x4_t load16_global(const bf16_t* a) {
   return *reinterpret_cast<global_u4_ptr>(addr);
 }
 
-__device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row >> 4) & 3); }
+// Tells the compiler a value is the same in every lane (it then lives in scalar registers).
+__device__ __forceinline__ uint64_t uniform64(uint64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 7); }
 
 // Loads one operand tile (R rows x 64 k) from global memory into registers, then into LDS.
 // KC: operand is k-contiguous in memory (element (row,k) at base + row*ld + k), else
@@ -146,13 +155,18 @@ struct TileLoader {
   int64_t ld;
   int ksplit; int64_t seg_stride;  // KC only: segments along k (multiple of 64)
   const bf16_t* safe;              // any valid address: out-of-range items read it and are zeroed
+  // fast path (tile fully inside the operand, K a multiple of 64, operand spans < 2 GiB): a
+  // wave-uniform base pointer plus one 32-bit byte offset per item; a K step only moves the base
+  const char* ubase;
+  uint32_t voff[NL];
 
   __device__ __forceinline__ void init(const bf16_t* base, int64_t ld_, int row0, int row_lim, int K, int split,
                                        int split_on_k, int64_t seg_stride_, int tid) {
-    ld = ld_;
+    ld = (int64_t)uniform64((uint64_t)ld_);
     safe = base;
-    ksplit = (KC && split && split_on_k) ? split : 0;
-    seg_stride = seg_stride_;
+    ubase = reinterpret_cast<const char*>(uniform64(reinterpret_cast<uint64_t>(base)));
+    ksplit = (KC && split && split_on_k) ? __builtin_amdgcn_readfirstlane(split) : 0;
+    seg_stride = (int64_t)uniform64((uint64_t)seg_stride_);
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       const int q = tid + 256 * i;
@@ -163,6 +177,7 @@ struct TileLoader {
         int rl = gr;
         if (split && !split_on_k) { const int sg = gr / split; rl = gr - sg * split; b += (int64_t)sg * seg_stride_; }
         ptr[i] = b + (int64_t)rl * ld_ + c * 8;
+        voff[i] = (uint32_t)((ptr[i] - base) * 2);
         klim[i] = gr < row_lim ? K - c * 8 : 0;
         off[i] = row * 128 + ((c ^ swz(row)) << 4);
       } else {
@@ -172,6 +187,7 @@ struct TileLoader {
         int cl = gc;
         if (split && !split_on_k) { const int sg = gc / split; cl = gc - sg * split; b += (int64_t)sg * seg_stride_; }
         ptr[i] = b + (int64_t)(kq * 4) * ld_ + cl;
+        voff[i] = kq < 16 ? (uint32_t)((ptr[i] - base) * 2) : 0u;
         klim[i] = (gc < row_lim && kq < 16) ? K - kq * 4 : 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -199,6 +215,47 @@ struct TileLoader {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           v[i * 4 + j] = load16_global(k0 + j < klim[i] ? p0 + (int64_t)j * ld : safe);
+        }
+      }
+    }
+  }
+
+  __device__ __forceinline__ void load_fast(int k0, u32x4_t (&v)[NV]) const {
+    if (KC) {
+      int64_t koff = k0;
+      if (ksplit) { const int sg = k0 / ksplit; koff = (int64_t)sg * seg_stride + (k0 - sg * ksplit); }
+      const char* b = ubase + koff * 2;
+#pragma unroll
+      for (int i = 0; i < NL; ++i) v[i] = *(global_u4_ptr)(b + voff[i]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const char* b = ubase + ((int64_t)(k0 + j) * ld) * 2;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) v[i * 4 + j] = *(global_u4_ptr)(b + voff[i]);
+      }
+    }
+  }
+
+  __device__ __forceinline__ void store_fast(unsigned char* lds, const u32x4_t (&v)[NV]) const {
+    if (KC) {
+#pragma unroll
+      for (int i = 0; i < NL; ++i) *reinterpret_cast<u32x4_t*>(lds + off[i]) = v[i];
+    } else {
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        if (off[i * 8] < 0) continue;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          uint2 o;
+          if (e & 1) {
+            o.x = (v[i * 4 + 0][e >> 1] >> 16) | (v[i * 4 + 1][e >> 1] & 0xffff0000u);
+            o.y = (v[i * 4 + 2][e >> 1] >> 16) | (v[i * 4 + 3][e >> 1] & 0xffff0000u);
+          } else {
+            o.x = (v[i * 4 + 0][e >> 1] & 0xffffu) | (v[i * 4 + 1][e >> 1] << 16);
+            o.y = (v[i * 4 + 2][e >> 1] & 0xffffu) | (v[i * 4 + 3][e >> 1] << 16);
+          }
+          *reinterpret_cast<uint2*>(lds + off[i * 8 + e]) = o;
         }
       }
     }
@@ -260,9 +317,9 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
 
   float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const bool do_cs = CS && p.colsum_dst != nullptr && m0 == 0;
-  u32x4_t va[PF][TileLoader<BM, KCA>::NV];
-  u32x4_t vb[PF][TileLoader<BN, KCB>::NV];
-  auto add_colsum = [&](const u32x4_t (&v)[TileLoader<BN, KCB>::NV], int k0) {
+  u32x4_t va[TileLoader<BM, KCA>::NV];
+  u32x4_t vb[TileLoader<BN, KCB>::NV];
+  auto add_colsum = [&](int k0) {
     if (CS && !KCB && BN == 128) {
       if (do_cs) {
 #pragma unroll
@@ -270,8 +327,8 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
           if (k0 + j < lb.klim[0]) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              cs[2 * e] += __uint_as_float(v[j][e] << 16);
-              cs[2 * e + 1] += __uint_as_float(v[j][e] & 0xffff0000u);
+              cs[2 * e] += __uint_as_float(vb[j][e] << 16);
+              cs[2 * e + 1] += __uint_as_float(vb[j][e] & 0xffff0000u);
             }
           }
         }
@@ -280,13 +337,6 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   };
 
   const int nk = (p.K + BK - 1) / BK;
-#pragma unroll
-  for (int u = 0; u < PF; ++u) {
-    if (u < nk) {
-      la.load(u * BK, va[u]);
-      lb.load(u * BK, vb[u]);
-    }
-  }
   const int lrow = lane & 31, lhalf = lane >> 5;
   int a_off[MT][BK / 16], b_off[NT][BK / 16];
 #pragma unroll
@@ -299,40 +349,64 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
       const int row = wn * WN + j * 32 + lrow;
-      b_off[j][kk] = row * 128 + (((kk * 2 + lhalf) ^ swz(row)) << 4);
+      b_off[j][kk] = A_BYTES + row * 128 + (((kk * 2 + lhalf) ^ swz(row)) << 4);
     }
   }
-  for (int kt0 = 0; kt0 < nk; kt0 += PF) {
+  // multiply the tile pair sitting in LDS stage `stage` (compile-time: the stage offset folds
+  // into the ds_read instructions' immediate field)
+  auto compute = [&](auto stage_tag) {
+    constexpr int SOFF = decltype(stage_tag)::value * STAGE;
 #pragma unroll
-    for (int u = 0; u < PF; ++u) {
-      const int kt = kt0 + u;
-      if (kt >= nk) break;
-      unsigned char* sA = lds + (kt & 1) * STAGE;
-      unsigned char* sB = sA + A_BYTES;
-      // the stage written here was last read two steps ago; every wave has passed the barrier of
-      // the step in between, so nobody still reads it
-      la.store(sA, kt * BK, va[u]);
-      lb.store(sB, kt * BK, vb[u]);
-      add_colsum(vb[u], kt * BK);
-      if (kt + PF < nk) {
-        la.load((kt + PF) * BK, va[u]);
-        lb.load((kt + PF) * BK, vb[u]);
-      }
-      __syncthreads();
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8_t af[MT], bfr[NT];
 #pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
-        bf16x8_t af[MT], bfr[NT];
+      for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(lds + a_off[i][kk] + SOFF);
 #pragma unroll
-        for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(sA + a_off[i][kk]);
+      for (int j = 0; j < NT; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(lds + b_off[j][kk] + SOFF);
 #pragma unroll
-        for (int j = 0; j < NT; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(sB + b_off[j][kk]);
+      for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-          for (int j = 0; j < NT; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
+        for (int j = 0; j < NT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
+  };
+  // One K step: registers -> LDS stage, start the next step's global loads, barrier, multiply.
+  // The stage written here was last read two steps ago; every wave has since passed the barrier of
+  // the step in between, so nobody still reads it.
+  const bool fast = (m0 + BM <= p.M) && (n0 + BN <= p.N) && (p.K % BK == 0) && !p.wide;
+  auto step = [&](auto stage_tag, auto fast_tag, int kt) {
+    constexpr int SOFF = decltype(stage_tag)::value * STAGE;
+    constexpr bool F = decltype(fast_tag)::value;
+    if (F) { la.store_fast(lds + SOFF, va); lb.store_fast(lds + SOFF + A_BYTES, vb); }
+    else { la.store(lds + SOFF, kt * BK, va); lb.store(lds + SOFF + A_BYTES, kt * BK, vb); }
+    add_colsum(kt * BK);
+    if (kt + 1 < nk) {
+      if (F) { la.load_fast((kt + 1) * BK, va); lb.load_fast((kt + 1) * BK, vb); }
+      else { la.load((kt + 1) * BK, va); lb.load((kt + 1) * BK, vb); }
+    }
+    __syncthreads();
+    compute(stage_tag);
+  };
+  typedef std::integral_constant<int, 0> S0;
+  typedef std::integral_constant<int, 1> S1;
+  if (fast) {
+    la.load_fast(0, va);
+    lb.load_fast(0, vb);
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+      step(S0(), std::true_type(), kt);
+      step(S1(), std::true_type(), kt + 1);
+    }
+    if (kt < nk) step(S0(), std::true_type(), kt);
+  } else {
+    la.load(0, va);
+    lb.load(0, vb);
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+      step(S0(), std::false_type(), kt);
+      step(S1(), std::false_type(), kt + 1);
+    }
+    if (kt < nk) step(S0(), std::false_type(), kt);
   }
   __syncthreads();
 
@@ -429,10 +503,25 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   }
 }
 
+// Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.
+// remap_xcd() renumbers them so that the workgroups one XCD runs one after the other are
+// consecutive logical tiles: neighbours that share an operand tile then share it through one L2
+// instead of each XCD fetching its own copy.
+__device__ __forceinline__ int remap_xcd(int bid, int total) {
+  const int q = total >> 3, r = total & 7, x = bid & 7;
+  return x * q + (x < r ? x : r) + (bid >> 3);
+}
+
 template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF>
 __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
-  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, PF>(p, blockIdx.y * BM, blockIdx.x * BN, lds);
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  const int L = remap_xcd(blockIdx.x, tiles_m * tiles_n);
+  int tm, tn;
+  // walk along the axis of the SMALLER operand: it is re-read from L2 while the larger one streams
+  if ((int64_t)p.M <= (int64_t)p.N) { tm = L % tiles_m; tn = L / tiles_m; }
+  else { tn = L % tiles_n; tm = L / tiles_n; }
+  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, PF>(p, tm * BM, tn * BN, lds);
 }
 
 // Many independent problems of one layout in one launch: workgroup -> (problem, tile) through a
@@ -447,7 +536,7 @@ __global__ void __launch_bounds__(256) gemm_mfma_grouped_kernel(const GemmParams
   __shared__ int local_tile;
   if (threadIdx.x == 0) {
     int lo = 0, hi = n_problems - 1;
-    const int t = blockIdx.x;
+    const int t = remap_xcd(blockIdx.x, gridDim.x);
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
       if (tile_start[mid] <= t) lo = mid; else hi = mid - 1;
@@ -464,9 +553,23 @@ __global__ void __launch_bounds__(256) gemm_mfma_grouped_kernel(const GemmParams
   gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, 1, true>(prm, tm * BM, tn * BN, lds);
 }
 
+// An operand whose extent reaches 2 GiB cannot use the 32-bit per-lane offsets of the fast path.
+void set_wide(GemmParams& p) {
+  const int64_t lim = (int64_t)1 << 31;
+  const int64_t a = (int64_t)(p.transA ? p.K : p.M) * p.lda * 2;
+  int64_t b = (int64_t)(p.transB ? p.N : p.K) * p.ldb * 2;
+  if (p.b_split) {
+    const int64_t nseg = ((p.b_split_on_k ? p.K : p.N) + p.b_split - 1) / p.b_split;
+    b = nseg * p.b_seg_stride * 2 + b;
+  }
+  p.wide = (a >= lim || b >= lim) ? 1 : 0;
+}
+
 template <int BM, int BN, int WM, int WN, int PF>
-void launch_mfma_cfg(hipStream_t st, const GemmParams& p) {
-  dim3 grid((p.N + BN - 1) / BN, (p.M + BM - 1) / BM);
+void launch_mfma_cfg(hipStream_t st, const GemmParams& p_in) {
+  GemmParams p = p_in;
+  set_wide(p);
+  dim3 grid(((p.N + BN - 1) / BN) * ((p.M + BM - 1) / BM));
   constexpr int LDS = 2 * (BM + BN) * 128;
   const bool kca = !p.transA, kcb = p.transB != 0;
 #define MM_GO(KA, KB)                                                                               \
@@ -512,6 +615,8 @@ bool gemm_groupable(Dtype dt, const GemmParams& p) {
 }
 
 int gemm_grouped_tiles(const GemmParams& p) { return ((p.M + 127) / 128) * ((p.N + 127) / 128); }
+
+void gemm_prepare_grouped(GemmParams& p) { set_wide(p); }
 
 void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const int32_t* tile_start_dev,
                             int n_problems, int total_tiles) {

@@ -53,6 +53,7 @@ struct GemmParams {
   const float* residual;  // fp32 [M,N], row stride ldr, same segmentation as C: added last
   int64_t ldr;
   int out_f32;            // 1: C is fp32; 0: C has the working dtype
+  int wide;               // set by the launcher: an operand spans 2 GiB or more (32-bit offsets unusable)
   float* colsum_dst;      // grouped weight-gradient launch only: [N] (segmented like C) += column
                           // sums of B over K, i.e. the bias gradient belonging to this product
 };
@@ -62,6 +63,7 @@ void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p);
 // gemm_grouped_tiles() and total_tiles its total.  Every problem must satisfy gemm_groupable().
 bool gemm_groupable(Dtype dt, const GemmParams& p);
 int gemm_grouped_tiles(const GemmParams& p);
+void gemm_prepare_grouped(GemmParams& p);  // call on each table entry before upload
 void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const int32_t* tile_start_dev,
                             int n_problems, int total_tiles);
 // Tuning hook: one named tile configuration of the MFMA kernel; false if the shape is not eligible.

@@ -389,6 +389,7 @@ struct Step {
     int tiles = 0;
     double flops = 0;
     for (size_t i = 0; i < deferred.size(); ++i) {
+      gemm_prepare_grouped(deferred[i]);
       c->gtab_host[i] = deferred[i];
       c->gstart_host[i] = tiles;
       tiles += gemm_grouped_tiles(deferred[i]);
