@@ -9,6 +9,8 @@
 // exactly 0 (they are skipped, not given a large negative score).
 #include "mm_kernels.h"
 
+#include <algorithm>
+
 namespace mm {
 namespace {
 
@@ -251,7 +253,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // natural tile: [rows][64] bf16, 128-byte rows, 16-byte chunk c of row r in slot c ^ swz64(r)
 __device__ __forceinline__ void load_natural(unsigned char* lds, const bf16_t* g, int64_t ld, int row0, int len,
                                              int rows_pad, int tid) {
-  for (int q = tid; q < rows_pad * 8; q += 256) {
+  for (int q = tid; q < rows_pad * 8; q += blockDim.x) {
     const int row = q >> 3, c = q & 7;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (row < len) v = *reinterpret_cast<const uint4*>(g + (int64_t)(row0 + row) * ld + c * 8);
@@ -263,7 +265,7 @@ __device__ __forceinline__ void load_natural(unsigned char* lds, const bf16_t* g
 __device__ __forceinline__ void load_transposed(unsigned char* lds, const bf16_t* g, int64_t ld, int row0, int len,
                                                 int rows_pad, int tid) {
   const int stride = (rows_pad + 8) * 2;
-  for (int q = tid; q < (rows_pad >> 2) * 8; q += 256) {
+  for (int q = tid; q < (rows_pad >> 2) * 8; q += blockDim.x) {
     const int cg = q & 7, tq = q >> 3;
     uint4 v[4];
 #pragma unroll
@@ -322,7 +324,8 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams 
   __syncthreads();
   const float scale = 0.125f;  // 1 / sqrt(64)
   const int nqt = (lq + 31) >> 5;
-  for (int qt = wave; qt < nqt; qt += 4) {
+  const int nwave = blockDim.x >> 6;
+  for (int qt = wave; qt < nqt; qt += nwave) {
     const int ql = qt * 32 + lcol;
     const bool valid_q = ql < lq;
     const int64_t grow = q0 + (valid_q ? ql : lq - 1);
@@ -437,7 +440,8 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
   const float scale = 0.125f;
 
   // D_i = sum_c dO[i][c] O[i][c]; one lane handles one 16-byte chunk, eight lanes one row
-  for (int q = tid; q < Lqp * 8; q += 256) {
+  const int nwave = blockDim.x >> 6;
+  for (int q = tid; q < Lqp * 8; q += blockDim.x) {
     const int row = q >> 3, c = q & 7;
     float part = 0.f;
     if (row < lq) {
@@ -469,7 +473,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
     load_natural(Vn, vg, p.ldv, k0, lk, Lkp, tid);
     load_transposed(Kt, kg, p.ldk, k0, lk, Lkp, tid);
     __syncthreads();
-    for (int qt = wave; qt < nqt; qt += 4) {
+    for (int qt = wave; qt < nqt; qt += nwave) {
       const int ql = qt * 32 + lcol;
       const bool valid_q = ql < lq;
       const int64_t grow = q0 + (valid_q ? ql : lq - 1);
@@ -539,7 +543,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
     load_transposed(Qt, qg, p.ldq, q0, lq, Lqp, tid);
     load_transposed(dOt, dog, p.lddo, q0, lq, Lqp, tid);
     __syncthreads();
-    for (int kt = wave; kt < nkt; kt += 4) {
+    for (int kt = wave; kt < nkt; kt += nwave) {
       const int kl = kt * 32 + lcol;
       const bool valid_k = kl < lk;
       const int64_t grow = k0 + (valid_k ? kl : lk - 1);
@@ -636,12 +640,14 @@ static bool mfma_ok(Dtype dt, const AttnParams& p) {
 void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p) {
   if (mfma_ok(dt, p)) {
     const size_t lds = mfma_fwd_lds(p.max_lk);
+    // one wavefront per 32 queries: short sentences get small workgroups, so more of them share a CU
+    const int threads = 64 * std::min(4, (p.max_lq + 31) / 32);
     if (p.max_lk <= 128) {
       hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      attn_fwd_mfma_kernel<4><<<p.B * p.H, 256, lds, st>>>(p);
+      attn_fwd_mfma_kernel<4><<<p.B * p.H, threads, lds, st>>>(p);
     } else {
       hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      attn_fwd_mfma_kernel<8><<<p.B * p.H, 256, lds, st>>>(p);
+      attn_fwd_mfma_kernel<8><<<p.B * p.H, threads, lds, st>>>(p);
     }
     return;
   }
@@ -659,7 +665,8 @@ void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p) {
   if (mfma_ok(dt, p) && p.lddo % 8 == 0 && p.lddq % 4 == 0 && p.lddk % 4 == 0 && p.lddv % 4 == 0) {
     const size_t lds = mfma_bwd_lds(p.max_lq, p.max_lk);
     hipFuncSetAttribute((const void*)attn_bwd_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attn_bwd_mfma_kernel<<<p.B * p.H, 256, lds, st>>>(p);
+    const int threads = 64 * std::min(4, (std::max(p.max_lq, p.max_lk) + 31) / 32);
+    attn_bwd_mfma_kernel<<<p.B * p.H, threads, lds, st>>>(p);
     return;
   }
   const size_t lds = attn_lds_bytes(dt, p.dh, p.max_lq, p.max_lk, true);
