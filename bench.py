@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (a kernel of known traffic, used to "
+                         "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the path's cross-GPU gradient exchange is "
@@ -99,6 +102,12 @@ def main():
 
     run(0, args.warmup)
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     t0 = time.perf_counter()
     tokens, last_loss = run(args.warmup, n_steps)
     torch.cuda.synchronize()
@@ -117,6 +126,12 @@ def main():
                 "generator, input- and weight-gradient products)", "achieved": achieved / 1e12,
                 "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
                 "avg_launch_us": 1e3 * g["ms"] / max(1, g["launches"]), "launches_per_step": g["launches"] / args.steps}
+    # HBM bytes per GEMM launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (same workload)
+    tpath = os.path.join(ROOT, "profiles", f"bench_config{args.config}_gemm_traffic.json")
+    if os.path.exists(tpath):
+        t = json.load(open(tpath))
+        roofline["traffic"] = t["read_bytes_per_launch"] + t["written_bytes_per_launch"]
+        roofline["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel)"
     classes = {}
     for name, r in prof.items():
         if r["launches"] == 0:
