@@ -148,7 +148,44 @@ def build_setup(index: int) -> Setup:
                                ix[("dec", t)], ix[("gen", t)]]) for s, t in _pairs(8)]
         return Setup(5, "Transformer-big bf16, one GPU's share", shape, mods, tasks, 10, 200,
                      "loguniform", **_seeds(5))
+    if index in (6, 7, 8):
+        # The paper's own benchmark shapes (section 4): d=512, 8 heads, FFN 2048, 64k vocabulary,
+        # maximum length 200, 4096-token batches; four languages resident as one GPU's share.
+        shape = ModelShape(d_model=512, n_heads=8, d_ff=2048, vocab=64000, dtype="bf16", max_len=200,
+                           batch_tokens=4096)
+        n_lang = 4
+        mods: List[ModuleSpec] = []
+        ix = {}
+
+        def add(key, spec):
+            ix[key] = len(mods)
+            mods.append(spec)
+
+        enc_split = {6: None, 7: (4, 4), 8: None}[index]
+        enc_layers = {6: 6, 7: 8, 8: 9}[index]
+        dec_layers = {6: 6, 7: 4, 8: 4}[index]
+        for l in range(n_lang):
+            add(("src_emb", l), ModuleSpec("src_emb", f"lang{l}"))
+            add(("tgt_emb", l), ModuleSpec("tgt_emb", f"lang{l}"))
+            add(("dec", l), ModuleSpec("dec", f"lang{l}", 0, dec_layers, True))
+            add(("gen", l), ModuleSpec("gen", f"lang{l}"))
+            if index == 6:
+                add(("enc0", l), ModuleSpec("enc", f"lang{l}", 0, enc_layers, True))
+            elif index == 7:
+                add(("enc0", l), ModuleSpec("enc", f"lang{l}", 0, enc_split[0], False))
+        if index == 7:
+            add(("enc1", 0), ModuleSpec("enc", "full", 1, enc_split[1], True))
+        if index == 8:
+            add(("enc0", 0), ModuleSpec("enc", "full", 0, enc_layers, True))
+        tasks = []
+        for s_, t_ in _pairs(n_lang):
+            enc = [ix[("enc0", s_ if index != 8 else 0)]] + ([ix[("enc1", 0)]] if index == 7 else [])
+            tasks.append((f"{s_}-{t_}", [ix[("src_emb", s_)]] + enc + [ix[("tgt_emb", t_)], ix[("dec", t_)], ix[("gen", t_)]]))
+        title = {6: "paper shape: language-specific 6+6, 64k vocab", 7: "paper shape: 4 language-specific + 4 shared encoder layers, 4 decoder layers",
+                 8: "paper shape: shared 9-layer encoder, 4-layer language-specific decoders"}[index]
+        return Setup(index, title, shape, mods, tasks, 10, 200, "loguniform", **_seeds(index))
     raise ValueError(f"no such setup: {index}")
 
 
 CONFIGS = (1, 2, 3, 4, 5)
+PAPER_SHAPES = (6, 7, 8)

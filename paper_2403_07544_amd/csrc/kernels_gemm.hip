@@ -356,6 +356,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   // into the ds_read instructions' immediate field)
   auto compute = [&](auto stage_tag) {
     constexpr int SOFF = decltype(stage_tag)::value * STAGE;
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8_t af[MT], bfr[NT];
@@ -369,6 +370,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
         for (int j = 0; j < NT; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
+    __builtin_amdgcn_s_setprio(0);
   };
   // One K step: registers -> LDS stage, start the next step's global loads, barrier, multiply.
   // The stage written here was last read two steps ago; every wave has since passed the barrier of

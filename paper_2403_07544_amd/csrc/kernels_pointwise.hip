@@ -34,6 +34,17 @@ template <> struct Io<bf16_t> {
   }
 };
 
+// streaming accesses (touched once per step): bypass-friendly nontemporal loads and stores
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 nt_ld4(const float* p) {
+  const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_st4(float* p, float4 v) {
+  const f32x4_t o = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(p));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
@@ -593,8 +604,8 @@ __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict
   for (int it = 0; it < ADAM_CHUNK / 1024; ++it) {
     const int64_t i = base + it * 1024 + threadIdx.x * 4;
     if (i >= sg.len) break;
-    float4 g = Io<float>::ld4(sg.g + i), th = Io<float>::ld4(sg.theta + i);
-    float4 m = Io<float>::ld4(sg.m + i), v = Io<float>::ld4(sg.v + i);
+    float4 g = nt_ld4(sg.g + i), th = nt_ld4(sg.theta + i);
+    float4 m = nt_ld4(sg.m + i), v = nt_ld4(sg.v + i);
     float* gp = &g.x; float* tp = &th.x; float* mp = &m.x; float* vp = &v.x;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -604,10 +615,10 @@ __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict
       const float mh = mp[e] / sg.bc1, vh = vp[e] / sg.bc2;
       tp[e] = tp[e] - lr * mh / (sqrtf(vh) + eps);
     }
-    Io<float>::st4(sg.theta + i, th);
-    Io<float>::st4(sg.m + i, m);
-    Io<float>::st4(sg.v + i, v);
-    Io<float>::st4(sg.g + i, make_float4(0.f, 0.f, 0.f, 0.f));
+    nt_st4(sg.theta + i, th);
+    nt_st4(sg.m + i, m);
+    nt_st4(sg.v + i, v);
+    nt_st4(sg.g + i, make_float4(0.f, 0.f, 0.f, 0.f));
     if (sg.w16) Io<bf16_t>::st4(sg.w16 + i, th);
   }
 }

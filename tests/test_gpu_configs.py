@@ -99,3 +99,11 @@ def test_config4_partially_shared_with_adapters():
 
 def test_config5_transformer_big_one_task():
     _modular_case(5, n_tasks=1, seed=3)
+
+
+@pytest.mark.parametrize("index", [6, 7, 8])
+def test_paper_benchmark_shapes(index):
+    """The paper's own benchmark shapes (section 4): 64k vocabulary, maximum length 200, and the
+    three sharing schemes (language-specific 6+6; 4+4 partially shared encoder with 4 decoder
+    layers; shared 9-layer encoder with 4 decoder layers)."""
+    _modular_case(index, n_tasks=1, seed=10 + index)
