@@ -317,18 +317,24 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
 
   float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const bool do_cs = CS && p.colsum_dst != nullptr && m0 == 0;
-  u32x4_t va[TileLoader<BM, KCA>::NV];
-  u32x4_t vb[TileLoader<BN, KCB>::NV];
-  auto add_colsum = [&](int k0) {
-    if (CS && !KCB && BN == 128) {
+  static_assert(PF == 1 || PF == 2, "one or two K steps of global loads in flight");
+  u32x4_t va[PF][TileLoader<BM, KCA>::NV];   // register sets: tile t travels in set t % PF
+  u32x4_t vb[PF][TileLoader<BN, KCB>::NV];
+  // every item of a thread covers the same 8 columns (items differ in their k rows only)
+  constexpr bool CS_ON = CS && !KCB && (BN == 128 || BN == 256);
+  auto add_colsum = [&](int k0, const u32x4_t (&v)[TileLoader<BN, KCB>::NV]) {
+    if (CS_ON) {
       if (do_cs) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (k0 + j < lb.klim[0]) {
+        for (int i = 0; i < TileLoader<BN, KCB>::NL; ++i) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              cs[2 * e] += __uint_as_float(vb[j][e] << 16);
-              cs[2 * e + 1] += __uint_as_float(vb[j][e] & 0xffff0000u);
+          for (int j = 0; j < 4; ++j) {
+            if (k0 + j < lb.klim[i]) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                cs[2 * e] += __uint_as_float(v[i * 4 + j][e] << 16);
+                cs[2 * e + 1] += __uint_as_float(v[i * 4 + j][e] & 0xffff0000u);
+              }
             }
           }
         }
@@ -372,59 +378,77 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     }
     __builtin_amdgcn_s_setprio(0);
   };
-  // One K step: registers -> LDS stage, start the next step's global loads, barrier, multiply.
-  // The stage written here was last read two steps ago; every wave has since passed the barrier of
-  // the step in between, so nobody still reads it.
+  // One K step = barrier, then (a) park the NEXT tile pair (already in registers) in the other LDS
+  // stage and start the global loads of a later one, (b) multiply the current stage.  The LDS
+  // writes of (a) and the loads' latency run under the MFMAs of (b).  The barrier at the top
+  // guarantees both that everybody has finished reading the stage (a) overwrites (it was multiplied
+  // in the previous step) and that everybody's writes to the current stage have landed.
   const bool fast = (m0 + BM <= p.M) && (n0 + BN <= p.N) && (p.K % BK == 0) && !p.wide;
-  auto step = [&](auto stage_tag, auto fast_tag, int kt) {
+  auto stash = [&](auto stage_tag, auto set_tag, auto fast_tag, int kt) {  // registers (tile kt) -> LDS stage
     constexpr int SOFF = decltype(stage_tag)::value * STAGE;
+    constexpr int SET = decltype(set_tag)::value;
     constexpr bool F = decltype(fast_tag)::value;
-    if (F) { la.store_fast(lds + SOFF, va); lb.store_fast(lds + SOFF + A_BYTES, vb); }
-    else { la.store(lds + SOFF, kt * BK, va); lb.store(lds + SOFF + A_BYTES, kt * BK, vb); }
-    add_colsum(kt * BK);
-    if (kt + 1 < nk) {
-      if (F) { la.load_fast((kt + 1) * BK, va); lb.load_fast((kt + 1) * BK, vb); }
-      else { la.load((kt + 1) * BK, va); lb.load((kt + 1) * BK, vb); }
-    }
-    __syncthreads();
-    compute(stage_tag);
+    if (F) { la.store_fast(lds + SOFF, va[SET]); lb.store_fast(lds + SOFF + A_BYTES, vb[SET]); }
+    else { la.store(lds + SOFF, kt * BK, va[SET]); lb.store(lds + SOFF + A_BYTES, kt * BK, vb[SET]); }
+    add_colsum(kt * BK, vb[SET]);
+  };
+  auto fetch = [&](auto set_tag, auto fast_tag, int kt) {                  // global tile kt -> registers
+    constexpr int SET = decltype(set_tag)::value;
+    constexpr bool F = decltype(fast_tag)::value;
+    if (F) { la.load_fast(kt * BK, va[SET]); lb.load_fast(kt * BK, vb[SET]); }
+    else { la.load(kt * BK, va[SET]); lb.load(kt * BK, vb[SET]); }
   };
   typedef std::integral_constant<int, 0> S0;
   typedef std::integral_constant<int, 1> S1;
-  if (fast) {
-    la.load_fast(0, va);
-    lb.load_fast(0, vb);
+  // set_tag: the register set of tile kt + 1 (parked now, then refilled with tile kt + 1 + PF).
+  // Nothing in a step is conditional: past the end the last tile is fetched again and never
+  // used.  With a branch around the loads the compiler could no longer tell how many are still
+  // in flight at the next wait and would drain them all, which serialises the pipeline.
+  auto step = [&](auto cur_tag, auto nxt_tag, auto set_tag, auto fast_tag, int kt) {
+    __syncthreads();
+    stash(nxt_tag, set_tag, fast_tag, kt + 1);
+    fetch(set_tag, fast_tag, min(kt + 1 + PF, nk - 1));
+    compute(cur_tag);
+  };
+  auto last = [&](auto cur_tag) {
+    __syncthreads();
+    compute(cur_tag);
+  };
+  auto run = [&](auto fast_tag) {
+    typedef std::integral_constant<int, 1 % PF> SetOdd;   // tiles with odd index
+    fetch(S0(), fast_tag, 0);
+    if (PF > 1) fetch(SetOdd(), fast_tag, min(1, nk - 1));
+    stash(S0(), S0(), fast_tag, 0);
+    fetch(S0(), fast_tag, min(PF, nk - 1));
     int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-      step(S0(), std::true_type(), kt);
-      step(S1(), std::true_type(), kt + 1);
+    for (; kt + 2 < nk; kt += 2) {
+      step(S0(), S1(), SetOdd(), fast_tag, kt);
+      step(S1(), S0(), S0(), fast_tag, kt + 1);
     }
-    if (kt < nk) step(S0(), std::true_type(), kt);
-  } else {
-    la.load(0, va);
-    lb.load(0, vb);
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-      step(S0(), std::false_type(), kt);
-      step(S1(), std::false_type(), kt + 1);
+    if (nk - kt == 2) {
+      step(S0(), S1(), SetOdd(), fast_tag, kt);
+      last(S1());
+    } else {
+      last(S0());
     }
-    if (kt < nk) step(S0(), std::false_type(), kt);
-  }
+  };
+  if (fast) run(std::true_type()); else run(std::false_type());
   __syncthreads();
 
-  if (CS && !KCB && BN == 128) {
+  if (CS_ON) {
     if (do_cs) {  // uniform over the workgroup; LDS is free after the loop's last barrier
-      float* red = reinterpret_cast<float*>(lds);  // [16 k-groups][128 columns]
-      const int cg = tid & 15, kq = tid >> 4;
+      constexpr int NCG = BN / 8, NKG = 256 / NCG;   // column groups, threads per column group
+      float* red = reinterpret_cast<float*>(lds);    // [NKG][BN]
+      const int cg = tid % NCG, kg = tid / NCG;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) red[kq * 128 + cg * 8 + e] = cs[e];
+      for (int e = 0; e < 8; ++e) red[kg * BN + cg * 8 + e] = cs[e];
       __syncthreads();
-      if (tid < 128) {
+      if (tid < BN) {
         const int n = n0 + tid;
         if (n < p.N) {
           float t = 0.f;
 #pragma unroll
-          for (int g = 0; g < 16; ++g) t += red[g * 128 + tid];
+          for (int g = 0; g < NKG; ++g) t += red[g * BN + tid];
           int64_t idx = n;
           if (p.c_split) { const int sg = n / p.c_split; idx = (int64_t)sg * p.c_seg_stride + (n - sg * p.c_split); }
           p.colsum_dst[idx] += t;
@@ -441,7 +465,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   constexpr int PW = WN + 4;                       // patch row stride in floats
   float* patch = reinterpret_cast<float*>(lds) + wave * 32 * PW;   // (the loop's last barrier has passed)
   static_assert(4 * 32 * PW * 4 <= 2 * STAGE, "epilogue patch fits the tile buffers");
-  if (CS && !KCB && BN == 128) __syncthreads();    // the column-sum scratch above used the same memory
+  if (CS_ON) __syncthreads();                      // the column-sum scratch above used the same memory
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
 #pragma unroll
@@ -552,7 +576,7 @@ __global__ void __launch_bounds__(256) gemm_mfma_grouped_kernel(const GemmParams
   const int tiles_m = (prm.M + BM - 1) / BM;
   const int tm = local_tile % tiles_m, tn = local_tile / tiles_m;
   (void)tiles_n;
-  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, 1, true>(prm, tm * BM, tn * BN, lds);
+  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, 2, true>(prm, tm * BM, tn * BN, lds);
 }
 
 // An operand whose extent reaches 2 GiB cannot use the 32-bit per-lane offsets of the fast path.
@@ -595,6 +619,7 @@ inline bool aligned16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr
 
 // The MFMA kernel takes 16-byte chunks along each operand's contiguous axis.
 bool mfma_eligible(const GemmParams& p) {
+  if (p.K <= 0) return false;   // the K pipeline always loads its first tile
   if (!aligned16(p.A) || !aligned16(p.B)) return false;
   if (p.lda % 8 || p.ldb % 8) return false;
   if (!p.transA ? p.K % 8 : p.M % 8) return false;       // A's contiguous extent
@@ -642,11 +667,10 @@ bool launch_gemm_variant(hipStream_t st, const GemmParams& p, int variant) {
     case 1: launch_mfma_cfg<128, 128, 64, 64, 2>(st, p); return true;
     case 2: launch_mfma_cfg<64, 64, 32, 32, 1>(st, p); return true;
     case 3: launch_mfma_cfg<64, 64, 32, 32, 2>(st, p); return true;
-    case 4: launch_mfma_cfg<64, 64, 32, 32, 4>(st, p); return true;
-    case 5: launch_mfma_cfg<128, 64, 64, 32, 2>(st, p); return true;
-    case 6: launch_mfma_cfg<128, 64, 64, 32, 3>(st, p); return true;
-    case 7: launch_mfma_cfg<64, 128, 32, 64, 2>(st, p); return true;
-    case 8: launch_mfma_cfg<128, 128, 64, 64, 4>(st, p); return true;
+    case 4: launch_mfma_cfg<64, 128, 32, 64, 2>(st, p); return true;
+    case 5: launch_mfma_cfg<128, 64, 64, 32, 1>(st, p); return true;
+    case 6: launch_mfma_cfg<128, 64, 64, 32, 2>(st, p); return true;
+    case 7: launch_mfma_cfg<64, 128, 32, 64, 1>(st, p); return true;
     default: return false;
   }
 }
@@ -661,9 +685,18 @@ void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p) {
 void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p) {
   if (p.M <= 0 || p.N <= 0) return;
   if (dt == BF16 && mfma_eligible(p)) {
+    // Measured on the step's shapes: 128x128 tiles once they fill the chip, with two K steps of
+    // loads in flight when there are several rounds of tiles or a long K; few output tiles and a
+    // very long K (the generator's input gradient): 128x64; otherwise 64x64.
     const long tiles_big = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
-    if (tiles_big >= 192) launch_mfma_cfg<128, 128, 64, 64, 1>(st, p);
-    else launch_mfma_cfg<64, 64, 32, 32, 1>(st, p);
+    if (tiles_big >= 192) {
+      if (tiles_big >= 1024 || p.K >= 1024) launch_mfma_cfg<128, 128, 64, 64, 2>(st, p);
+      else launch_mfma_cfg<128, 128, 64, 64, 1>(st, p);
+    } else if (p.K >= 8192) {
+      launch_mfma_cfg<128, 64, 64, 32, 2>(st, p);
+    } else {
+      launch_mfma_cfg<64, 64, 32, 32, 1>(st, p);
+    }
     return;
   }
   launch_gemm_simt(st, dt, p);
