@@ -250,46 +250,58 @@ __device__ __forceinline__ int swz64(int row) { return ((row >> 1) & 7) ^ ((row 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
 }
-// natural tile: [rows][64] bf16, 128-byte rows, 16-byte chunk c of row r in slot c ^ swz64(r)
-__device__ __forceinline__ void load_natural(unsigned char* lds, const bf16_t* g, int64_t ld, int row0, int len,
-                                             int rows_pad, int tid) {
-  for (int q = tid; q < rows_pad * 8; q += blockDim.x) {
-    const int row = q >> 3, c = q & 7;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (row < len) v = *reinterpret_cast<const uint4*>(g + (int64_t)(row0 + row) * ld + c * 8);
-    *reinterpret_cast<uint4*>(lds + row * 128 + ((c ^ swz64(row)) << 4)) = v;
+// Tile loading.  One work item = 4 consecutive rows x one 16-byte chunk (8 columns); a workgroup
+// issues the loads of all its tiles back to back and only then starts storing, so a sentence costs
+// one global-memory round trip rather than one per loop iteration.  The same four registers feed
+// both LDS forms of a tile:
+//   natural:    [rows][64] bf16, 128-byte rows, 16-byte chunk c of row r in slot c ^ swz64(r)
+//   transposed: [64 columns][rows_pad + 8] bf16; within each block of 16 source rows the four
+//               row-quads are stored in the order 0,2,1,3 (the k-slot order described above)
+__device__ __forceinline__ void tile_fetch(uint4 (&v)[4], const bf16_t* g, int64_t ld, int row0, int len, int item) {
+  const int cg = item & 7, tq = item >> 3;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = tq * 4 + j;
+    v[j] = make_uint4(0, 0, 0, 0);
+    if (row < len) v[j] = *reinterpret_cast<const uint4*>(g + (int64_t)(row0 + row) * ld + cg * 8);
   }
 }
-// transposed tile: [64 columns][rows_pad + 8] bf16; within each block of 16 source rows the four
-// row-quads are stored in the order 0,2,1,3 (the k-slot order described above)
-__device__ __forceinline__ void load_transposed(unsigned char* lds, const bf16_t* g, int64_t ld, int row0, int len,
-                                                int rows_pad, int tid) {
-  const int stride = (rows_pad + 8) * 2;
-  for (int q = tid; q < (rows_pad >> 2) * 8; q += blockDim.x) {
-    const int cg = q & 7, tq = q >> 3;
-    uint4 v[4];
+__device__ __forceinline__ void tile_store_natural(unsigned char* lds, const uint4 (&v)[4], int item) {
+  const int cg = item & 7, tq = item >> 3;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int row = tq * 4 + j;
-      v[j] = make_uint4(0, 0, 0, 0);
-      if (row < len) v[j] = *reinterpret_cast<const uint4*>(g + (int64_t)(row0 + row) * ld + cg * 8);
-    }
-    const int qd = tq & 3;
-    const int pos = (tq >> 2) * 16 + (((qd & 1) << 1) | (qd >> 1)) * 4;
-    const uint32_t* w0 = &v[0].x; const uint32_t* w1 = &v[1].x; const uint32_t* w2 = &v[2].x; const uint32_t* w3 = &v[3].x;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      uint2 o;
-      if (e & 1) {
-        o.x = (w0[e >> 1] >> 16) | (w1[e >> 1] & 0xffff0000u);
-        o.y = (w2[e >> 1] >> 16) | (w3[e >> 1] & 0xffff0000u);
-      } else {
-        o.x = (w0[e >> 1] & 0xffffu) | (w1[e >> 1] << 16);
-        o.y = (w2[e >> 1] & 0xffffu) | (w3[e >> 1] << 16);
-      }
-      *reinterpret_cast<uint2*>(lds + (cg * 8 + e) * stride + pos * 2) = o;
-    }
+  for (int j = 0; j < 4; ++j) {
+    const int row = tq * 4 + j;
+    *reinterpret_cast<uint4*>(lds + row * 128 + ((cg ^ swz64(row)) << 4)) = v[j];
   }
+}
+__device__ __forceinline__ void tile_store_transposed(unsigned char* lds, int stride, const uint4 (&v)[4], int item) {
+  const int cg = item & 7, tq = item >> 3;
+  const int qd = tq & 3;
+  const int pos = (tq >> 2) * 16 + (((qd & 1) << 1) | (qd >> 1)) * 4;
+  const uint32_t* w0 = &v[0].x; const uint32_t* w1 = &v[1].x; const uint32_t* w2 = &v[2].x; const uint32_t* w3 = &v[3].x;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    uint2 o;
+    if (e & 1) {
+      o.x = (w0[e >> 1] >> 16) | (w1[e >> 1] & 0xffff0000u);
+      o.y = (w2[e >> 1] >> 16) | (w3[e >> 1] & 0xffff0000u);
+    } else {
+      o.x = (w0[e >> 1] & 0xffffu) | (w1[e >> 1] << 16);
+      o.y = (w2[e >> 1] & 0xffffu) | (w3[e >> 1] << 16);
+    }
+    *reinterpret_cast<uint2*>(lds + (cg * 8 + e) * stride + pos * 2) = o;
+  }
+}
+// dot product of two 8-element bf16 chunks
+__device__ __forceinline__ float dot8(const uint4& a, const uint4& b) {
+  const uint32_t* aw = &a.x; const uint32_t* bw = &b.x;
+  float t = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    t += __uint_as_float(aw[e] << 16) * __uint_as_float(bw[e] << 16);
+    t += __uint_as_float(aw[e] & 0xffff0000u) * __uint_as_float(bw[e] & 0xffff0000u);
+  }
+  return t;
 }
 __device__ __forceinline__ bf16x8_t frag_natural(const unsigned char* lds, int row, int chunk) {
   return *reinterpret_cast<const bf16x8_t*>(lds + row * 128 + ((chunk ^ swz64(row)) << 4));
@@ -319,19 +331,33 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams 
   unsigned char* Vt = Kn + Lp * 128;
   const int vstride = (Lp + 8) * 2;
   const bf16_t* qg = (const bf16_t*)p.q + h * 64;
-  load_natural(Kn, (const bf16_t*)p.k + h * 64, p.ldk, k0, lk, Lp, tid);
-  load_transposed(Vt, (const bf16_t*)p.v + h * 64, p.ldv, k0, lk, Lp, tid);
-  __syncthreads();
   const float scale = 0.125f;  // 1 / sqrt(64)
   const int nqt = (lq + 31) >> 5;
   const int nwave = blockDim.x >> 6;
+  // this wavefront's first Q fragments travel while the K and V tiles are fetched
+  bf16x8_t qf[4];
+  auto load_q = [&](int qt) {
+    const int64_t grow = q0 + min(qt * 32 + lcol, lq - 1);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) qf[s] = frag_global(qg + grow * p.ldq + (2 * s + hh) * 8);
+  };
+  if (wave < nqt) load_q(wave);
+  for (int base = 0; base < Lp * 2; base += blockDim.x) {
+    const int it = base + tid;
+    if (it < Lp * 2) {
+      uint4 vk[4], vv[4];
+      tile_fetch(vk, (const bf16_t*)p.k + h * 64, p.ldk, k0, lk, it);
+      tile_fetch(vv, (const bf16_t*)p.v + h * 64, p.ldv, k0, lk, it);
+      tile_store_natural(Kn, vk, it);
+      tile_store_transposed(Vt, vstride, vv, it);
+    }
+  }
+  __syncthreads();
   for (int qt = wave; qt < nqt; qt += nwave) {
     const int ql = qt * 32 + lcol;
     const bool valid_q = ql < lq;
     const int64_t grow = q0 + (valid_q ? ql : lq - 1);
-    bf16x8_t qf[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) qf[s] = frag_global(qg + grow * p.ldq + (2 * s + hh) * 8);
+    if (qt != wave) load_q(qt);
     const int kt_end = p.causal ? min(nkt, qt + 1) : nkt;
     f32x16_t sc[NKT];
 #pragma unroll
@@ -415,12 +441,15 @@ inline size_t mfma_fwd_lds(int max_lk) {
   return (size_t)Lp * 128 + (size_t)64 * (Lp + 8) * 2;
 }
 
-// Backward with the same layouts.  Phase A: a wavefront owns 32 queries and walks the key tiles:
-// S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D) * scale, dQ^T += K^T dS^T.  Phase B: a
-// wavefront owns 32 keys and walks the query tiles: S = Q K^T, dP = dO V^T, then
-// dV^T += dO^T P and dK^T += Q^T dS.  Each phase keeps its A operands in LDS (natural and
-// transposed tiles) and takes its B operands straight from global memory (its own 32 rows) or
-// from the accumulators of the previous product.
+// Backward with the same layouts, as two kinds of workgroup per (sentence, head), told apart by
+// blockIdx.y, which run side by side.  Kind 0 (dQ): a wavefront owns 32 queries and walks the key
+// tiles: S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D) * scale, dQ^T += K^T dS^T.  Kind 1
+// (dK, dV): a wavefront owns 32 keys and walks the query tiles: S = Q K^T, dP = dO V^T, then
+// dV^T += dO^T P and dK^T += Q^T dS.  Each kind keeps its A operands in LDS (natural and
+// transposed tiles, both written from one set of loads) and takes its B operands straight from
+// global memory (its own 32 rows) or from the accumulators of the previous product.
+// D_i = sum_c dO[i][c] O[i][c]: kind 0 forms it in registers from the fragments of its own
+// queries; kind 1 needs it for every query and builds a table in LDS while loading the dO tile.
 __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int b = blockIdx.x / p.H, h = blockIdx.x % p.H;
@@ -429,61 +458,58 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
   const int nkt = (lk + 31) >> 5, Lkp = nkt * 32;
   const int nqt = (lq + 31) >> 5, Lqp = nqt * 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lcol = lane & 31, hh = lane >> 5;
-  float* Dd = reinterpret_cast<float*>(smem_raw);   // [max_lq padded to 32]
-  float* Ls = Dd + (((p.max_lq + 31) >> 5) << 5);
-  unsigned char* tiles = reinterpret_cast<unsigned char*>(Ls + (((p.max_lq + 31) >> 5) << 5));
   const bf16_t* qg = (const bf16_t*)p.q + h * 64;
   const bf16_t* kg = (const bf16_t*)p.k + h * 64;
   const bf16_t* vg = (const bf16_t*)p.v + h * 64;
   const bf16_t* og = (const bf16_t*)p.o + h * 64;
   const bf16_t* dog = (const bf16_t*)p.d_o + h * 64;
+  const float* lseg = p.lse + (int64_t)h * p.rows_q + q0;
   const float scale = 0.125f;
-
-  // D_i = sum_c dO[i][c] O[i][c]; one lane handles one 16-byte chunk, eight lanes one row
   const int nwave = blockDim.x >> 6;
-  for (int q = tid; q < Lqp * 8; q += blockDim.x) {
-    const int row = q >> 3, c = q & 7;
-    float part = 0.f;
-    if (row < lq) {
-      const uint4 a = *reinterpret_cast<const uint4*>(dog + (int64_t)(q0 + row) * p.lddo + c * 8);
-      const uint4 o = *reinterpret_cast<const uint4*>(og + (int64_t)(q0 + row) * p.ldo + c * 8);
-      const uint32_t* aw = &a.x; const uint32_t* ow = &o.x;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        part += __uint_as_float(aw[e] << 16) * __uint_as_float(ow[e] << 16);
-        part += __uint_as_float(aw[e] & 0xffff0000u) * __uint_as_float(ow[e] & 0xffff0000u);
-      }
-    }
-    part += __shfl_xor(part, 1, WAVE);
-    part += __shfl_xor(part, 2, WAVE);
-    part += __shfl_xor(part, 4, WAVE);
-    if (c == 0) {
-      Dd[row] = part;
-      Ls[row] = row < lq ? p.lse[(int64_t)h * p.rows_q + q0 + row] : 0.f;
-    }
-  }
 
-  // ---------------- phase A: dQ ----------------
-  {
-    unsigned char* Kn = tiles;
+  if (blockIdx.y == 0) {
+    // ---------------- dQ ----------------
+    unsigned char* Kn = smem_raw;
     unsigned char* Vn = Kn + Lkp * 128;
     unsigned char* Kt = Vn + Lkp * 128;
     const int tstride = (Lkp + 8) * 2;
-    load_natural(Kn, kg, p.ldk, k0, lk, Lkp, tid);
-    load_natural(Vn, vg, p.ldv, k0, lk, Lkp, tid);
-    load_transposed(Kt, kg, p.ldk, k0, lk, Lkp, tid);
-    __syncthreads();
-    for (int qt = wave; qt < nqt; qt += nwave) {
-      const int ql = qt * 32 + lcol;
-      const bool valid_q = ql < lq;
-      const int64_t grow = q0 + (valid_q ? ql : lq - 1);
-      bf16x8_t qf[4], dof[4];
+    bf16x8_t qf[4], dof[4], of[4];
+    float lse_q = 0.f;
+    auto load_rows = [&](int qt) {   // fragments of this wavefront's 32 queries
+      const int rl = min(qt * 32 + lcol, lq - 1);
+      const int64_t grow = q0 + rl;
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         qf[s] = frag_global(qg + grow * p.ldq + (2 * s + hh) * 8);
         dof[s] = frag_global(dog + grow * p.lddo + (2 * s + hh) * 8);
+        of[s] = frag_global(og + grow * p.ldo + (2 * s + hh) * 8);
       }
-      const float Lq_ = Ls[qt * 32 + lcol], Dq = Dd[qt * 32 + lcol];
+      lse_q = lseg[rl];
+    };
+    if (wave < nqt) load_rows(wave);
+    for (int base = 0; base < Lkp * 2; base += blockDim.x) {
+      const int it = base + tid;
+      if (it < Lkp * 2) {
+        uint4 vk[4], vv[4];
+        tile_fetch(vk, kg, p.ldk, k0, lk, it);
+        tile_fetch(vv, vg, p.ldv, k0, lk, it);
+        tile_store_natural(Kn, vk, it);
+        tile_store_transposed(Kt, tstride, vk, it);
+        tile_store_natural(Vn, vv, it);
+      }
+    }
+    __syncthreads();
+    for (int qt = wave; qt < nqt; qt += nwave) {
+      if (qt != wave) load_rows(qt);
+      const int ql = qt * 32 + lcol;
+      const bool valid_q = ql < lq;
+      const int64_t grow = q0 + (valid_q ? ql : lq - 1);
+      float Dq = 0.f;
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) Dq += (float)dof[s][e] * (float)of[s][e];
+      Dq += __shfl_xor(Dq, 32, WAVE);
       f32x16_t dq[2];
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct)
@@ -504,7 +530,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
         for (int r = 0; r < 16; ++r) {
           const int key = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
           const bool ok = !attn_blocked(ql, key, lk, p.causal);
-          const float pr = ok ? __expf(sc[r] * scale - Lq_) : 0.f;
+          const float pr = ok ? __expf(sc[r] * scale - lse_q) : 0.f;
           ds[r] = pr * (dp[r] - Dq) * scale;
         }
 #pragma unroll
@@ -529,82 +555,109 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
           }
       }
     }
+    return;
+  }
+
+  // ---------------- dK, dV ----------------
+  float* Dd = reinterpret_cast<float*>(smem_raw);   // [Lqp]
+  float* Ls = Dd + Lqp;
+  unsigned char* Qn = reinterpret_cast<unsigned char*>(Ls + Lqp);
+  unsigned char* dOn = Qn + Lqp * 128;
+  unsigned char* Qt = dOn + Lqp * 128;
+  const int tstride = (Lqp + 8) * 2;
+  unsigned char* dOt = Qt + 64 * tstride;
+  bf16x8_t kf[4], vf[4];
+  auto load_rows = [&](int kt) {   // fragments of this wavefront's 32 keys
+    const int64_t grow = k0 + min(kt * 32 + lcol, lk - 1);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      kf[s] = frag_global(kg + grow * p.ldk + (2 * s + hh) * 8);
+      vf[s] = frag_global(vg + grow * p.ldv + (2 * s + hh) * 8);
+    }
+  };
+  if (wave < nkt) load_rows(wave);
+  for (int base = 0; base < Lqp * 2; base += blockDim.x) {
+    const int it = base + tid;
+    if (it < Lqp * 2) {
+      uint4 vq[4], vdo[4], vo[4];
+      tile_fetch(vq, qg, p.ldq, q0, lq, it);
+      tile_fetch(vdo, dog, p.lddo, q0, lq, it);
+      tile_fetch(vo, og, p.ldo, q0, lq, it);
+      const int cg = it & 7, tq = it >> 3;
+      float lse_r[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) lse_r[j] = (cg == 0 && tq * 4 + j < lq) ? lseg[tq * 4 + j] : 0.f;
+      tile_store_natural(Qn, vq, it);
+      tile_store_transposed(Qt, tstride, vq, it);
+      tile_store_natural(dOn, vdo, it);
+      tile_store_transposed(dOt, tstride, vdo, it);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float part = dot8(vdo[j], vo[j]);   // rows past lq were loaded as zeros
+        part += __shfl_xor(part, 1, WAVE);
+        part += __shfl_xor(part, 2, WAVE);
+        part += __shfl_xor(part, 4, WAVE);
+        if (cg == 0) { Dd[tq * 4 + j] = part; Ls[tq * 4 + j] = lse_r[j]; }
+      }
+    }
   }
   __syncthreads();
-  // ---------------- phase B: dK, dV ----------------
-  {
-    unsigned char* Qn = tiles;
-    unsigned char* dOn = Qn + Lqp * 128;
-    unsigned char* Qt = dOn + Lqp * 128;
-    const int tstride = (Lqp + 8) * 2;
-    unsigned char* dOt = Qt + 64 * tstride;
-    load_natural(Qn, qg, p.ldq, q0, lq, Lqp, tid);
-    load_natural(dOn, dog, p.lddo, q0, lq, Lqp, tid);
-    load_transposed(Qt, qg, p.ldq, q0, lq, Lqp, tid);
-    load_transposed(dOt, dog, p.lddo, q0, lq, Lqp, tid);
-    __syncthreads();
-    for (int kt = wave; kt < nkt; kt += nwave) {
-      const int kl = kt * 32 + lcol;
-      const bool valid_k = kl < lk;
-      const int64_t grow = k0 + (valid_k ? kl : lk - 1);
-      bf16x8_t kf[4], vf[4];
+  for (int kt = wave; kt < nkt; kt += nwave) {
+    if (kt != wave) load_rows(kt);
+    const int kl = kt * 32 + lcol;
+    const bool valid_k = kl < lk;
+    const int64_t grow = k0 + (valid_k ? kl : lk - 1);
+    f32x16_t dk[2], dv[2];
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { dk[ct][r] = 0.f; dv[ct][r] = 0.f; }
+    const int qt_begin = p.causal ? kt : 0;
+    for (int qt = qt_begin; qt < nqt; ++qt) {
+      f32x16_t sc, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        kf[s] = frag_global(kg + grow * p.ldk + (2 * s + hh) * 8);
-        vf[s] = frag_global(vg + grow * p.ldv + (2 * s + hh) * 8);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Qn, qt * 32 + lcol, 2 * s + hh), kf[s], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(dOn, qt * 32 + lcol, 2 * s + hh), vf[s], dp, 0, 0, 0);
       }
-      f32x16_t dk[2], dv[2];
+      float pr[16], ds[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int qi = qt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+        const bool ok = qi < lq && !attn_blocked(qi, kl, lk, p.causal);
+        pr[r] = ok ? __expf(sc[r] * scale - Ls[qi]) : 0.f;
+        ds[r] = pr[r] * (dp[r] - Dd[qi]) * scale;
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8_t pf = frag_from_regs(&pr[8 * s2]);
+        const bf16x8_t dsf = frag_from_regs(&ds[8 * s2]);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+          dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_transposed(dOt, tstride, ct * 32 + lcol, qt * 32 + s2 * 16 + hh * 8), pf, dv[ct], 0, 0, 0);
+          dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_transposed(Qt, tstride, ct * 32 + lcol, qt * 32 + s2 * 16 + hh * 8), dsf, dk[ct], 0, 0, 0);
+        }
+      }
+    }
+    if (valid_k) {
+      bf16_t* dkd = (bf16_t*)p.dk + grow * p.lddk + h * 64;
+      bf16_t* dvd = (bf16_t*)p.dv + grow * p.lddv + h * 64;
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { dk[ct][r] = 0.f; dv[ct][r] = 0.f; }
-      const int qt_begin = p.causal ? kt : 0;
-      for (int qt = qt_begin; qt < nqt; ++qt) {
-        f32x16_t sc, dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Qn, qt * 32 + lcol, 2 * s + hh), kf[s], sc, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(dOn, qt * 32 + lcol, 2 * s + hh), vf[s], dp, 0, 0, 0);
+        for (int g4 = 0; g4 < 4; ++g4) {
+          uint2 o;
+          o.x = pack_bf16(dk[ct][4 * g4 + 0], dk[ct][4 * g4 + 1]);
+          o.y = pack_bf16(dk[ct][4 * g4 + 2], dk[ct][4 * g4 + 3]);
+          *reinterpret_cast<uint2*>(dkd + ct * 32 + 8 * g4 + 4 * hh) = o;
+          o.x = pack_bf16(dv[ct][4 * g4 + 0], dv[ct][4 * g4 + 1]);
+          o.y = pack_bf16(dv[ct][4 * g4 + 2], dv[ct][4 * g4 + 3]);
+          *reinterpret_cast<uint2*>(dvd + ct * 32 + 8 * g4 + 4 * hh) = o;
         }
-        float pr[16], ds[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int qi = qt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-          const bool ok = qi < lq && !attn_blocked(qi, kl, lk, p.causal);
-          pr[r] = ok ? __expf(sc[r] * scale - Ls[qi]) : 0.f;
-          ds[r] = pr[r] * (dp[r] - Dd[qi]) * scale;
-        }
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8_t pf = frag_from_regs(&pr[8 * s2]);
-          const bf16x8_t dsf = frag_from_regs(&ds[8 * s2]);
-#pragma unroll
-          for (int ct = 0; ct < 2; ++ct) {
-            dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_transposed(dOt, tstride, ct * 32 + lcol, qt * 32 + s2 * 16 + hh * 8), pf, dv[ct], 0, 0, 0);
-            dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_transposed(Qt, tstride, ct * 32 + lcol, qt * 32 + s2 * 16 + hh * 8), dsf, dk[ct], 0, 0, 0);
-          }
-        }
-      }
-      if (valid_k) {
-        bf16_t* dkd = (bf16_t*)p.dk + grow * p.lddk + h * 64;
-        bf16_t* dvd = (bf16_t*)p.dv + grow * p.lddv + h * 64;
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            uint2 o;
-            o.x = pack_bf16(dk[ct][4 * g4 + 0], dk[ct][4 * g4 + 1]);
-            o.y = pack_bf16(dk[ct][4 * g4 + 2], dk[ct][4 * g4 + 3]);
-            *reinterpret_cast<uint2*>(dkd + ct * 32 + 8 * g4 + 4 * hh) = o;
-            o.x = pack_bf16(dv[ct][4 * g4 + 0], dv[ct][4 * g4 + 1]);
-            o.y = pack_bf16(dv[ct][4 * g4 + 2], dv[ct][4 * g4 + 3]);
-            *reinterpret_cast<uint2*>(dvd + ct * 32 + 8 * g4 + 4 * hh) = o;
-          }
-      }
     }
   }
 }
@@ -666,7 +719,7 @@ void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p) {
     const size_t lds = mfma_bwd_lds(p.max_lq, p.max_lk);
     hipFuncSetAttribute((const void*)attn_bwd_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     const int threads = 64 * std::min(4, (std::max(p.max_lq, p.max_lk) + 31) / 32);
-    attn_bwd_mfma_kernel<<<p.B * p.H, threads, lds, st>>>(p);
+    attn_bwd_mfma_kernel<<<dim3(p.B * p.H, 2), threads, lds, st>>>(p);
     return;
   }
   const size_t lds = attn_lds_bytes(dt, p.dh, p.max_lq, p.max_lk, true);

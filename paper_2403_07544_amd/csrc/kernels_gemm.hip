@@ -383,7 +383,11 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   // writes of (a) and the loads' latency run under the MFMAs of (b).  The barrier at the top
   // guarantees both that everybody has finished reading the stage (a) overwrites (it was multiplied
   // in the previous step) and that everybody's writes to the current stage have landed.
-  const bool fast = (m0 + BM <= p.M) && (n0 + BN <= p.N) && (p.K % BK == 0) && !p.wide;
+  // The K loop below runs in pairs of steps (one per LDS stage) with no conditional code around
+  // the multiplications: the unmasked fast path therefore wants an even number of K steps; the
+  // masked path rounds an odd count up, the extra step multiplying a tile the masks turn to zeros.
+  const bool fast = (m0 + BM <= p.M) && (n0 + BN <= p.N) && (p.K % (2 * BK) == 0) && !p.wide;
+  const int nk2 = (nk + 1) & ~1;
   auto stash = [&](auto stage_tag, auto set_tag, auto fast_tag, int kt) {  // registers (tile kt) -> LDS stage
     constexpr int SOFF = decltype(stage_tag)::value * STAGE;
     constexpr int SET = decltype(set_tag)::value;
@@ -421,16 +425,12 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     stash(S0(), S0(), fast_tag, 0);
     fetch(S0(), fast_tag, min(PF, nk - 1));
     int kt = 0;
-    for (; kt + 2 < nk; kt += 2) {
+    for (; kt + 2 < nk2; kt += 2) {
       step(S0(), S1(), SetOdd(), fast_tag, kt);
       step(S1(), S0(), S0(), fast_tag, kt + 1);
     }
-    if (nk - kt == 2) {
-      step(S0(), S1(), SetOdd(), fast_tag, kt);
-      last(S1());
-    } else {
-      last(S0());
-    }
+    step(S0(), S1(), SetOdd(), fast_tag, kt);
+    last(S1());
   };
   if (fast) run(std::true_type()); else run(std::false_type());
   __syncthreads();
@@ -671,6 +671,8 @@ bool launch_gemm_variant(hipStream_t st, const GemmParams& p, int variant) {
     case 5: launch_mfma_cfg<128, 64, 64, 32, 1>(st, p); return true;
     case 6: launch_mfma_cfg<128, 64, 64, 32, 2>(st, p); return true;
     case 7: launch_mfma_cfg<64, 128, 32, 64, 1>(st, p); return true;
+    case 8: launch_mfma_cfg<256, 256, 128, 128, 1>(st, p); return true;
+    case 9: launch_mfma_cfg<256, 128, 128, 64, 1>(st, p); return true;
     default: return false;
   }
 }
