@@ -261,6 +261,37 @@ struct TileLoader {
     }
   }
 
+  // One quarter (Q of 4) of this thread's share of a K step: the LDS stores of tile k_st from v,
+  // then the global loads of tile k_ld into the registers just freed.  Spread over the four MFMA
+  // groups of a K step, the stores and loads issue while the matrix pipeline is busy.
+  // element offset of k along a k-contiguous row (k segments, if any, taken into account)
+  __device__ __forceinline__ int64_t k_offset(int k) const {
+    if (KC && ksplit) { const int sg = k / ksplit; return (int64_t)sg * seg_stride + (k - sg * ksplit); }
+    return k;
+  }
+  template <int Q, bool F>
+  __device__ __forceinline__ void roll(unsigned char* lds, int k_st, int k_ld, int64_t koff, u32x4_t (&v)[NV]) const {
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
+    if (KC) {
+      constexpr int I0 = NL >= 4 ? Q * (NL / 4) : Q, I1 = NL >= 4 ? (Q + 1) * (NL / 4) : (Q < NL ? Q + 1 : Q);
+      if (I0 == I1) return;
+      const char* b = ubase + koff * 2;
+#pragma unroll
+      for (int i = I0; i < I1; ++i) {
+        *reinterpret_cast<u32x4_t*>(lds + off[i]) = (F || k_st < klim[i]) ? v[i] : zero;
+        if (F) v[i] = *(global_u4_ptr)(b + voff[i]);
+        else v[i] = load16_global(k_ld < klim[i] ? ptr[i] + koff : safe);
+      }
+    } else {
+      // all of it in the first quarter: every store needs all four k rows of its item, and the
+      // reloads, which can only follow the stores, then have the rest of the K step to land
+      if (Q == 0) {
+        if (F) { store_fast(lds, v); load_fast(k_ld, v); }
+        else { store(lds, k_st, v); load(k_ld, v); }
+      }
+    }
+  }
+
   // k0: the K step these registers were loaded for (items beyond the operand's extent become 0)
   __device__ __forceinline__ void store(unsigned char* lds, int k0, const u32x4_t (&v)[NV]) const {
     const u32x4_t zero = {0u, 0u, 0u, 0u};
@@ -358,29 +389,44 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
       b_off[j][kk] = A_BYTES + row * 128 + (((kk * 2 + lhalf) ^ swz(row)) << 4);
     }
   }
-  // multiply the tile pair sitting in LDS stage `stage` (compile-time: the stage offset folds
-  // into the ds_read instructions' immediate field)
-  auto compute = [&](auto stage_tag) {
+  // Multiplies the tile pair sitting in one LDS stage (compile-time: the stage offset folds into
+  // the ds_read instructions' immediate field).  The fragments of MFMA group kk + 1 are read while
+  // group kk multiplies; after each group, `between(kk)` may slot other work into the instruction
+  // stream, and a scheduling fence keeps the compiler from gathering that work in one place.
+  auto compute = [&](auto stage_tag, auto&& between) {
     constexpr int SOFF = decltype(stage_tag)::value * STAGE;
-    __builtin_amdgcn_s_setprio(1);
+    bf16x8_t af[2][MT], bfr[2][NT];
+    auto read_frags = [&](auto buf_tag, int kk) {
+      constexpr int BUF = decltype(buf_tag)::value;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8_t af[MT], bfr[NT];
+      for (int i = 0; i < MT; ++i) af[BUF][i] = *reinterpret_cast<const bf16x8_t*>(lds + a_off[i][kk] + SOFF);
 #pragma unroll
-      for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(lds + a_off[i][kk] + SOFF);
-#pragma unroll
-      for (int j = 0; j < NT; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(lds + b_off[j][kk] + SOFF);
+      for (int j = 0; j < NT; ++j) bfr[BUF][j] = *reinterpret_cast<const bf16x8_t*>(lds + b_off[j][kk] + SOFF);
+    };
+    auto mfmas = [&](auto buf_tag) {
+      constexpr int BUF = decltype(buf_tag)::value;
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[BUF][i], bfr[BUF][j], acc[i][j], 0, 0, 0);
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    typedef std::integral_constant<int, 2> I2;
+    typedef std::integral_constant<int, 3> I3;
+    static_assert(BK == 64, "four MFMA groups per K step");
+    __builtin_amdgcn_s_setprio(1);
+    read_frags(I0(), 0);
+    read_frags(I1(), 1); mfmas(I0()); between(I0()); __builtin_amdgcn_sched_barrier(0);
+    read_frags(I0(), 2); mfmas(I1()); between(I1()); __builtin_amdgcn_sched_barrier(0);
+    read_frags(I1(), 3); mfmas(I0()); between(I2()); __builtin_amdgcn_sched_barrier(0);
+    mfmas(I1()); between(I3());
     __builtin_amdgcn_s_setprio(0);
   };
-  // One K step = barrier, then (a) park the NEXT tile pair (already in registers) in the other LDS
-  // stage and start the global loads of a later one, (b) multiply the current stage.  The LDS
-  // writes of (a) and the loads' latency run under the MFMAs of (b).  The barrier at the top
+  // One K step = barrier, then, interleaved, (a) park the NEXT tile pair (already in registers) in
+  // the other LDS stage, refilling each register with a later tile as soon as it is free, and (b)
+  // multiply the current stage.  The barrier at the top
   // guarantees both that everybody has finished reading the stage (a) overwrites (it was multiplied
   // in the previous step) and that everybody's writes to the current stage have landed.
   // The K loop below runs in pairs of steps (one per LDS stage) with no conditional code around
@@ -409,14 +455,22 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   // used.  With a branch around the loads the compiler could no longer tell how many are still
   // in flight at the next wait and would drain them all, which serialises the pipeline.
   auto step = [&](auto cur_tag, auto nxt_tag, auto set_tag, auto fast_tag, int kt) {
+    constexpr int SN = decltype(nxt_tag)::value * STAGE;
+    constexpr int SET = decltype(set_tag)::value;
+    constexpr bool F = decltype(fast_tag)::value;
+    const int k_st = (kt + 1) * BK, k_ld = min(kt + 1 + PF, nk - 1) * BK;
+    const int64_t koff_a = la.k_offset(k_ld), koff_b = lb.k_offset(k_ld);
     __syncthreads();
-    stash(nxt_tag, set_tag, fast_tag, kt + 1);
-    fetch(set_tag, fast_tag, min(kt + 1 + PF, nk - 1));
-    compute(cur_tag);
+    add_colsum(k_st, vb[SET]);
+    compute(cur_tag, [&](auto q_tag) {
+      constexpr int Q = decltype(q_tag)::value;
+      la.template roll<Q, F>(lds + SN, k_st, k_ld, koff_a, va[SET]);
+      lb.template roll<Q, F>(lds + SN + A_BYTES, k_st, k_ld, koff_b, vb[SET]);
+    });
   };
   auto last = [&](auto cur_tag) {
     __syncthreads();
-    compute(cur_tag);
+    compute(cur_tag, [&](auto) {});
   };
   auto run = [&](auto fast_tag) {
     typedef std::integral_constant<int, 1 % PF> SetOdd;   // tiles with odd index
@@ -553,8 +607,8 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
 // Many independent problems of one layout in one launch: workgroup -> (problem, tile) through a
 // prefix table of tile counts.  Used for the weight-gradient products of a whole step, each of
 // which alone has too few output tiles to fill 256 compute units.
-template <int BM, int BN, int WM, int WN, bool KCA, bool KCB>
-__global__ void __launch_bounds__(256) gemm_mfma_grouped_kernel(const GemmParams* __restrict__ table,
+template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF>
+__global__ void __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) gemm_mfma_grouped_kernel(const GemmParams* __restrict__ table,
                                                                 const int32_t* __restrict__ tile_start,
                                                                 int n_problems) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -576,7 +630,7 @@ __global__ void __launch_bounds__(256) gemm_mfma_grouped_kernel(const GemmParams
   const int tiles_m = (prm.M + BM - 1) / BM;
   const int tm = local_tile % tiles_m, tn = local_tile / tiles_m;
   (void)tiles_n;
-  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, 2, true>(prm, tm * BM, tn * BN, lds);
+  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, PF, true>(prm, tm * BM, tn * BN, lds);
 }
 
 // An operand whose extent reaches 2 GiB cannot use the 32-bit per-lane offsets of the fast path.
@@ -645,18 +699,20 @@ int gemm_grouped_tiles(const GemmParams& p) { return ((p.M + 127) / 128) * ((p.N
 
 void gemm_prepare_grouped(GemmParams& p) { set_wide(p); }
 
+// 128x128 tiles: 256x256 ones (one workgroup per compute unit) were measured slower on the mix of
+// products a training step defers, also when only the generator's product used them.
 void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const int32_t* tile_start_dev,
                             int n_problems, int total_tiles) {
   if (n_problems <= 0 || total_tiles <= 0) return;
   constexpr int LDS = 2 * (128 + 128) * 128;
   static bool attr_set = false;
   if (!attr_set) {
-    hipFuncSetAttribute((const void*)gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false>,
+    hipFuncSetAttribute((const void*)gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false, 2>,
                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     attr_set = true;
   }
-  gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false><<<total_tiles, 256, LDS, st>>>(table_dev, tile_start_dev,
-                                                                                          n_problems);
+  gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false, 2><<<total_tiles, 256, LDS, st>>>(table_dev, tile_start_dev,
+                                                                                             n_problems);
 }
 
 // Tuning hook: run one named tile configuration of the MFMA kernel.
