@@ -6,7 +6,11 @@ embedding + positions, encoder and decoder forward, generator, label-smoothed cr
 full backward into the per-module buckets, and the Adam update of the touched modules.  Token
 ids are resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--accumulate A] [--no-cpu-baseline]
+
+--accumulate A > 1: A routed passes (A sampled tasks, which may share modules) feed one update, the
+single-GPU form of several tasks per device (paper section 3.2, algorithm 1: a module's gradient is
+divided by the number of passes that used it).  A "step" is then A passes plus one update.
 """
 from __future__ import annotations
 
@@ -57,6 +61,7 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--accumulate", type=int, default=1, help="routed passes per update")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a kernel of known traffic, used to "
@@ -77,7 +82,8 @@ def main():
     torch.cuda.set_device(0)
     setup = mm_synth.build_setup(args.config)
     sh = setup.shape
-    n_steps = args.warmup + args.steps
+    A = max(1, args.accumulate)
+    n_steps = (args.warmup + args.steps) * A      # routed passes; A of them per update
     batches = mm_synth.make_batches(setup)
     directions = mm_synth.sample_directions(setup, n_steps)
     ctx = context_from_setup(setup, fill_params=mm_synth.fill_params)
@@ -90,16 +96,23 @@ def main():
                     torch.tensor(b.tgt_ids, dtype=torch.int32, device="cuda"), b.lengths, b))
     torch.cuda.synchronize()
 
-    def run(lo, hi):
+    def run(lo, hi, marks=None):
+        """updates lo..hi-1; marks: one event per update boundary, on the library's (default) stream"""
         toks = 0
-        loss = 0.0
-        for k in range(lo, hi):
-            src, tgt, lengths, b = dev[k]
-            loss = ctx.mm_train_step(int(directions[k]), src, tgt, lengths)
+        for u in range(lo, hi):
+            for k in range(u * A, (u + 1) * A):
+                src, tgt, lengths, b = dev[k]
+                # asynchronous: the host enqueues the next pass while this one runs (the loss is read
+                # back once, after the last step)
+                ctx.mm_train_step(int(directions[k]), src, tgt, lengths, sync=False)
+                toks += b.n_tgt_tokens
             ctx.mm_apply_update(None, sh.lr)
-            toks += b.n_tgt_tokens
-        return toks, loss
+            if marks is not None:
+                marks[u - lo + 1].record()
+        torch.cuda.synchronize()
+        return toks, ctx.mm_last_loss()
 
+    n_upd = args.warmup + args.steps
     run(0, args.warmup)
     torch.cuda.synchronize()
     if args.calibrate_copy:
@@ -108,15 +121,19 @@ def main():
         b.copy_(a)
         torch.cuda.synchronize()
         del a, b
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    tokens, last_loss = run(args.warmup, n_steps)
+    marks[0].record()
+    tokens, last_loss = run(args.warmup, n_upd, marks)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    src_tokens = sum(dev[k][3].n_src_tokens for k in range(args.warmup, n_steps))
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
+    src_tokens = sum(dev[k][3].n_src_tokens for k in range(args.warmup * A, n_steps))
 
     # per-kernel-class timing with HIP events on the library's stream, same steps again
     ctx.mm_profile(True)
-    run(args.warmup, n_steps)
+    run(args.warmup, n_upd)
     prof = ctx.mm_profile_read()
     ctx.mm_profile(False)
     g = prof["gemm"]
@@ -145,18 +162,20 @@ def main():
     out = {
         "metric": "training tokens/s per MI355X (fwd+bwd+update), modular Transformer-base",
         "value": tokens / elapsed, "unit": "target tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps,
+        "ms_per_step_gpu": {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90)}, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}]: {setup.title}; d={sh.d_model} heads={sh.n_heads} "
                                f"ffn={sh.d_ff} vocab={sh.vocab}, {len(setup.modules)} modules resident, "
-                               f"{len(setup.tasks)} task(s), ~{sh.batch_tokens}-token length-bucketed batches",
+                               f"{len(setup.tasks)} task(s), ~{sh.batch_tokens}-token length-bucketed batches"
+                               + (f", {A} routed passes per update" if A > 1 else ""),
                    "target_tokens_per_step": tokens / args.steps, "source_tokens_per_step": src_tokens / args.steps,
                    "src_plus_tgt_tokens_per_s": (tokens + src_tokens) / elapsed, "last_loss": last_loss},
         "roofline": roofline,
         "kernel_classes": classes,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(setup, dev[args.warmup][3])
+        out["cpu_baseline"] = cpu_baseline(setup, dev[args.warmup * A][3])
     print(json.dumps(out))
 
 

@@ -13,7 +13,8 @@ from typing import List, Optional, Sequence, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmammoth_hip.so")
+# MAMMOTH_HIP_LIB: load another build of the library instead (side-by-side timing of two builds)
+LIB_PATH = os.environ.get("MAMMOTH_HIP_LIB") or os.path.join(_HERE, "libmammoth_hip.so")
 
 MM_OK, MM_EINVAL, MM_ENOMEM, MM_ESTATE, MM_ERANGE, MM_ENONFINITE, MM_EHIP = 0, -1, -2, -3, -4, -5, -6
 STATUS_NAMES = {0: "MM_OK", -1: "MM_EINVAL", -2: "MM_ENOMEM", -3: "MM_ESTATE", -4: "MM_ERANGE",

@@ -13,19 +13,20 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fno
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result", "-Wno-unused-value"]
 
 
-def build(verbose: bool = True) -> str:
+def build(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
+    """extra_flags / out: an experimental build beside the standard one (e.g. a -D switch)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+    cmd = [hipcc] + FLAGS + list(extra_flags) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in res.stdout.splitlines()
-                    if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
-    if verbose and out.strip():
-        print(out)
+    text = "\n".join(l for l in res.stdout.splitlines()
+                     if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
+    if verbose and text.strip():
+        print(text)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed ({res.returncode})\n{res.stdout}")
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
