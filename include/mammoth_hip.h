@@ -174,7 +174,8 @@ typedef enum {
   MM_K_EMBED = 5, MM_K_EMBED_GRAD = 6, MM_K_CE = 7, MM_K_COLSUM = 8, MM_K_ADAM = 9, MM_K_OTHER = 10,
   MM_K_COUNT = 11
 } mm_kernel_class;
-/* enable = 1: every launch is bracketed by an event pair and its algorithmic work (flops for
+/* enable = 1: an event is recorded after every launch (and one at the start of each call); a launch
+ * is charged the stream time since the event before it, and its algorithmic work (flops for
  * GEMM/attention, bytes for the rest) is tallied; enable = 0 stops.  Counters reset on enable. */
 mm_status mm_profile(mm_ctx* ctx, int32_t enable);
 /* Arrays of MM_K_COUNT entries: total milliseconds, launches, algorithmic work (flops or bytes). */

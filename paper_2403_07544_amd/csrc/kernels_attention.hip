@@ -9,6 +9,8 @@
 // exactly 0 (they are skipped, not given a large negative score).
 #include "mm_kernels.h"
 
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 
 namespace mm {
@@ -690,45 +692,45 @@ static bool mfma_ok(Dtype dt, const AttnParams& p) {
          p.ldv % 8 == 0 && p.ldo % 4 == 0;
 }
 
-void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p) {
+void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p, const LaunchEvents& ev) {
   if (mfma_ok(dt, p)) {
     const size_t lds = mfma_fwd_lds(p.max_lk);
     // one wavefront per 32 queries: short sentences get small workgroups, so more of them share a CU
     const int threads = 64 * std::min(4, (p.max_lq + 31) / 32);
     if (p.max_lk <= 128) {
       hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      attn_fwd_mfma_kernel<4><<<p.B * p.H, threads, lds, st>>>(p);
+      hipExtLaunchKernelGGL(attn_fwd_mfma_kernel<4>, dim3(p.B * p.H), dim3(threads), lds, st, ev.start, ev.stop, 0, p);
     } else {
       hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      attn_fwd_mfma_kernel<8><<<p.B * p.H, threads, lds, st>>>(p);
+      hipExtLaunchKernelGGL(attn_fwd_mfma_kernel<8>, dim3(p.B * p.H), dim3(threads), lds, st, ev.start, ev.stop, 0, p);
     }
     return;
   }
   const size_t lds = attn_lds_bytes(dt, p.dh, p.max_lq, p.max_lk, false);
   if (dt == BF16) {
     hipFuncSetAttribute((const void*)attn_fwd_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attn_fwd_kernel<bf16_t><<<p.B * p.H, 256, lds, st>>>(p);
+    hipExtLaunchKernelGGL(attn_fwd_kernel<bf16_t>, dim3(p.B * p.H), dim3(256), lds, st, ev.start, ev.stop, 0, p);
   } else {
     hipFuncSetAttribute((const void*)attn_fwd_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attn_fwd_kernel<float><<<p.B * p.H, 256, lds, st>>>(p);
+    hipExtLaunchKernelGGL(attn_fwd_kernel<float>, dim3(p.B * p.H), dim3(256), lds, st, ev.start, ev.stop, 0, p);
   }
 }
 
-void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p) {
+void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p, const LaunchEvents& ev) {
   if (mfma_ok(dt, p) && p.lddo % 8 == 0 && p.lddq % 4 == 0 && p.lddk % 4 == 0 && p.lddv % 4 == 0) {
     const size_t lds = mfma_bwd_lds(p.max_lq, p.max_lk);
     hipFuncSetAttribute((const void*)attn_bwd_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     const int threads = 64 * std::min(4, (std::max(p.max_lq, p.max_lk) + 31) / 32);
-    attn_bwd_mfma_kernel<<<dim3(p.B * p.H, 2), threads, lds, st>>>(p);
+    hipExtLaunchKernelGGL(attn_bwd_mfma_kernel, dim3(p.B * p.H, 2), dim3(threads), lds, st, ev.start, ev.stop, 0, p);
     return;
   }
   const size_t lds = attn_lds_bytes(dt, p.dh, p.max_lq, p.max_lk, true);
   if (dt == BF16) {
     hipFuncSetAttribute((const void*)attn_bwd_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attn_bwd_kernel<bf16_t><<<p.B * p.H, 256, lds, st>>>(p);
+    hipExtLaunchKernelGGL(attn_bwd_kernel<bf16_t>, dim3(p.B * p.H), dim3(256), lds, st, ev.start, ev.stop, 0, p);
   } else {
     hipFuncSetAttribute((const void*)attn_bwd_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attn_bwd_kernel<float><<<p.B * p.H, 256, lds, st>>>(p);
+    hipExtLaunchKernelGGL(attn_bwd_kernel<float>, dim3(p.B * p.H), dim3(256), lds, st, ev.start, ev.stop, 0, p);
   }
 }
 

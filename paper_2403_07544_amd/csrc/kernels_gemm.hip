@@ -7,6 +7,8 @@
 //   gemm_mfma_kernel : bf16 MFMA kernel, LDS-staged 128x128 or 64x64 tiles.
 #include "mm_kernels.h"
 
+#include <hip/hip_ext.h>
+
 #include <type_traits>
 
 namespace mm {
@@ -646,7 +648,7 @@ void set_wide(GemmParams& p) {
 }
 
 template <int BM, int BN, int WM, int WN, int PF>
-void launch_mfma_cfg(hipStream_t st, const GemmParams& p_in) {
+void launch_mfma_cfg(hipStream_t st, const GemmParams& p_in, const LaunchEvents& ev = LaunchEvents()) {
   GemmParams p = p_in;
   set_wide(p);
   dim3 grid(((p.N + BN - 1) / BN) * ((p.M + BM - 1) / BM));
@@ -660,7 +662,8 @@ void launch_mfma_cfg(hipStream_t st, const GemmParams& p_in) {
                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);                         \
       attr_set = true;                                                                              \
     }                                                                                               \
-    gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF><<<grid, 256, LDS, st>>>(p);                        \
+    hipExtLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF>), grid, dim3(256), LDS, st, \
+                          ev.start, ev.stop, 0, p);                                                 \
   } while (0)
   if (kca && kcb) MM_GO(true, true);
   else if (kca && !kcb) MM_GO(true, false);
@@ -702,7 +705,7 @@ void gemm_prepare_grouped(GemmParams& p) { set_wide(p); }
 // 128x128 tiles: 256x256 ones (one workgroup per compute unit) were measured slower on the mix of
 // products a training step defers, also when only the generator's product used them.
 void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const int32_t* tile_start_dev,
-                            int n_problems, int total_tiles) {
+                            int n_problems, int total_tiles, const LaunchEvents& ev) {
   if (n_problems <= 0 || total_tiles <= 0) return;
   constexpr int LDS = 2 * (128 + 128) * 128;
   static bool attr_set = false;
@@ -711,8 +714,8 @@ void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const i
                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     attr_set = true;
   }
-  gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false, 2><<<total_tiles, 256, LDS, st>>>(table_dev, tile_start_dev,
-                                                                                             n_problems);
+  hipExtLaunchKernelGGL((gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false, 2>), dim3(total_tiles), dim3(256), LDS,
+                        st, ev.start, ev.stop, 0, table_dev, tile_start_dev, n_problems);
 }
 
 // Tuning hook: run one named tile configuration of the MFMA kernel.
@@ -733,14 +736,14 @@ bool launch_gemm_variant(hipStream_t st, const GemmParams& p, int variant) {
   }
 }
 
-void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p) {
+void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p, const LaunchEvents& ev) {
   if (p.M <= 0 || p.N <= 0) return;
   dim3 grid((p.N + SB - 1) / SB, (p.M + SB - 1) / SB);
-  if (dt == BF16) gemm_simt_kernel<bf16_t><<<grid, 256, 0, st>>>(p);
-  else gemm_simt_kernel<float><<<grid, 256, 0, st>>>(p);
+  if (dt == BF16) hipExtLaunchKernelGGL(gemm_simt_kernel<bf16_t>, grid, dim3(256), 0, st, ev.start, ev.stop, 0, p);
+  else hipExtLaunchKernelGGL(gemm_simt_kernel<float>, grid, dim3(256), 0, st, ev.start, ev.stop, 0, p);
 }
 
-void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p) {
+void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p, const LaunchEvents& ev) {
   if (p.M <= 0 || p.N <= 0) return;
   if (dt == BF16 && mfma_eligible(p)) {
     // Measured on the step's shapes: 128x128 tiles once they fill the chip, with two K steps of
@@ -748,16 +751,16 @@ void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p) {
     // very long K (the generator's input gradient): 128x64; otherwise 64x64.
     const long tiles_big = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
     if (tiles_big >= 192) {
-      if (tiles_big >= 1024 || p.K >= 1024) launch_mfma_cfg<128, 128, 64, 64, 2>(st, p);
-      else launch_mfma_cfg<128, 128, 64, 64, 1>(st, p);
+      if (tiles_big >= 1024 || p.K >= 1024) launch_mfma_cfg<128, 128, 64, 64, 2>(st, p, ev);
+      else launch_mfma_cfg<128, 128, 64, 64, 1>(st, p, ev);
     } else if (p.K >= 8192) {
-      launch_mfma_cfg<128, 64, 64, 32, 2>(st, p);
+      launch_mfma_cfg<128, 64, 64, 32, 2>(st, p, ev);
     } else {
-      launch_mfma_cfg<64, 64, 32, 32, 1>(st, p);
+      launch_mfma_cfg<64, 64, 32, 32, 1>(st, p, ev);
     }
     return;
   }
-  launch_gemm_simt(st, dt, p);
+  launch_gemm_simt(st, dt, p, ev);
 }
 
 }  // namespace mm

@@ -3,6 +3,8 @@
 // cross-entropy, Adam.  gfx950, 64-wide wavefronts, 16-byte accesses wherever rows allow.
 #include "mm_kernels.h"
 
+#include <hip/hip_ext.h>
+
 namespace mm {
 
 namespace {
@@ -688,14 +690,14 @@ void launch_embed_grad(hipStream_t st, const uint32_t* keys, const float* dx, fl
 
 #define MM_LN_DISPATCH(KERNEL, T, ...)                                        \
   switch (nv_for(d)) {                                                        \
-    case 1: KERNEL<T, 1><<<grid, 256, 0, st>>>(__VA_ARGS__); break;           \
-    case 2: KERNEL<T, 2><<<grid, 256, 0, st>>>(__VA_ARGS__); break;           \
-    case 4: KERNEL<T, 4><<<grid, 256, 0, st>>>(__VA_ARGS__); break;           \
-    default: KERNEL<T, 8><<<grid, 256, 0, st>>>(__VA_ARGS__); break;          \
+    case 1: hipExtLaunchKernelGGL((KERNEL<T, 1>), dim3(grid), dim3(256), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break;  \
+    case 2: hipExtLaunchKernelGGL((KERNEL<T, 2>), dim3(grid), dim3(256), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break;  \
+    case 4: hipExtLaunchKernelGGL((KERNEL<T, 4>), dim3(grid), dim3(256), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break;  \
+    default: hipExtLaunchKernelGGL((KERNEL<T, 8>), dim3(grid), dim3(256), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break; \
   }
 
 void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float* gamma, const float* beta,
-                          void* y, float* mean, float* rstd, int rows, int d, float eps) {
+                          void* y, float* mean, float* rstd, int rows, int d, float eps, const LaunchEvents& ev) {
   const int grid = (rows + 3) / 4;
   if (dt == BF16) {
     MM_LN_DISPATCH(layernorm_fwd_kernel, bf16_t, x, gamma, beta, (bf16_t*)y, mean, rstd, rows, d, eps)
@@ -711,7 +713,7 @@ int ln_bwd_partial_rows(int rows) {
 
 void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float* x, const float* mean,
                           const float* rstd, const float* gamma, const float* dres, float* dx_out,
-                          void* dxT_out, float* partial, int rows, int d) {
+                          void* dxT_out, float* partial, int rows, int d, const LaunchEvents& ev) {
   const int grid = ln_bwd_partial_rows(rows);
   if (dt == BF16) {
     MM_LN_DISPATCH(layernorm_bwd_kernel, bf16_t, dy, x, mean, rstd, gamma, dres, dx_out, (bf16_t*)dxT_out,
@@ -744,12 +746,14 @@ void launch_colsum(hipStream_t st, Dtype dt, const void* Y, int y_f32, int64_t l
 }
 
 void launch_ce(hipStream_t st, Dtype dt, void* z, const int32_t* label, float* loss_rows, int U, int V,
-               float eps, float scale, const int32_t* flag) {
+               float eps, float scale, const int32_t* flag, const LaunchEvents& ev) {
   const int threads = V >= 16384 ? 1024 : V >= 2048 ? 256 : 64;
   if (dt == BF16)
-    ce_kernel<bf16_t><<<U, threads, 0, st>>>((bf16_t*)z, label, loss_rows, V, eps, scale, flag);
+    hipExtLaunchKernelGGL(ce_kernel<bf16_t>, dim3(U), dim3(threads), 0, st, ev.start, ev.stop, 0, (bf16_t*)z, label,
+                          loss_rows, V, eps, scale, flag);
   else
-    ce_kernel<float><<<U, threads, 0, st>>>((float*)z, label, loss_rows, V, eps, scale, flag);
+    hipExtLaunchKernelGGL(ce_kernel<float>, dim3(U), dim3(threads), 0, st, ev.start, ev.stop, 0, (float*)z, label,
+                          loss_rows, V, eps, scale, flag);
 }
 
 void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float* out) {
@@ -757,8 +761,10 @@ void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float
 }
 
 void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int total_chunks, float lr,
-                 float beta1, float beta2, float eps) {
-  if (total_chunks > 0) adam_kernel<<<total_chunks, 256, 0, st>>>(segs_dev, n_segs, lr, beta1, beta2, eps);
+                 float beta1, float beta2, float eps, const LaunchEvents& ev) {
+  if (total_chunks > 0)
+    hipExtLaunchKernelGGL(adam_kernel, dim3(total_chunks), dim3(256), 0, st, ev.start, ev.stop, 0, segs_dev, n_segs, lr,
+                          beta1, beta2, eps);
 }
 
 void launch_to_bf16(hipStream_t st, const float* src, bf16_t* dst, int64_t n) {

@@ -24,6 +24,11 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {
   return (bf16_t)(c.u >> 16);
 }
 
+// Timing handles for the launch being issued: when set, the launcher attaches them to its kernel
+// (hipExtLaunchKernel), so they carry the kernel's own start and stop timestamps and no marker
+// has to be queued around it.
+struct LaunchEvents { hipEvent_t start = nullptr; hipEvent_t stop = nullptr; };
+
 // ---------------------------------------------------------------------------------------------
 // GEMM:  C[M,N] = epilogue( op(A)[M,K] * op(B)[K,N] )
 //   transA = 0: A stored [M,K] row-major (lda = row stride); 1: stored [K,M] row-major.
@@ -57,7 +62,7 @@ struct GemmParams {
   float* colsum_dst;      // grouped weight-gradient launch only: [N] (segmented like C) += column
                           // sums of B over K, i.e. the bias gradient belonging to this product
 };
-void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p);
+void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p, const LaunchEvents& ev = LaunchEvents());
 // Weight-gradient products (transA = 1, transB = 0) of a whole step in one launch.  table_dev and
 // tile_start_dev are device arrays of n_problems entries; tile_start is the running sum of
 // gemm_grouped_tiles() and total_tiles its total.  Every problem must satisfy gemm_groupable().
@@ -65,11 +70,11 @@ bool gemm_groupable(Dtype dt, const GemmParams& p);
 int gemm_grouped_tiles(const GemmParams& p);
 void gemm_prepare_grouped(GemmParams& p);  // call on each table entry before upload
 void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const int32_t* tile_start_dev,
-                            int n_problems, int total_tiles);
+                            int n_problems, int total_tiles, const LaunchEvents& ev = LaunchEvents());
 // Tuning hook: one named tile configuration of the MFMA kernel; false if the shape is not eligible.
 bool launch_gemm_variant(hipStream_t st, const GemmParams& p, int variant);
 // Same contract, always the plain FMA kernel (cross-check of the MFMA path).
-void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p);
+void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p, const LaunchEvents& ev = LaunchEvents());
 
 // ---------------------------------------------------------------------------------------------
 // token bookkeeping
@@ -99,7 +104,7 @@ void launch_embed_grad(hipStream_t st, const uint32_t* keys, const float* dx, fl
 // ---------------------------------------------------------------------------------------------
 void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float* gamma,
                           const float* beta, void* y, float* mean, float* rstd, int rows, int d,
-                          float eps);
+                          float eps, const LaunchEvents& ev = LaunchEvents());
 // dx_out = dres + LN'(dy);  dxT_out (working dtype, may be null) = same, rounded.
 // The column sums for the gain and shift gradients leave as ln_bwd_partial_rows(rows) partial
 // rows, partial[p][0][d] (gain) and partial[p][1][d] (shift); launch_ln_reduce_grouped adds them
@@ -108,7 +113,7 @@ int ln_bwd_partial_rows(int rows);
 void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float* x,
                           const float* mean, const float* rstd, const float* gamma,
                           const float* dres, float* dx_out, void* dxT_out, float* partial,
-                          int rows, int d);
+                          int rows, int d, const LaunchEvents& ev = LaunchEvents());
 struct LnReduceJob {
   const float* partial; float* dgamma; float* dbeta;
   int32_t n_partial, d, first_block, pad;   // first_block: running sum of ceil(2d/64)
@@ -135,8 +140,8 @@ struct AttnParams {
   int64_t lddo, lddq, lddk, lddv;
 };
 size_t attn_lds_bytes(Dtype dt, int dh, int max_lq, int max_lk, bool backward);
-void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p);
-void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p);
+void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p, const LaunchEvents& ev = LaunchEvents());
+void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p, const LaunchEvents& ev = LaunchEvents());
 
 // ---------------------------------------------------------------------------------------------
 // label-smoothed cross-entropy over the vocabulary, forward and backward in one pass
@@ -144,7 +149,7 @@ void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p);
 //   where ok = (flag[0] == 0).  z has the working dtype, [U, V] with row stride V.
 // ---------------------------------------------------------------------------------------------
 void launch_ce(hipStream_t st, Dtype dt, void* z, const int32_t* label, float* loss_rows, int U,
-               int V, float eps, float scale, const int32_t* flag);
+               int V, float eps, float scale, const int32_t* flag, const LaunchEvents& ev = LaunchEvents());
 // out[0] = (sum of loss_rows) * scale
 void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float* out);
 
@@ -160,7 +165,7 @@ struct AdamSegment {
 };
 static const int ADAM_CHUNK = 4096;
 void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int total_chunks,
-                 float lr, float beta1, float beta2, float eps);
+                 float lr, float beta1, float beta2, float eps, const LaunchEvents& ev = LaunchEvents());
 
 // fp32 -> bf16 copy (working weights) and fill
 void launch_to_bf16(hipStream_t st, const float* src, bf16_t* dst, int64_t n);

@@ -50,7 +50,9 @@ struct Arena {
   }
 };
 
-struct ProfRec { int cls; hipEvent_t a, b; };
+// One timed launch: the event recorded right after it.  cls < 0: a mark that starts a new chain
+// (the beginning of a call); a launch's time is the distance from the previous event of its chain.
+struct ProfRec { int cls; hipEvent_t e; hipEvent_t s; };   // s: the kernel's own start time, where the launcher provides it
 constexpr int MAX_GROUPED_C = 1024;
 
 }  // namespace
@@ -162,32 +164,49 @@ struct Run {
     if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
     hipEvent_t e; hipEventCreate(&e); return e;
   }
+  // Timing: one event after every launch and one at the start of each call; a launch is charged
+  // the time since the previous event on the stream.  (A pair of events around each launch would
+  // add two markers per launch to the queue and time the gaps they create.)
+  int open_cls = -1;
+  void mark() {
+    if (!c->prof) return;
+    ProfRec r{-1, get_event(), nullptr};
+    hipEventRecord(r.e, c->st);
+    c->prof_recs.push_back(r);
+  }
   void begin(int cls, double work) {
     if (!c->prof) return;
-    ProfRec r{cls, get_event(), get_event()};
-    hipEventRecord(r.a, c->st);
-    c->prof_recs.push_back(r);
+    open_cls = cls;
     c->prof_n[cls] += 1;
     c->prof_work[cls] += work;
   }
   void end() {
     if (!c->prof) return;
-    hipEventRecord(c->prof_recs.back().b, c->st);
+    ProfRec r{open_cls, get_event(), nullptr};
+    hipEventRecord(r.e, c->st);
+    c->prof_recs.push_back(r);
+  }
+  // GEMM launches carry their own start/stop timestamps instead
+  LaunchEvents begin_timed(int cls, double work) {
+    LaunchEvents ev;
+    if (!c->prof) return ev;
+    c->prof_n[cls] += 1;
+    c->prof_work[cls] += work;
+    ev.start = get_event(); ev.stop = get_event();
+    c->prof_recs.push_back(ProfRec{cls, ev.stop, ev.start});
+    return ev;
   }
   size_t esz() const { return c->dt == BF16 ? 2 : 4; }
 
   void gemm(const GemmParams& p) {
     if (dry) return;
-    begin(MM_K_GEMM, 2.0 * p.M * p.N * p.K);
-    launch_gemm(c->st, c->dt, p);
-    end();
+    launch_gemm(c->st, c->dt, p, begin_timed(MM_K_GEMM, 2.0 * p.M * p.N * p.K));
   }
   void ln_fwd(const float* x, const float* g, const float* b, void* y, float* mean, float* rstd, int rows) {
     if (dry) return;
     const int d = c->cfg.d_model;
-    begin(MM_K_LAYERNORM_FWD, (double)rows * d * (4 + esz()));
-    launch_layernorm_fwd(c->st, c->dt, x, g, b, y, mean, rstd, rows, d, c->cfg.ln_eps);
-    end();
+    launch_layernorm_fwd(c->st, c->dt, x, g, b, y, mean, rstd, rows, d, c->cfg.ln_eps,
+                         begin_timed(MM_K_LAYERNORM_FWD, (double)rows * d * (4 + esz())));
   }
   // The gain/shift gradient sums of all LayerNorms of the step are reduced in one launch at the end.
   std::vector<LnReduceJob>* ln_jobs = nullptr;
@@ -197,10 +216,8 @@ struct Run {
     const int n_partial = ln_bwd_partial_rows(rows);
     float* partial = (float*)c->ws.take((size_t)n_partial * 2 * d * sizeof(float));
     if (dry) return;
-    begin(MM_K_LAYERNORM_BWD, (double)rows * d * (12 + (dres ? 4 : 0) + (c->dt == BF16 ? 2 : 0)));
-    launch_layernorm_bwd(c->st, c->dt, dy, x, mean, rstd, g, dres, dx, c->dt == BF16 ? dxT : nullptr,
-                         partial, rows, d);
-    end();
+    launch_layernorm_bwd(c->st, c->dt, dy, x, mean, rstd, g, dres, dx, c->dt == BF16 ? dxT : nullptr, partial, rows, d,
+                         begin_timed(MM_K_LAYERNORM_BWD, (double)rows * d * (12 + (dres ? 4 : 0) + (c->dt == BF16 ? 2 : 0))));
     LnReduceJob jb;
     jb.partial = partial; jb.dgamma = gg; jb.dbeta = gb; jb.n_partial = n_partial; jb.d = d;
     jb.first_block = 0; jb.pad = 0;
@@ -230,15 +247,11 @@ struct Run {
   }
   void attn_fwd(const AttnParams& p, double flops) {
     if (dry) return;
-    begin(MM_K_ATTN_FWD, flops);
-    launch_attn_fwd(c->st, c->dt, p);
-    end();
+    launch_attn_fwd(c->st, c->dt, p, begin_timed(MM_K_ATTN_FWD, flops));
   }
   void attn_bwd(const AttnParams& p, double flops) {
     if (dry) return;
-    begin(MM_K_ATTN_BWD, flops);
-    launch_attn_bwd(c->st, c->dt, p);
-    end();
+    launch_attn_bwd(c->st, c->dt, p, begin_timed(MM_K_ATTN_BWD, flops));
   }
 };
 
@@ -398,9 +411,8 @@ struct Step {
     hipMemcpyAsync(c->gtab_dev, c->gtab_host, deferred.size() * sizeof(GemmParams), hipMemcpyHostToDevice, c->st);
     hipMemcpyAsync(c->gstart_dev, c->gstart_host, deferred.size() * sizeof(int32_t), hipMemcpyHostToDevice, c->st);
     hipEventRecord(c->ev_gtab, c->st);
-    run.begin(MM_K_GEMM, flops);
-    launch_gemm_grouped_tn(c->st, c->gtab_dev, c->gstart_dev, (int)deferred.size(), tiles);
-    run.end();
+    launch_gemm_grouped_tn(c->st, c->gtab_dev, c->gstart_dev, (int)deferred.size(), tiles,
+                           run.begin_timed(MM_K_GEMM, flops));
     deferred.clear();
   }
 
@@ -488,12 +500,14 @@ double work_bytes_adam(const mm_ctx* c, int64_t n) { return (double)n * (c->dt =
 mm_status collect_profile(mm_ctx* c) {
   if (c->prof_recs.empty()) return MM_OK;
   HIP_TRY(c, hipStreamSynchronize(c->st));
+  hipEvent_t prev = nullptr;
   for (auto& r : c->prof_recs) {
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) c->prof_ms[r.cls] += ms;
-    c->ev_pool.push_back(r.a);
-    c->ev_pool.push_back(r.b);
+    hipEvent_t from = r.s ? r.s : prev;
+    if (r.cls >= 0 && from && hipEventElapsedTime(&ms, from, r.e) == hipSuccess) c->prof_ms[r.cls] += ms;
+    prev = r.e;
   }
+  for (auto& r : c->prof_recs) { c->ev_pool.push_back(r.e); if (r.s) c->ev_pool.push_back(r.s); }
   c->prof_recs.clear();
   return MM_OK;
 }
@@ -572,6 +586,7 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
   }
   const int d = s.d, S = s.S, U = s.U, V = s.V;
   Run& run = s.run;
+  if (!dry) run.mark();
   std::vector<LnReduceJob> ln_jobs;
   run.ln_jobs = &ln_jobs;
   c->ws.reset(dry);
@@ -664,9 +679,8 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
     run.gemm(p);
   }
   if (!dry) {
-    run.begin(MM_K_CE, (double)U * V * s.esz * 2);
-    launch_ce(c->st, c->dt, z, c->label, loss_rows, U, V, c->cfg.label_smoothing, 1.0f / (float)U, c->flag);
-    run.end();
+    launch_ce(c->st, c->dt, z, c->label, loss_rows, U, V, c->cfg.label_smoothing, 1.0f / (float)U, c->flag,
+              run.begin_timed(MM_K_CE, (double)U * V * s.esz * 2));
     run.begin(MM_K_OTHER, (double)U * 4);
     launch_sum_scaled(c->st, loss_rows, U, 1.0f / (float)U, c->loss_dev);
     run.end();
@@ -859,7 +873,7 @@ mm_status mm_destroy(mm_ctx* c) {
     if (c->seg_host) hipHostFree(c->seg_host);
     if (c->seg_dev) hipFree(c->seg_dev);
     if (c->ws.base) hipFree(c->ws.base);
-    for (auto& r : c->prof_recs) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+    for (auto& r : c->prof_recs) { hipEventDestroy(r.e); if (r.s) hipEventDestroy(r.s); }
     for (auto e : c->ev_pool) hipEventDestroy(e);
     if (c->ev_stage) hipEventDestroy(c->ev_stage);
     if (c->ev_done) hipEventDestroy(c->ev_done);
@@ -1095,9 +1109,9 @@ mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float
   HIP_TRY(c, hipMemcpyAsync(c->seg_dev, c->seg_host, use.size() * sizeof(AdamSegment), hipMemcpyHostToDevice, c->st));
   HIP_TRY(c, hipEventRecord(c->ev_seg, c->st));
   Run run{c, false};
-  run.begin(MM_K_ADAM, work_bytes_adam(c, total));
-  launch_adam(c->st, c->seg_dev, (int)use.size(), chunks, lr, c->cfg.adam_beta1, c->cfg.adam_beta2, c->cfg.adam_eps);
-  run.end();
+  run.mark();
+  launch_adam(c->st, c->seg_dev, (int)use.size(), chunks, lr, c->cfg.adam_beta1, c->cfg.adam_beta2, c->cfg.adam_eps,
+              run.begin_timed(MM_K_ADAM, work_bytes_adam(c, total)));
   HIP_TRY(c, hipGetLastError());
   return MM_OK;
 }
