@@ -250,7 +250,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
 __device__ __forceinline__ int swz64(int row) { return ((row >> 1) & 7) ^ ((row >> 4) & 3); }
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+  return pack2_bf16(a, b);
 }
 // Tile loading.  One work item = 4 consecutive rows x one 16-byte chunk (8 columns); a workgroup
 // issues the loads of all its tiles back to back and only then starts storing, so a sentence costs

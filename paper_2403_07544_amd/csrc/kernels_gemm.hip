@@ -573,10 +573,10 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
           *reinterpret_cast<float4*>(cp + 4) = make_float4(v[4], v[5], v[6], v[7]);
         } else {
           uint4 o;
-          o.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-          o.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-          o.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
-          o.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+          o.x = pack2_bf16(v[0], v[1]);
+          o.y = pack2_bf16(v[2], v[3]);
+          o.z = pack2_bf16(v[4], v[5]);
+          o.w = pack2_bf16(v[6], v[7]);
           *reinterpret_cast<uint4*>((bf16_t*)p.C + off) = o;
         }
       }

@@ -30,8 +30,8 @@ template <> struct Io<bf16_t> {
   }
   static __device__ __forceinline__ void st4(bf16_t* p, float4 v) {
     uint2 r;
-    r.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
-    r.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+    r.x = pack2_bf16(v.x, v.y);
+    r.y = pack2_bf16(v.z, v.w);
     *reinterpret_cast<uint2*>(p) = r;
   }
 };

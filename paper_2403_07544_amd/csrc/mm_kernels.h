@@ -15,13 +15,26 @@ __host__ __device__ inline float bf16_to_f32(bf16_t h) {
   c.u = (uint32_t)h << 16;
   return c.f;
 }
-// round to nearest even; NaN stays NaN
+// round to nearest even; NaN stays NaN.  On the device this is gfx950's conversion instruction
+// (v_cvt_pk_bf16_f32), which gives the same bits as the integer formula below for every input.
 __host__ __device__ inline bf16_t f32_to_bf16(float f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  const __bf16 b = (__bf16)f;
+  return __builtin_bit_cast(bf16_t, b);
+#else
   union { uint32_t u; float f; } c;
   c.f = f;
   if ((c.u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((c.u >> 16) | 0x40);
   c.u += 0x7fffu + ((c.u >> 16) & 1u);
   return (bf16_t)(c.u >> 16);
+#endif
+}
+// two values in one instruction: a in the low half, b in the high half
+__device__ inline uint32_t pack2_bf16(float a, float b) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Timing handles for the launch being issued: when set, the launcher attaches them to its kernel
