@@ -372,28 +372,35 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams 
           sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Kn, kt * 32 + lcol, 2 * s + hh), qf[s], sc[kt], 0, 0, 0);
       }
     }
-    // softmax over keys: registers, then the other half of the keys in lane ^ 32
+    // softmax over keys: registers, then the other half of the keys in lane ^ 32.  The maximum is
+    // taken over the raw products and the 1/sqrt(64) scale rides in the exponent's multiplier;
+    // only tiles that hold keys past the sentence end or the causal diagonal are masked; the
+    // probabilities go to the second product un-normalised and O is divided once at the end.
+    const float cexp = scale * 1.44269504088896341f;   // exp(s * scale) = exp2(s * cexp)
     float mx = -INFINITY;
 #pragma unroll
     for (int kt = 0; kt < NKT; ++kt) {
       if (kt < kt_end) {
+        if (kt * 32 + 32 > lk || (p.causal && kt == qt)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-          const bool ok = !attn_blocked(ql, key, lk, p.causal);
-          sc[kt][r] = ok ? sc[kt][r] * scale : -INFINITY;
-          mx = fmaxf(mx, sc[kt][r]);
+          for (int r = 0; r < 16; ++r) {
+            const int key = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+            if (attn_blocked(ql, key, lk, p.causal)) sc[kt][r] = -INFINITY;
+          }
         }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[kt][r]);
       }
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+    const float moff = -mx * cexp;
     float sum = 0.f;
 #pragma unroll
     for (int kt = 0; kt < NKT; ++kt) {
       if (kt < kt_end) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float e = (sc[kt][r] == -INFINITY) ? 0.f : __expf(sc[kt][r] - mx);
+          const float e = __builtin_amdgcn_exp2f(fmaf(sc[kt][r], cexp, moff));   // blocked: exp2(-inf) = 0
           sc[kt][r] = e;
           sum += e;
         }
@@ -401,7 +408,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams 
     }
     sum += __shfl_xor(sum, 32, WAVE);
     const float inv = 1.0f / sum;
-    if (valid_q && hh == 0) p.lse[(int64_t)h * p.rows_q + q0 + ql] = mx + __logf(sum);
+    if (valid_q && hh == 0) p.lse[(int64_t)h * p.rows_q + q0 + ql] = mx * scale + __logf(sum);
     f32x16_t oc[2];
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
@@ -414,7 +421,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams 
         for (int s2 = 0; s2 < 2; ++s2) {
           float pv[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) pv[e] = sc[kt][8 * s2 + e] * inv;
+          for (int e = 0; e < 8; ++e) pv[e] = sc[kt][8 * s2 + e];
           const bf16x8_t pf = frag_from_regs(pv);
 #pragma unroll
           for (int ct = 0; ct < 2; ++ct)
@@ -423,6 +430,10 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams 
         }
       }
     }
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oc[ct][r] *= inv;
     if (valid_q) {
       bf16_t* og = (bf16_t*)p.o + grow * p.ldo + h * 64;
 #pragma unroll
@@ -467,6 +478,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
   const bf16_t* dog = (const bf16_t*)p.d_o + h * 64;
   const float* lseg = p.lse + (int64_t)h * p.rows_q + q0;
   const float scale = 0.125f;
+  const float cexp = scale * 1.44269504088896341f;   // exp(s * scale) = exp2(s * cexp)
   const int nwave = blockDim.x >> 6;
 
   if (blockIdx.y == 0) {
@@ -486,7 +498,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
         dof[s] = frag_global(dog + grow * p.lddo + (2 * s + hh) * 8);
         of[s] = frag_global(og + grow * p.ldo + (2 * s + hh) * 8);
       }
-      lse_q = lseg[rl];
+      lse_q = lseg[rl] * 1.44269504088896341f;   // in the exponent's base-2 units
     };
     if (wave < nqt) load_rows(wave);
     for (int base = 0; base < Lkp * 2; base += blockDim.x) {
@@ -527,13 +539,20 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
           sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Kn, kt * 32 + lcol, 2 * s + hh), qf[s], sc, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Vn, kt * 32 + lcol, 2 * s + hh), dof[s], dp, 0, 0, 0);
         }
+        // Keys past the sentence end need no mask here: their rows of K are zeros in LDS, so
+        // whatever dS holds for them adds nothing to dQ.  Only the causal diagonal tile is masked.
         float ds[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int key = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-          const bool ok = !attn_blocked(ql, key, lk, p.causal);
-          const float pr = ok ? __expf(sc[r] * scale - lse_q) : 0.f;
+          const float pr = __builtin_amdgcn_exp2f(fmaf(sc[r], cexp, -lse_q));
           ds[r] = pr * (dp[r] - Dq) * scale;
+        }
+        if (p.causal && kt == qt) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+            if (key > ql) ds[r] = 0.f;
+          }
         }
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
@@ -599,7 +618,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
         part += __shfl_xor(part, 1, WAVE);
         part += __shfl_xor(part, 2, WAVE);
         part += __shfl_xor(part, 4, WAVE);
-        if (cg == 0) { Dd[tq * 4 + j] = part; Ls[tq * 4 + j] = lse_r[j]; }
+        if (cg == 0) { Dd[tq * 4 + j] = part; Ls[tq * 4 + j] = lse_r[j] * 1.44269504088896341f; }
       }
     }
   }
@@ -624,13 +643,22 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
         sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Qn, qt * 32 + lcol, 2 * s + hh), kf[s], sc, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(dOn, qt * 32 + lcol, 2 * s + hh), vf[s], dp, 0, 0, 0);
       }
+      // Queries past the sentence end have zero rows of Q and dO in LDS and add nothing; this
+      // wavefront's own keys past the end produce columns that are never stored.  Only the
+      // causal diagonal tile is masked.
       float pr[16], ds[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int qi = qt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-        const bool ok = qi < lq && !attn_blocked(qi, kl, lk, p.causal);
-        pr[r] = ok ? __expf(sc[r] * scale - Ls[qi]) : 0.f;
+        pr[r] = __builtin_amdgcn_exp2f(fmaf(sc[r], cexp, -Ls[qi]));
         ds[r] = pr[r] * (dp[r] - Dd[qi]) * scale;
+      }
+      if (p.causal && qt == kt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qi = qt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          if (kl > qi) { pr[r] = 0.f; ds[r] = 0.f; }
+        }
       }
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
