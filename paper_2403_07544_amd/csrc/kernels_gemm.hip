@@ -392,21 +392,24 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     }
   }
   // Multiplies the tile pair sitting in one LDS stage (compile-time: the stage offset folds into
-  // the ds_read instructions' immediate field).  The fragments of MFMA group kk + 1 are read while
-  // group kk multiplies; after each group, `between(kk)` may slot other work into the instruction
-  // stream, and a scheduling fence keeps the compiler from gathering that work in one place.
+  // the ds_read instructions' immediate field).  Fragments are read ahead of the MFMA group that
+  // uses them: one group ahead when a group is four or more MFMAs (enough to cover the LDS
+  // latency), all four groups at the top of the step when a group is only one or two.  After
+  // each group, `between(kk)` may slot other work into the instruction stream, and a scheduling
+  // fence keeps the compiler from gathering that work in one place.
   auto compute = [&](auto stage_tag, auto&& between) {
     constexpr int SOFF = decltype(stage_tag)::value * STAGE;
-    bf16x8_t af[2][MT], bfr[2][NT];
+    constexpr int NBUF = (MT * NT <= 2) ? 4 : 2;
+    bf16x8_t af[NBUF][MT], bfr[NBUF][NT];
     auto read_frags = [&](auto buf_tag, int kk) {
-      constexpr int BUF = decltype(buf_tag)::value;
+      constexpr int BUF = decltype(buf_tag)::value % NBUF;
 #pragma unroll
       for (int i = 0; i < MT; ++i) af[BUF][i] = *reinterpret_cast<const bf16x8_t*>(lds + a_off[i][kk] + SOFF);
 #pragma unroll
       for (int j = 0; j < NT; ++j) bfr[BUF][j] = *reinterpret_cast<const bf16x8_t*>(lds + b_off[j][kk] + SOFF);
     };
     auto mfmas = [&](auto buf_tag) {
-      constexpr int BUF = decltype(buf_tag)::value;
+      constexpr int BUF = decltype(buf_tag)::value % NBUF;
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -419,11 +422,19 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     typedef std::integral_constant<int, 3> I3;
     static_assert(BK == 64, "four MFMA groups per K step");
     __builtin_amdgcn_s_setprio(1);
-    read_frags(I0(), 0);
-    read_frags(I1(), 1); mfmas(I0()); between(I0()); __builtin_amdgcn_sched_barrier(0);
-    read_frags(I0(), 2); mfmas(I1()); between(I1()); __builtin_amdgcn_sched_barrier(0);
-    read_frags(I1(), 3); mfmas(I0()); between(I2()); __builtin_amdgcn_sched_barrier(0);
-    mfmas(I1()); between(I3());
+    if constexpr (NBUF == 4) {
+      read_frags(I0(), 0); read_frags(I1(), 1); read_frags(I2(), 2); read_frags(I3(), 3);
+      mfmas(I0()); between(I0()); __builtin_amdgcn_sched_barrier(0);
+      mfmas(I1()); between(I1()); __builtin_amdgcn_sched_barrier(0);
+      mfmas(I2()); between(I2()); __builtin_amdgcn_sched_barrier(0);
+      mfmas(I3()); between(I3());
+    } else {
+      read_frags(I0(), 0);
+      read_frags(I1(), 1); mfmas(I0()); between(I0()); __builtin_amdgcn_sched_barrier(0);
+      read_frags(I2(), 2); mfmas(I1()); between(I1()); __builtin_amdgcn_sched_barrier(0);
+      read_frags(I3(), 3); mfmas(I2()); between(I2()); __builtin_amdgcn_sched_barrier(0);
+      mfmas(I3()); between(I3());
+    }
     __builtin_amdgcn_s_setprio(0);
   };
   // One K step = barrier, then, interleaved, (a) park the NEXT tile pair (already in registers) in

@@ -602,13 +602,22 @@ __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict
   const AdamSegment sg = segs[lo];
   const int64_t base = (int64_t)(chunk - sg.first_chunk) * ADAM_CHUNK;
   const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+  // all of the chunk's loads are issued before the first result is needed (16 x 16 bytes in
+  // flight per thread); slots past the end of the segment re-read its last four elements and are
+  // not stored
+  constexpr int NIT = ADAM_CHUNK / 1024;
+  float4 g[NIT], th[NIT], m[NIT], v[NIT];
+  int64_t idx[NIT];
 #pragma unroll
-  for (int it = 0; it < ADAM_CHUNK / 1024; ++it) {
-    const int64_t i = base + it * 1024 + threadIdx.x * 4;
-    if (i >= sg.len) break;
-    float4 g = nt_ld4(sg.g + i), th = nt_ld4(sg.theta + i);
-    float4 m = nt_ld4(sg.m + i), v = nt_ld4(sg.v + i);
-    float* gp = &g.x; float* tp = &th.x; float* mp = &m.x; float* vp = &v.x;
+  for (int it = 0; it < NIT; ++it) {
+    idx[it] = base + it * 1024 + threadIdx.x * 4;
+    const int64_t i = idx[it] < sg.len ? idx[it] : sg.len - 4;
+    g[it] = nt_ld4(sg.g + i); th[it] = nt_ld4(sg.theta + i);
+    m[it] = nt_ld4(sg.m + i); v[it] = nt_ld4(sg.v + i);
+  }
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    float* gp = &g[it].x; float* tp = &th[it].x; float* mp = &m[it].x; float* vp = &v[it].x;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const float ge = gp[e] / sg.n_uses;
@@ -617,11 +626,14 @@ __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict
       const float mh = mp[e] / sg.bc1, vh = vp[e] / sg.bc2;
       tp[e] = tp[e] - lr * mh / (sqrtf(vh) + eps);
     }
-    nt_st4(sg.theta + i, th);
-    nt_st4(sg.m + i, m);
-    nt_st4(sg.v + i, v);
-    nt_st4(sg.g + i, make_float4(0.f, 0.f, 0.f, 0.f));
-    if (sg.w16) Io<bf16_t>::st4(sg.w16 + i, th);
+    if (idx[it] < sg.len) {
+      const int64_t i = idx[it];
+      nt_st4(sg.theta + i, th[it]);
+      nt_st4(sg.m + i, m[it]);
+      nt_st4(sg.v + i, v[it]);
+      nt_st4(sg.g + i, make_float4(0.f, 0.f, 0.f, 0.f));
+      if (sg.w16) Io<bf16_t>::st4(sg.w16 + i, th[it]);
+    }
   }
 }
 
