@@ -569,6 +569,96 @@ __global__ void __launch_bounds__(1024) ce_kernel(T* __restrict__ z, const int32
   }
 }
 
+// The same for bf16 rows that fit a workgroup's registers (V a multiple of 8, at most
+// 8 * 1024 * NCH): the row is read once with 16-byte loads and stays in registers, the maximum and
+// the sums are plain (not online) reductions, and exp(z - max) is computed once and reused for the
+// gradient.
+template <int NCH>
+__global__ void __launch_bounds__(1024) ce_rows_kernel(bf16_t* __restrict__ z, const int32_t* __restrict__ label,
+                                                       float* __restrict__ loss_rows, int V, float eps, float scale,
+                                                       const int32_t* __restrict__ flag) {
+  const int row = blockIdx.x;
+  bf16_t* zr = z + (int64_t)row * V;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int y = label[row];
+  float zy = 0.f;
+  if (tid == 0) zy = bf16_to_f32(zr[y]);   // before the row is overwritten
+  float val[NCH][8];
+  float mx = -INFINITY, sz = 0.f;
+#pragma unroll
+  for (int k = 0; k < NCH; ++k) {
+    const int c = (k * 1024 + tid) * 8;
+    if (c < V) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(zr + c);
+      const uint32_t* w = &raw.x;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        val[k][2 * e] = __uint_as_float(w[e] << 16);
+        val[k][2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { mx = fmaxf(mx, val[k][e]); sz += val[k][e]; }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) val[k][e] = -INFINITY;
+    }
+  }
+  __shared__ float s_a[16], s_b[16];
+  __shared__ float s_max, s_lse, s_inv, s_sumz;
+  mx = wave_max(mx);
+  if (lane == 0) s_a[wave] = mx;
+  __syncthreads();
+  if (tid == 0) {
+    float gm = s_a[0];
+    for (int w = 1; w < 16; ++w) gm = fmaxf(gm, s_a[w]);
+    s_max = gm;
+  }
+  __syncthreads();
+  const float gm = s_max;
+  const float L2E = 1.44269504088896341f;
+  const float off = -gm * L2E;
+  float se = 0.f;
+#pragma unroll
+  for (int k = 0; k < NCH; ++k)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      val[k][e] = __builtin_amdgcn_exp2f(fmaf(val[k][e], L2E, off));   // past the row's end: exp2(-inf) = 0
+      se += val[k][e];
+    }
+  se = wave_sum(se);
+  sz = wave_sum(sz);
+  if (lane == 0) { s_a[wave] = se; s_b[wave] = sz; }
+  __syncthreads();
+  if (tid == 0) {
+    float gs = 0.f, gz = 0.f;
+    for (int w = 0; w < 16; ++w) { gs += s_a[w]; gz += s_b[w]; }
+    s_lse = gm + logf(gs);
+    s_inv = 1.0f / gs;
+    s_sumz = gz;
+    loss_rows[row] = s_lse - (1.0f - eps) * zy - (eps / (float)V) * gz;
+  }
+  __syncthreads();
+  const float ok = (*flag == 0) ? scale : 0.0f;
+  const float inv = s_inv * ok, uni = (eps / (float)V) * ok, one = (1.0f - eps) * ok;
+#pragma unroll
+  for (int k = 0; k < NCH; ++k) {
+    const int c = (k * 1024 + tid) * 8;
+    if (c < V) {
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = val[k][e] * inv - uni;
+      if (y >= c && y < c + 8) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) if (y == c + e) o[e] -= one;
+      }
+      uint4 r;
+      r.x = pack2_bf16(o[0], o[1]); r.y = pack2_bf16(o[2], o[3]);
+      r.z = pack2_bf16(o[4], o[5]); r.w = pack2_bf16(o[6], o[7]);
+      *reinterpret_cast<uint4*>(zr + c) = r;
+    }
+  }
+}
+
 __global__ void __launch_bounds__(1024) sum_scaled_kernel(const float* __restrict__ v, int n, float scale,
                                                           float* __restrict__ out) {
   __shared__ float part[16];
@@ -760,6 +850,15 @@ void launch_colsum(hipStream_t st, Dtype dt, const void* Y, int y_f32, int64_t l
 void launch_ce(hipStream_t st, Dtype dt, void* z, const int32_t* label, float* loss_rows, int U, int V,
                float eps, float scale, const int32_t* flag, const LaunchEvents& ev) {
   const int threads = V >= 16384 ? 1024 : V >= 2048 ? 256 : 64;
+  if (dt == BF16 && V % 8 == 0 && V >= 16384 && V <= 8 * 1024 * 8 && (reinterpret_cast<uintptr_t>(z) & 15) == 0) {
+    if (V <= 8 * 1024 * 4)
+      hipExtLaunchKernelGGL(ce_rows_kernel<4>, dim3(U), dim3(1024), 0, st, ev.start, ev.stop, 0, (bf16_t*)z, label,
+                            loss_rows, V, eps, scale, flag);
+    else
+      hipExtLaunchKernelGGL(ce_rows_kernel<8>, dim3(U), dim3(1024), 0, st, ev.start, ev.stop, 0, (bf16_t*)z, label,
+                            loss_rows, V, eps, scale, flag);
+    return;
+  }
   if (dt == BF16)
     hipExtLaunchKernelGGL(ce_kernel<bf16_t>, dim3(U), dim3(threads), 0, st, ev.start, ev.stop, 0, (bf16_t*)z, label,
                           loss_rows, V, eps, scale, flag);
