@@ -524,6 +524,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
 #pragma unroll
         for (int e = 0; e < 8; ++e) Dq += (float)dof[s][e] * (float)of[s][e];
       Dq += __shfl_xor(Dq, 32, WAVE);
+      Dq *= scale;   // dS = P * (dP - D) * scale = P * (dP * scale - D * scale)
       f32x16_t dq[2];
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct)
@@ -545,7 +546,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float pr = __builtin_amdgcn_exp2f(fmaf(sc[r], cexp, -lse_q));
-          ds[r] = pr * (dp[r] - Dq) * scale;
+          ds[r] = pr * fmaf(dp[r], scale, -Dq);
         }
         if (p.causal && kt == qt) {
 #pragma unroll
@@ -618,7 +619,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
         part += __shfl_xor(part, 1, WAVE);
         part += __shfl_xor(part, 2, WAVE);
         part += __shfl_xor(part, 4, WAVE);
-        if (cg == 0) { Dd[tq * 4 + j] = part; Ls[tq * 4 + j] = lse_r[j] * 1.44269504088896341f; }
+        if (cg == 0) { Dd[tq * 4 + j] = part * scale; Ls[tq * 4 + j] = lse_r[j] * 1.44269504088896341f; }
       }
     }
   }
@@ -648,10 +649,17 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
       // causal diagonal tile is masked.
       float pr[16], ds[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int qi = qt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-        pr[r] = __builtin_amdgcn_exp2f(fmaf(sc[r], cexp, -Ls[qi]));
-        ds[r] = pr[r] * (dp[r] - Dd[qi]) * scale;
+      for (int g4 = 0; g4 < 4; ++g4) {
+        // accumulator registers 4 g4 .. 4 g4 + 3 are four consecutive queries: one 16-byte read each
+        const float4 l4 = *reinterpret_cast<const float4*>(Ls + qt * 32 + 8 * g4 + 4 * hh);
+        const float4 d4 = *reinterpret_cast<const float4*>(Dd + qt * 32 + 8 * g4 + 4 * hh);
+        const float lq[4] = {l4.x, l4.y, l4.z, l4.w}, dq_[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * g4 + e;
+          pr[r] = __builtin_amdgcn_exp2f(fmaf(sc[r], cexp, -lq[e]));
+          ds[r] = pr[r] * fmaf(dp[r], scale, -dq_[e]);
+        }
       }
       if (p.causal && qt == kt) {
 #pragma unroll
