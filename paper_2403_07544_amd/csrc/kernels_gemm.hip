@@ -140,6 +140,14 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v) {
   return ((uint64_t)hi << 32) | lo;
 }
 
+// s_waitcnt with only the vector-memory counter constrained: returns once at most N loads of this
+// wavefront are still in flight (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the others left open)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
 __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 7); }
 
 // Loads one operand tile (R rows x 64 k) from global memory into registers, then into LDS.
@@ -327,7 +335,13 @@ struct TileLoader {
 // weight gradient: dW = X^T dY, db = column sums of dY).  Only the tiles of the first tile row do
 // it, from the registers the transposing loader has just filled (4 k x 8 columns per thread).
 // PF: K steps whose global loads are in flight ahead of the one being multiplied (register staged).
-template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF, bool CS = false>
+// DMA (both operands k-contiguous, K a multiple of 128): the tiles go from global memory straight
+// into LDS (global_load_lds_dwordx4: lane l of a wavefront deposits its 16 bytes at base + 16 l, so
+// one instruction fills eight 128-byte tile rows; the slot swizzle is applied by choosing which
+// chunk each lane fetches).  No staging registers, no LDS store instructions.  DMA is the number of
+// LDS stages: DMA - 1 tiles are in flight while one is multiplied.  Rows past the edge of an
+// operand are read from its last row: they only feed outputs that are never stored.
+template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF, bool CS = false, int DMA = 0>
 __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0, const int n0, unsigned char* lds) {
   static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts");
   constexpr int MT = WM / 32, NT = WN / 32;
@@ -335,10 +349,58 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave / (BN / WN), wn = wave % (BN / WN);
 
+  static_assert(!DMA || (KCA && KCB && !CS), "direct-to-LDS loads need k-contiguous operands");
   TileLoader<BM, KCA> la;
-  la.init((const bf16_t*)p.A, p.lda, m0, p.M, p.K, 0, 0, 0, tid);
   TileLoader<BN, KCB> lb;
-  lb.init((const bf16_t*)p.B, p.ldb, n0, p.N, p.K, p.b_split, p.b_split_on_k, p.b_seg_stride, tid);
+  if constexpr (!DMA) {
+    la.init((const bf16_t*)p.A, p.lda, m0, p.M, p.K, 0, 0, 0, tid);
+    lb.init((const bf16_t*)p.B, p.ldb, n0, p.N, p.K, p.b_split, p.b_split_on_k, p.b_seg_stride, tid);
+  }
+  // DMA: per-lane source addresses at k = 0, one per wavefront instruction (8 tile rows each)
+  constexpr int NIA = BM / 32, NIB = BN / 32;
+  const bf16_t* dma_a[DMA ? NIA : 1];
+  const bf16_t* dma_b[DMA ? NIB : 1];
+  int dma_ksplit = 0; int64_t dma_seg = 0;
+  if constexpr (DMA) {
+    const int slot = lane & 7;
+#pragma unroll
+    for (int i = 0; i < NIA; ++i) {
+      const int row = (i * 4 + wave) * 8 + (lane >> 3);
+      const int gr = min(m0 + row, p.M - 1);
+      dma_a[i] = (const bf16_t*)p.A + (int64_t)gr * p.lda + ((slot ^ swz(row)) << 3);
+    }
+#pragma unroll
+    for (int j = 0; j < NIB; ++j) {
+      const int row = (j * 4 + wave) * 8 + (lane >> 3);
+      const int gr = min(n0 + row, p.N - 1);
+      const bf16_t* b = (const bf16_t*)p.B;
+      int rl = gr;
+      if (p.b_split && !p.b_split_on_k) { const int sg = gr / p.b_split; rl = gr - sg * p.b_split; b += (int64_t)sg * p.b_seg_stride; }
+      dma_b[j] = b + (int64_t)rl * p.ldb + ((slot ^ swz(row)) << 3);
+    }
+    if (p.b_split && p.b_split_on_k) { dma_ksplit = __builtin_amdgcn_readfirstlane(p.b_split); dma_seg = p.b_seg_stride; }
+  }
+  // quarter q (of 4) of this wavefront's loads of tile kt -> LDS stage at byte offset soff
+  auto dma_kb = [&](int kt) -> int64_t {   // B's element offset of tile kt along k (k segments)
+    const int k0 = kt * BK;
+    if (dma_ksplit) { const int sg = k0 / dma_ksplit; return (int64_t)sg * dma_seg + (k0 - sg * dma_ksplit); }
+    return k0;
+  };
+  auto dma_issue = [&](int soff, int kt, int64_t kb, int q) {
+    if constexpr (DMA) {
+      const int k0 = kt * BK;
+#pragma unroll
+      for (int i = 0; i < NIA; ++i)
+        if ((i & 3) == q)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(dma_a[i] + k0),
+                                           (__attribute__((address_space(3))) void*)(lds + soff + (i * 4 + wave) * 1024), 16, 0, 0);
+#pragma unroll
+      for (int j = 0; j < NIB; ++j)
+        if (((j + NIA) & 3) == q)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(dma_b[j] + kb),
+                                           (__attribute__((address_space(3))) void*)(lds + soff + A_BYTES + (j * 4 + wave) * 1024), 16, 0, 0);
+    }
+  };
 
   f32x16_t acc[MT][NT];
 #pragma unroll
@@ -397,8 +459,8 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   // latency), all four groups at the top of the step when a group is only one or two.  After
   // each group, `between(kk)` may slot other work into the instruction stream, and a scheduling
   // fence keeps the compiler from gathering that work in one place.
-  auto compute = [&](auto stage_tag, auto&& between) {
-    constexpr int SOFF = decltype(stage_tag)::value * STAGE;
+  auto compute = [&](auto stage_tag, auto&& between, int rt_off = 0) {
+    const int SOFF = decltype(stage_tag)::value * STAGE + rt_off;
     constexpr int NBUF = (MT * NT <= 2) ? 4 : 2;
     bf16x8_t af[NBUF][MT], bfr[NBUF][NT];
     auto read_frags = [&](auto buf_tag, int kk) {
@@ -499,7 +561,31 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     step(S0(), S1(), SetOdd(), fast_tag, kt);
     last(S1());
   };
-  if (fast) run(std::true_type()); else run(std::false_type());
+  // DMA: at the top of step kt this wavefront waits until all but the loads of the DMA - 2 newest
+  // tiles have landed (its part of tile kt is then in LDS), and the barrier extends that to the
+  // whole workgroup and tells that everybody has finished multiplying stage (kt - 1) % DMA, which is
+  // refilled with tile kt + DMA - 1 in four portions between the MFMA groups.  Every step issues
+  // the same number of loads (past the end the last tile is fetched again into a stage nobody
+  // reads), so the count in the wait is a constant.
+  auto run_dma = [&]() {
+    constexpr int LPW = NIA + NIB;               // loads per wavefront per tile
+    constexpr int KEEP = (DMA - 2) * LPW;        // loads that may stay in flight at the top of a step
+    for (int t = 0; t < DMA - 1; ++t)
+      for (int q = 0; q < 4; ++q) dma_issue(t * STAGE, min(t, nk - 1), dma_kb(min(t, nk - 1)), q);
+    int st = 0;                                   // kt % DMA
+    for (int kt = 0; kt < nk; ++kt) {
+      wait_vmcnt<(KEEP > 0 ? KEEP : 0)>();
+      __builtin_amdgcn_s_barrier();
+      const int st_new = st == 0 ? DMA - 1 : st - 1;   // (kt + DMA - 1) % DMA
+      const int kt_new = min(kt + DMA - 1, nk - 1);
+      const int64_t kb_new = dma_kb(kt_new);
+      compute(S0(), [&](auto q_tag) { dma_issue(st_new * STAGE, kt_new, kb_new, decltype(q_tag)::value); }, st * STAGE);
+      st = st + 1 == DMA ? 0 : st + 1;
+    }
+    wait_vmcnt<0>();   // the re-fetched tiles have landed before LDS is reused
+  };
+  if constexpr (DMA) run_dma();
+  else { if (fast) run(std::true_type()); else run(std::false_type()); }
   __syncthreads();
 
   if (CS_ON) {
@@ -605,7 +691,7 @@ __device__ __forceinline__ int remap_xcd(int bid, int total) {
   return x * q + (x < r ? x : r) + (bid >> 3);
 }
 
-template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF>
+template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF, int DMA>
 __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
@@ -614,7 +700,7 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
   // walk along the axis of the SMALLER operand: it is re-read from L2 while the larger one streams
   if ((int64_t)p.M <= (int64_t)p.N) { tm = L % tiles_m; tn = L / tiles_m; }
   else { tn = L % tiles_n; tm = L / tiles_n; }
-  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, PF>(p, tm * BM, tn * BN, lds);
+  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, PF, false, DMA>(p, tm * BM, tn * BN, lds);
 }
 
 // Many independent problems of one layout in one launch: workgroup -> (problem, tile) through a
@@ -658,22 +744,26 @@ void set_wide(GemmParams& p) {
   p.wide = (a >= lim || b >= lim) ? 1 : 0;
 }
 
-template <int BM, int BN, int WM, int WN, int PF>
+template <int BM, int BN, int WM, int WN, int PF, int DMA = 0>
 void launch_mfma_cfg(hipStream_t st, const GemmParams& p_in, const LaunchEvents& ev = LaunchEvents()) {
+  if (DMA && !(p_in.transA == 0 && p_in.transB != 0 && p_in.K % BK == 0)) {
+    launch_mfma_cfg<BM, BN, WM, WN, PF, 0>(st, p_in, ev);
+    return;
+  }
   GemmParams p = p_in;
   set_wide(p);
   dim3 grid(((p.N + BN - 1) / BN) * ((p.M + BM - 1) / BM));
-  constexpr int LDS = 2 * (BM + BN) * 128;
+  constexpr int LDS = (DMA ? DMA : 2) * (BM + BN) * 128;
   const bool kca = !p.transA, kcb = p.transB != 0;
 #define MM_GO(KA, KB)                                                                               \
   do {                                                                                              \
     static bool attr_set = false;                                                                   \
     if (!attr_set) {                                                                                \
-      hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF>,                \
+      hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF, (KA && KB) ? DMA : 0>, \
                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);                         \
       attr_set = true;                                                                              \
     }                                                                                               \
-    hipExtLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF>), grid, dim3(256), LDS, st, \
+    hipExtLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF, (KA && KB) ? DMA : 0>), grid, dim3(256), LDS, st, \
                           ev.start, ev.stop, 0, p);                                                 \
   } while (0)
   if (kca && kcb) MM_GO(true, true);
@@ -743,6 +833,12 @@ bool launch_gemm_variant(hipStream_t st, const GemmParams& p, int variant) {
     case 7: launch_mfma_cfg<64, 128, 32, 64, 1>(st, p); return true;
     case 8: launch_mfma_cfg<256, 256, 128, 128, 1>(st, p); return true;
     case 9: launch_mfma_cfg<256, 128, 128, 64, 1>(st, p); return true;
+    case 10: launch_mfma_cfg<64, 64, 32, 32, 1, 4>(st, p); return true;
+    case 11: launch_mfma_cfg<128, 128, 64, 64, 1, 2>(st, p); return true;
+    case 12: launch_mfma_cfg<128, 64, 64, 32, 1, 3>(st, p); return true;
+    case 13: launch_mfma_cfg<64, 64, 32, 32, 1, 3>(st, p); return true;
+    case 14: launch_mfma_cfg<64, 64, 32, 32, 1, 2>(st, p); return true;
+    case 15: launch_mfma_cfg<128, 128, 64, 64, 1, 3>(st, p); return true;
     default: return false;
   }
 }
@@ -767,7 +863,9 @@ void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p, const LaunchEven
     } else if (p.K >= 8192) {
       launch_mfma_cfg<128, 64, 64, 32, 2>(st, p, ev);
     } else {
-      launch_mfma_cfg<64, 64, 32, 32, 1>(st, p, ev);
+      // (when both operands are k-contiguous and K is a multiple of 64 this runs the variant with
+      // direct-to-LDS loads and three stages)
+      launch_mfma_cfg<64, 64, 32, 32, 1, 3>(st, p, ev);
     }
     return;
   }
