@@ -349,7 +349,16 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave / (BN / WN), wn = wave % (BN / WN);
 
-  static_assert(!DMA || (KCA && KCB && !CS), "direct-to-LDS loads need k-contiguous operands");
+  static_assert(!DMA || (KCA && !CS), "direct-to-LDS loads need a k-contiguous A");
+  // DMA with a B whose contiguous axis is n (forward weights [K, N]): the B tile is kept in LDS as it
+  // lies in memory, [64 k][BN] with 16-byte chunk c of k row r in slot c ^ bt_swz(r), and the MFMA
+  // fragments (8 consecutive k of one column per lane) are formed by the transposing LDS read
+  // ds_read_b64_tr_b16: within 16 lanes, lane j supplies the address of 4 columns of row j / 4 and
+  // lane i receives rows 0..3 of column i.  The slot swizzle spreads the four rows of one read over
+  // different banks.
+  constexpr bool BTR = DMA && !KCB;
+  constexpr int BT_ROW = BN * 2;                        // bytes per k row of the B tile
+  auto bt_swz = [](int krow) { return BN >= 128 ? (krow & 3) << 2 : ((krow >> 1) & 1) << 2; };
   TileLoader<BM, KCA> la;
   TileLoader<BN, KCB> lb;
   if constexpr (!DMA) {
@@ -377,6 +386,15 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
       int rl = gr;
       if (p.b_split && !p.b_split_on_k) { const int sg = gr / p.b_split; rl = gr - sg * p.b_split; b += (int64_t)sg * p.b_seg_stride; }
       dma_b[j] = b + (int64_t)rl * p.ldb + ((slot ^ swz(row)) << 3);
+      if constexpr (BTR) {
+        constexpr int CPR = BN / 8;                     // chunks per k row; one instruction = 64 / CPR rows
+        const int krow = (j * 4 + wave) * (64 / CPR) + lane / CPR;
+        const int col = min(n0 + (((lane % CPR) ^ bt_swz(krow)) << 3), p.N - 8);
+        const bf16_t* bb = (const bf16_t*)p.B;
+        int cl = col;
+        if (p.b_split) { const int sg = col / p.b_split; cl = col - sg * p.b_split; bb += (int64_t)sg * p.b_seg_stride; }
+        dma_b[j] = bb + (int64_t)krow * p.ldb + cl;
+      }
     }
     if (p.b_split && p.b_split_on_k) { dma_ksplit = __builtin_amdgcn_readfirstlane(p.b_split); dma_seg = p.b_seg_stride; }
   }
@@ -397,7 +415,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
 #pragma unroll
       for (int j = 0; j < NIB; ++j)
         if (((j + NIA) & 3) == q)
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(dma_b[j] + kb),
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(dma_b[j] + (BTR ? (int64_t)k0 * p.ldb : kb)),
                                            (__attribute__((address_space(3))) void*)(lds + soff + A_BYTES + (j * 4 + wave) * 1024), 16, 0, 0);
     }
   };
@@ -440,6 +458,20 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   const int nk = (p.K + BK - 1) / BK;
   const int lrow = lane & 31, lhalf = lane >> 5;
   int a_off[MT][BK / 16], b_off[NT][BK / 16];
+  int bt_off[BTR ? NT : 1][BK / 16][2];   // BTR: the two transposing reads (k 0..3, k 4..7) of a fragment
+  if constexpr (BTR) {
+    const int jj = lane & 15, g2 = (lane >> 4) & 1;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+          const int krow = kk * 16 + lhalf * 8 + r * 4 + (jj >> 2);
+          const int col = wn * WN + j * 32 + 16 * g2 + 4 * (jj & 3);
+          bt_off[j][kk][r] = A_BYTES + krow * BT_ROW + ((((col >> 3) ^ bt_swz(krow))) << 4) + (((col >> 2) & 1) << 3);
+        }
+  }
 #pragma unroll
   for (int kk = 0; kk < BK / 16; ++kk) {
 #pragma unroll
@@ -468,7 +500,18 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
 #pragma unroll
       for (int i = 0; i < MT; ++i) af[BUF][i] = *reinterpret_cast<const bf16x8_t*>(lds + a_off[i][kk] + SOFF);
 #pragma unroll
-      for (int j = 0; j < NT; ++j) bfr[BUF][j] = *reinterpret_cast<const bf16x8_t*>(lds + b_off[j][kk] + SOFF);
+      for (int j = 0; j < NT; ++j) {
+        if constexpr (BTR) {
+          typedef short s16x4_t __attribute__((ext_vector_type(4)));
+          typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+          union { s16x4_t h[2]; bf16x8_t f; } u;
+          u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + bt_off[j][kk][0] + SOFF));
+          u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + bt_off[j][kk][1] + SOFF));
+          bfr[BUF][j] = u.f;
+        } else {
+          bfr[BUF][j] = *reinterpret_cast<const bf16x8_t*>(lds + b_off[j][kk] + SOFF);
+        }
+      }
     };
     auto mfmas = [&](auto buf_tag) {
       constexpr int BUF = decltype(buf_tag)::value % NBUF;
@@ -746,7 +789,7 @@ void set_wide(GemmParams& p) {
 
 template <int BM, int BN, int WM, int WN, int PF, int DMA = 0>
 void launch_mfma_cfg(hipStream_t st, const GemmParams& p_in, const LaunchEvents& ev = LaunchEvents()) {
-  if (DMA && !(p_in.transA == 0 && p_in.transB != 0 && p_in.K % BK == 0)) {
+  if (DMA && !(p_in.transA == 0 && p_in.K % BK == 0)) {
     launch_mfma_cfg<BM, BN, WM, WN, PF, 0>(st, p_in, ev);
     return;
   }
@@ -759,11 +802,11 @@ void launch_mfma_cfg(hipStream_t st, const GemmParams& p_in, const LaunchEvents&
   do {                                                                                              \
     static bool attr_set = false;                                                                   \
     if (!attr_set) {                                                                                \
-      hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF, (KA && KB) ? DMA : 0>, \
+      hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF, KA ? DMA : 0>, \
                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);                         \
       attr_set = true;                                                                              \
     }                                                                                               \
-    hipExtLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF, (KA && KB) ? DMA : 0>), grid, dim3(256), LDS, st, \
+    hipExtLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WM, WN, KA, KB, PF, KA ? DMA : 0>), grid, dim3(256), LDS, st, \
                           ev.start, ev.stop, 0, p);                                                 \
   } while (0)
   if (kca && kcb) MM_GO(true, true);
