@@ -735,10 +735,21 @@ __device__ __forceinline__ int remap_xcd(int bid, int total) {
 }
 
 template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF, int DMA>
-__global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p) {
+__global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p_in) {
   extern __shared__ __align__(16) unsigned char lds[];
+  GemmParams p = p_in;
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-  const int L = remap_xcd(blockIdx.x, tiles_m * tiles_n);
+  int L = remap_xcd(blockIdx.x, gridDim.x);
+  if (p.k_splits > 1) {   // this workgroup's share of K: shift the operands, shorten K, pick the part
+    const int ks = L / (tiles_m * tiles_n);
+    L -= ks * tiles_m * tiles_n;
+    const int k0 = ks * p.k_chunk;
+    p.A = (const bf16_t*)p.A + (KCA ? (int64_t)k0 : (int64_t)k0 * p.lda);
+    p.B = (const bf16_t*)p.B + (KCB ? (int64_t)k0 : (int64_t)k0 * p.ldb);
+    p.K = min(p.k_chunk, p.K - k0);
+    p.C = (float*)p.C + (int64_t)ks * p.c_part_stride;
+    if (ks > 0) { p.bias = nullptr; p.residual = nullptr; }
+  }
   int tm, tn;
   // walk along the axis of the SMALLER operand: it is re-read from L2 while the larger one streams
   if ((int64_t)p.M <= (int64_t)p.N) { tm = L % tiles_m; tn = L / tiles_m; }
@@ -795,7 +806,7 @@ void launch_mfma_cfg(hipStream_t st, const GemmParams& p_in, const LaunchEvents&
   }
   GemmParams p = p_in;
   set_wide(p);
-  dim3 grid(((p.N + BN - 1) / BN) * ((p.M + BM - 1) / BM));
+  dim3 grid(((p.N + BN - 1) / BN) * ((p.M + BM - 1) / BM) * (p.k_splits > 1 ? p.k_splits : 1));
   constexpr int LDS = (DMA ? DMA : 2) * (BM + BN) * 128;
   const bool kca = !p.transA, kcb = p.transB != 0;
 #define MM_GO(KA, KB)                                                                               \
@@ -821,6 +832,9 @@ inline bool aligned16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr
 // The MFMA kernel takes 16-byte chunks along each operand's contiguous axis.
 bool mfma_eligible(const GemmParams& p) {
   if (p.K <= 0) return false;   // the K pipeline always loads its first tile
+  if (p.k_splits > 1 && (!p.out_f32 || p.b_split || p.c_split || p.relu || p.relu_mask || p.k_chunk % BK ||
+                         (int64_t)(p.k_splits - 1) * p.k_chunk >= p.K))
+    return false;
   if (!aligned16(p.A) || !aligned16(p.B)) return false;
   if (p.lda % 8 || p.ldb % 8) return false;
   if (!p.transA ? p.K % 8 : p.M % 8) return false;       // A's contiguous extent
@@ -837,6 +851,8 @@ bool mfma_eligible(const GemmParams& p) {
 }
 
 }  // namespace
+
+bool gemm_can_split_k(Dtype dt, const GemmParams& p) { return dt == BF16 && p.k_splits > 1 && mfma_eligible(p); }
 
 bool gemm_groupable(Dtype dt, const GemmParams& p) {
   return dt == BF16 && p.transA == 1 && p.transB == 0 && mfma_eligible(p);
@@ -899,7 +915,7 @@ void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p, const LaunchEven
     // Measured on the step's shapes: 128x128 tiles once they fill the chip, with two K steps of
     // loads in flight when there are several rounds of tiles or a long K; few output tiles and a
     // very long K (the generator's input gradient): 128x64; otherwise 64x64.
-    const long tiles_big = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
+    const long tiles_big = (long)((p.M + 127) / 128) * ((p.N + 127) / 128) * (p.k_splits > 1 ? p.k_splits : 1);
     if (tiles_big >= 192) {
       if (tiles_big >= 1024 || p.K >= 1024) launch_mfma_cfg<128, 128, 64, 64, 2>(st, p, ev);
       else launch_mfma_cfg<128, 128, 64, 64, 1>(st, p, ev);

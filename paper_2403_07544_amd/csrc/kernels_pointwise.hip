@@ -339,7 +339,8 @@ template <typename T, int NV>
 __global__ void __launch_bounds__(256) layernorm_bwd_kernel(
     const float* __restrict__ dy, const float* __restrict__ x, const float* __restrict__ mean,
     const float* __restrict__ rstd, const float* __restrict__ gamma, const float* __restrict__ dres,
-    float* __restrict__ dx_out, T* __restrict__ dxT_out, float* __restrict__ partial, int rows, int d) {
+    float* __restrict__ dx_out, T* __restrict__ dxT_out, float* __restrict__ partial, int rows, int d, int dy_parts,
+    int64_t dy_part_stride) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   float4 g[NV], ag[NV], ab[NV];
 #pragma unroll
@@ -359,7 +360,11 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(
       const int c = (lane << 2) + k * 256;
       if (c < d) {
         const float4 xv = Io<float>::ld4(x + (int64_t)row * d + c);
-        const float4 dv = Io<float>::ld4(dy + (int64_t)row * d + c);
+        float4 dv = Io<float>::ld4(dy + (int64_t)row * d + c);
+        for (int s = 1; s < dy_parts; ++s) {   // split-K partial sums of the producing product
+          const float4 t = Io<float>::ld4(dy + s * dy_part_stride + (int64_t)row * d + c);
+          dv.x += t.x; dv.y += t.y; dv.z += t.z; dv.w += t.w;
+        }
         xh[k].x = (xv.x - mu) * rs; xh[k].y = (xv.y - mu) * rs;
         xh[k].z = (xv.z - mu) * rs; xh[k].w = (xv.w - mu) * rs;
         ag[k].x += dv.x * xh[k].x; ag[k].y += dv.y * xh[k].y;
@@ -815,14 +820,15 @@ int ln_bwd_partial_rows(int rows) {
 
 void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float* x, const float* mean,
                           const float* rstd, const float* gamma, const float* dres, float* dx_out,
-                          void* dxT_out, float* partial, int rows, int d, const LaunchEvents& ev) {
+                          void* dxT_out, float* partial, int rows, int d, const LaunchEvents& ev, int dy_parts,
+                          int64_t dy_part_stride) {
   const int grid = ln_bwd_partial_rows(rows);
   if (dt == BF16) {
     MM_LN_DISPATCH(layernorm_bwd_kernel, bf16_t, dy, x, mean, rstd, gamma, dres, dx_out, (bf16_t*)dxT_out,
-                   partial, rows, d)
+                   partial, rows, d, dy_parts, dy_part_stride)
   } else {
     MM_LN_DISPATCH(layernorm_bwd_kernel, float, dy, x, mean, rstd, gamma, dres, dx_out, (float*)nullptr,
-                   partial, rows, d)
+                   partial, rows, d, dy_parts, dy_part_stride)
   }
 }
 

@@ -72,10 +72,18 @@ struct GemmParams {
   int64_t ldr;
   int out_f32;            // 1: C is fp32; 0: C has the working dtype
   int wide;               // set by the launcher: an operand spans 2 GiB or more (32-bit offsets unusable)
+  // Split K (a long reduction with too few output tiles to fill the chip): k_splits > 1 workgroups
+  // per tile, split s reducing k in [s * k_chunk, (s+1) * k_chunk) into the fp32 partial result
+  // C + s * c_part_stride; the consumer adds the parts.  Needs out_f32, no operand segments, and
+  // k_chunk a multiple of 64; bias and residual go into part 0 only.
+  int k_splits, k_chunk;
+  int64_t c_part_stride;
   float* colsum_dst;      // grouped weight-gradient launch only: [N] (segmented like C) += column
                           // sums of B over K, i.e. the bias gradient belonging to this product
 };
 void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p, const LaunchEvents& ev = LaunchEvents());
+// true if a product with k_splits > 1 set can run that way (otherwise launch it with k_splits = 0)
+bool gemm_can_split_k(Dtype dt, const GemmParams& p);
 // Weight-gradient products (transA = 1, transB = 0) of a whole step in one launch.  table_dev and
 // tile_start_dev are device arrays of n_problems entries; tile_start is the running sum of
 // gemm_grouped_tiles() and total_tiles its total.  Every problem must satisfy gemm_groupable().
@@ -123,10 +131,12 @@ void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float*
 // rows, partial[p][0][d] (gain) and partial[p][1][d] (shift); launch_ln_reduce_grouped adds them
 // into the buckets for many LayerNorms at once.
 int ln_bwd_partial_rows(int rows);
+// dy may arrive as dy_parts partial sums (dy + s * dy_part_stride, s < dy_parts) that are added here.
 void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float* x,
                           const float* mean, const float* rstd, const float* gamma,
                           const float* dres, float* dx_out, void* dxT_out, float* partial,
-                          int rows, int d, const LaunchEvents& ev = LaunchEvents());
+                          int rows, int d, const LaunchEvents& ev = LaunchEvents(), int dy_parts = 1,
+                          int64_t dy_part_stride = 0);
 struct LnReduceJob {
   const float* partial; float* dgamma; float* dbeta;
   int32_t n_partial, d, first_block, pad;   // first_block: running sum of ceil(2d/64)

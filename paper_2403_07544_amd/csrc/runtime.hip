@@ -211,13 +211,15 @@ struct Run {
   // The gain/shift gradient sums of all LayerNorms of the step are reduced in one launch at the end.
   std::vector<LnReduceJob>* ln_jobs = nullptr;
   void ln_bwd(const float* dy, const float* x, const float* mean, const float* rstd, const float* g,
-              const float* dres, float* dx, void* dxT, float* gg, float* gb, int rows) {
+              const float* dres, float* dx, void* dxT, float* gg, float* gb, int rows, int dy_parts = 1,
+              int64_t dy_part_stride = 0) {
     const int d = c->cfg.d_model;
     const int n_partial = ln_bwd_partial_rows(rows);
     float* partial = (float*)c->ws.take((size_t)n_partial * 2 * d * sizeof(float));
     if (dry) return;
     launch_layernorm_bwd(c->st, c->dt, dy, x, mean, rstd, g, dres, dx, c->dt == BF16 ? dxT : nullptr, partial, rows, d,
-                         begin_timed(MM_K_LAYERNORM_BWD, (double)rows * d * (12 + (dres ? 4 : 0) + (c->dt == BF16 ? 2 : 0))));
+                         begin_timed(MM_K_LAYERNORM_BWD, (double)rows * d * (12 + (dres ? 4 : 0) + (c->dt == BF16 ? 2 : 0))),
+                         dy_parts, dy_part_stride);
     LnReduceJob jb;
     jb.partial = partial; jb.dgamma = gg; jb.dbeta = gb; jb.n_partial = n_partial; jb.d = d;
     jb.first_block = 0; jb.pad = 0;
@@ -687,16 +689,24 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
   }
 
   // ---------------- backward: generator, decoder ----------------
-  float* dh = s.f32((size_t)U * d);
+  // The generator's input gradient reduces over the vocabulary into only U x d outputs: its K range
+  // is split over several workgroups per tile, each writing its own partial sum, and the
+  // LayerNorm backward that consumes dh adds the parts.
+  int dh_parts = 4;   // measured best of 1, 2, 4, 8 at V = 32000
+  float* dh = s.f32((size_t)U * d * dh_parts);   // (sized before the decision below: same in the measuring pass)
   {
     GemmParams p = s.gp_dgrad(z, V, pv_gen.W(0), d, V, dh, U);
     p.out_f32 = 1;
+    p.k_splits = dh_parts;
+    p.k_chunk = (((V + dh_parts - 1) / dh_parts) + 127) / 128 * 128;   // whole pairs of K steps
+    p.c_part_stride = (int64_t)U * d;
+    if (dh_parts < 2 || !gemm_can_split_k(c->dt, p)) { p.k_splits = 0; dh_parts = 1; }
     run.gemm(p);
     s.wgrad(s.gp_wgrad(h, d, z, V, pv_gen.G(0), d, V, U), pv_gen.G(1), nullptr);
   }
   Step::Grad g{s.f32((size_t)U * d), c->dt == BF16 ? s.act((size_t)U * d) : nullptr};
   run.ln_bwd(dh, y_dec_top, ln_decf.mean, ln_decf.rstd, pv_decf.V(0), nullptr, g.dx, g.dxT,
-             pv_decf.G(0), pv_decf.G(1), U);
+             pv_decf.G(0), pv_decf.G(1), U, dh_parts, (int64_t)U * d);
   if (c->dt != BF16) g.dxT = g.dx;
   float* dmem = s.f32((size_t)S * d);
   bool first = true;
