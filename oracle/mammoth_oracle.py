@@ -20,7 +20,10 @@ Pins (tests/test_oracle_*.py): central finite differences of the loss for every 
 tensor; an independent autograd transcription built from library layer_norm / softmax /
 cross_entropy / Adam; closed forms (ln V loss for equal logits, first Adam step, LayerNorm
 moments, single-key attention); structural identities (split stack == whole stack,
-zero adapter == no adapter, padding width, unused modules untouched).
+zero adapter == no adapter, padding width, unused modules untouched).  Routed inference
+(`forward_logits`, `greedy_decode`): the library transcription sentence by sentence, a greedy
+loop written over it, the training step's own logits, prefix and batch-independence
+properties, forced and forbidden EOS, equal top logits.
 """
 from __future__ import annotations
 
@@ -556,6 +559,81 @@ class Oracle:
         if self.keep_trace:
             self.trace["dx_src"], self.trace["dy_tgt"] = dx, dy
         return float(loss)
+
+    # ---- routed inference (section 3.2: translating a task needs only that task's modules) ---
+    def forward_logits(self, task: int, src_ids, src_len, dec_in, dec_len):
+        """Generator logits [B, U_max, V] of one task for given decoder inputs: the forward half
+        of `train_step` on its own (same modules in the same order, same masks), with nothing
+        cached and no bookkeeping touched.  Rows at or beyond dec_len[b] are meaningless."""
+        src_ids, dec_in = np.asarray(src_ids), np.asarray(dec_in)
+        s_len, u_len = np.asarray(src_len), np.asarray(dec_len)
+        i_src, enc_ids, i_tgt, dec_ids, i_gen, ad = self.parse_route(self.routes[task])
+        M = self.modules
+        dt = self.dtype.type
+        B, S_max = src_ids.shape
+        U_max = dec_in.shape[1]
+        src_real = np.arange(S_max)[None, :] < s_len[:, None]
+        dec_real = np.arange(U_max)[None, :] < u_len[:, None]
+        enc_blocked = np.broadcast_to(~src_real[:, None, :], (B, S_max, S_max))
+        causal = np.arange(U_max)[None, :] > np.arange(U_max)[:, None]
+        dec_blocked = causal[None, :, :] | ~dec_real[:, None, :]
+        cross_blocked = np.broadcast_to(~src_real[:, None, :], (B, U_max, S_max))
+
+        sqrt_d = dt(np.sqrt(self.d))
+        x = (sqrt_d * M[i_src].p("E")[src_ids] + self.pe[None, :S_max, :]) * src_real[:, :, None]
+        ad_e = M[ad["enc"]] if ad["enc"] is not None else None
+        li = 0
+        for j in enc_ids:
+            for i in range(M[j].n_layers):
+                x, _ = self._enc_layer_fwd(x, M[j], i, enc_blocked)
+                if ad_e is not None:
+                    x, _ = self._adapter_fwd(x, ad_e, li)
+                li += 1
+        m_last = M[enc_ids[-1]]
+        mem, _ = layernorm_fwd(x, m_last.p("lnf.g"), m_last.p("lnf.b"), self.ln_eps)
+
+        y = (sqrt_d * M[i_tgt].p("E")[dec_in] + self.pe[None, :U_max, :]) * dec_real[:, :, None]
+        ad_d = M[ad["dec"]] if ad["dec"] is not None else None
+        li = 0
+        for j in dec_ids:
+            for i in range(M[j].n_layers):
+                y, _ = self._dec_layer_fwd(y, mem, M[j], i, dec_blocked, cross_blocked)
+                if ad_d is not None:
+                    y, _ = self._adapter_fwd(y, ad_d, li)
+                li += 1
+        d_last = M[dec_ids[-1]]
+        h, _ = layernorm_fwd(y, d_last.p("lnf.g"), d_last.p("lnf.b"), self.ln_eps)
+        return linear_fwd(h, M[i_gen].p("Wg"), M[i_gen].p("bg"))
+
+    def greedy_decode(self, task: int, src_ids, src_len, max_new: int):
+        """Greedy translation, the slow way: for t = 0, 1, ... every sentence's decoder input is
+        BOS followed by the t tokens it has produced, the whole model is run again from the
+        source, and token t is the position-t logit row's largest entry (lowest index among
+        equal ones).  A sentence stops once it has produced EOS (EOS is kept, PAD follows);
+        it also stops after max_new tokens.  Returns (ids [B, max_new], produced counts [B]).
+        The paper fixes no search procedure; this is the plainest one and is the reading the
+        GPU path is held to."""
+        src_ids, s_len = np.asarray(src_ids), np.asarray(src_len)
+        B = src_ids.shape[0]
+        assert 1 <= max_new <= self.max_len
+        out = np.full((B, max_new), PAD, dtype=np.int32)
+        n_out = np.zeros(B, dtype=np.int32)
+        alive = np.ones(B, dtype=bool)
+        for t in range(max_new):
+            if not alive.any():
+                break
+            dec_in = np.concatenate([np.full((B, 1), BOS, dtype=np.int32), out[:, :t]], axis=1)
+            # a finished sentence keeps its shorter input; its later rows are never looked at
+            dec_len = np.where(alive, t + 1, np.maximum(n_out, 1)).astype(np.int32)
+            z = self.forward_logits(task, src_ids, s_len, dec_in, dec_len)
+            for b in range(B):
+                if alive[b]:
+                    tok = int(np.argmax(z[b, t]))       # numpy returns the first maximum
+                    out[b, t] = tok
+                    n_out[b] = t + 1
+                    if tok == EOS:
+                        alive[b] = False
+        return out, n_out
 
     # ---- renormalise and update (Algorithm 1 last line + Adam) ---------------------------
     def apply_update(self, module_ids: Optional[Sequence[int]], lr: float):

@@ -71,6 +71,20 @@ def tiny_oracle(setup=None, dtype=np.float64, perturbed=True, keep_trace=False) 
 def tiny_batch(setup: Setup, lengths=((5, 4), (3, 7), (8, 2), (1, 5)), seed=3):
     return mm_synth.data.small_batch(setup.shape.vocab, lengths, seed)
 
+def sharpen(orc: Oracle, scale: float, eos_shift: float):
+    """Freshly initialised weights are so small that what the decoder writes hardly depends on
+    the source.  Multiplying every matrix by `scale` makes the source, and the attention over
+    it, decide the output; `eos_shift` is added to each generator's EOS bias to move where
+    sentences stop.  (A test knob: trained weights are not available.)"""
+    for m in orc.modules:
+        if m.theta is None:
+            continue
+        for s in m.specs:
+            if len(s.shape) == 2:
+                m.p(s.name)[...] *= scale
+        if m.kind == "gen":
+            m.p("bg")[2] += eos_shift
+
 
 # ----------------------------------------------------------------------------------------
 def _pe(n, d):
@@ -101,6 +115,57 @@ def _ffn(x, W, w1, b1, w2, b2):
     return F.relu(x @ W[w1] + W[b1]) @ W[w2] + W[b2]
 
 
+def _sentence_logits(orc: Oracle, task: int, per_mod, src, dec_in):
+    """Generator logits [len(dec_in), V] of one unpadded sentence pair, built from library
+    layer_norm / softmax calls; `per_mod[j][name]` holds module j's tensors."""
+    d, H, eps = orc.d, orc.H, orc.ln_eps
+    i_src, enc_ids, i_tgt, dec_ids, i_gen, ad = orc.parse_route(orc.routes[task])
+
+    def ln(x, W, name):
+        return F.layer_norm(x, (d,), W[name + ".g"], W[name + ".b"], eps)
+
+    def adapter(x, stack, li):
+        if ad[stack] is None:
+            return x
+        W = per_mod[ad[stack]]
+        return x + _ffn(ln(x, W, f"l{li}.ln"), W, f"l{li}.Wd", f"l{li}.bd", f"l{li}.Wu", f"l{li}.bu")
+
+    x = math.sqrt(d) * per_mod[i_src]["E"][src] + _pe(len(src), d)
+    li = 0
+    for j in enc_ids:
+        W = per_mod[j]
+        for i in range(orc.modules[j].n_layers):
+            a = ln(x, W, f"l{i}.ln1")
+            x = x + _mha(a, a, W, f"l{i}.self", H, False)
+            x = x + _ffn(ln(x, W, f"l{i}.ln2"), W, f"l{i}.W1", f"l{i}.b1", f"l{i}.W2", f"l{i}.b2")
+            x = adapter(x, "enc", li)
+            li += 1
+    mem = ln(x, per_mod[enc_ids[-1]], "lnf")
+    y = math.sqrt(d) * per_mod[i_tgt]["E"][dec_in] + _pe(len(dec_in), d)
+    li = 0
+    for j in dec_ids:
+        W = per_mod[j]
+        for i in range(orc.modules[j].n_layers):
+            a = ln(y, W, f"l{i}.ln1")
+            y = y + _mha(a, a, W, f"l{i}.self", H, True)
+            y = y + _mha(ln(y, W, f"l{i}.ln2"), mem, W, f"l{i}.cross", H, False)
+            y = y + _ffn(ln(y, W, f"l{i}.ln3"), W, f"l{i}.W1", f"l{i}.b1", f"l{i}.W2", f"l{i}.b2")
+            y = adapter(y, "dec", li)
+            li += 1
+    h = ln(y, per_mod[dec_ids[-1]], "lnf")
+    return h @ per_mod[i_gen]["Wg"] + per_mod[i_gen]["bg"]
+
+
+def torch_reference_logits(orc: Oracle, task: int, src, dec_in) -> np.ndarray:
+    """Logits of one unpadded sentence pair from the library transcription, as float64."""
+    per_mod = {j: {s.name: torch.tensor(np.array(orc.modules[j].p(s.name), dtype=np.float64))
+                   for s in orc.modules[j].specs} for j in orc.routes[task]}
+    with torch.no_grad():
+        z = _sentence_logits(orc, task, per_mod, torch.tensor(np.asarray(src, dtype=np.int64)),
+                             torch.tensor(np.asarray(dec_in, dtype=np.int64)))
+    return z.numpy()
+
+
 def torch_reference_step(orc: Oracle, task: int, batch) -> Tuple[float, Dict[Tuple[int, str], np.ndarray]]:
     """Loss and gradient of every tensor of every module on the task's route."""
     d, H, eps = orc.d, orc.H, orc.ln_eps
@@ -114,44 +179,12 @@ def torch_reference_step(orc: Oracle, task: int, batch) -> Tuple[float, Dict[Tup
             leaves[(j, s.name)] = t
             per_mod[j][s.name] = t
 
-    def ln(x, W, name):
-        return F.layer_norm(x, (d,), W[name + ".g"], W[name + ".b"], eps)
-
-    def adapter(x, stack, li):
-        if ad[stack] is None:
-            return x
-        W = per_mod[ad[stack]]
-        return x + _ffn(ln(x, W, f"l{li}.ln"), W, f"l{li}.Wd", f"l{li}.bd", f"l{li}.Wu", f"l{li}.bu")
-
     logits, labels = [], []
     for b in range(len(batch.lengths)):
         s_b, t_b = int(batch.lengths[b, 0]), int(batch.lengths[b, 1])
         src = torch.tensor(batch.src_ids[b, :s_b].astype(np.int64))
         tgt = torch.tensor(batch.tgt_ids[b, :t_b].astype(np.int64))
-        x = math.sqrt(d) * per_mod[i_src]["E"][src] + _pe(s_b, d)
-        li = 0
-        for j in enc_ids:
-            W = per_mod[j]
-            for i in range(orc.modules[j].n_layers):
-                a = ln(x, W, f"l{i}.ln1")
-                x = x + _mha(a, a, W, f"l{i}.self", H, False)
-                x = x + _ffn(ln(x, W, f"l{i}.ln2"), W, f"l{i}.W1", f"l{i}.b1", f"l{i}.W2", f"l{i}.b2")
-                x = adapter(x, "enc", li)
-                li += 1
-        mem = ln(x, per_mod[enc_ids[-1]], "lnf")
-        y = math.sqrt(d) * per_mod[i_tgt]["E"][tgt[:-1]] + _pe(t_b - 1, d)
-        li = 0
-        for j in dec_ids:
-            W = per_mod[j]
-            for i in range(orc.modules[j].n_layers):
-                a = ln(y, W, f"l{i}.ln1")
-                y = y + _mha(a, a, W, f"l{i}.self", H, True)
-                y = y + _mha(ln(y, W, f"l{i}.ln2"), mem, W, f"l{i}.cross", H, False)
-                y = y + _ffn(ln(y, W, f"l{i}.ln3"), W, f"l{i}.W1", f"l{i}.b1", f"l{i}.W2", f"l{i}.b2")
-                y = adapter(y, "dec", li)
-                li += 1
-        h = ln(y, per_mod[dec_ids[-1]], "lnf")
-        logits.append(h @ per_mod[i_gen]["Wg"] + per_mod[i_gen]["bg"])
+        logits.append(_sentence_logits(orc, task, per_mod, src, tgt[:-1]))
         labels.append(tgt[1:])
     loss = F.cross_entropy(torch.cat(logits), torch.cat(labels), label_smoothing=orc.eps_ls,
                            reduction="mean")
