@@ -123,6 +123,22 @@ mm_status mm_train_step(mm_ctx* ctx, int32_t task, const int32_t* src_ids, const
                         const int32_t* lengths, int32_t B, int32_t S_max, int32_t T_max,
                         int32_t ids_mem, float* out_loss);
 
+/* Greedy translation of one batch of one task with the task's own modules only (section 3.2,
+ * "inference": a task needs just its modules loaded; no other module's memory is read, and no
+ * bucket, use count or Adam state is written).  The search itself is the plainest one: every
+ * sentence starts from BOS (id 1); each step feeds the last token back, takes the largest
+ * generator logit (the lowest id among equal ones) and stops the sentence at EOS (id 2) or after
+ * max_new tokens.
+ *   src_ids [B, S_max] row-major int32 as for mm_train_step (ids_mem: MM_HOST or MM_DEVICE).
+ *   src_lengths [B] int32 (host), 1 <= s_b <= S_max <= max_len;  1 <= max_new <= max_len.
+ *   out_ids [B, max_new] int32 (host, caller-owned): produced ids, EOS included, then pad (0).
+ *   out_lengths [B] int32 (host): number of ids produced per sentence.
+ * Synchronous: returns when the outputs are written.  A training step still in flight is
+ * waited for first.  Errors as for mm_train_step; on error the outputs are unspecified. */
+mm_status mm_translate_greedy(mm_ctx* ctx, int32_t task, const int32_t* src_ids, const int32_t* src_lengths,
+                              int32_t B, int32_t S_max, int32_t max_new, int32_t ids_mem,
+                              int32_t* out_ids, int32_t* out_lengths);
+
 /* Waits for the most recent mm_train_step and returns its loss and status. */
 mm_status mm_last_loss(mm_ctx* ctx, float* out_loss);
 

@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmammoth_hip.so")
-SOURCES = ["runtime.hip", "kernels_pointwise.hip", "kernels_gemm.hip", "kernels_attention.hip"]
+SOURCES = ["runtime.hip", "kernels_pointwise.hip", "kernels_gemm.hip", "kernels_attention.hip",
+           "kernels_decode.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result", "-Wno-unused-value"]
 

@@ -190,6 +190,21 @@ static const int ADAM_CHUNK = 4096;
 void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int total_chunks,
                  float lr, float beta1, float beta2, float eps, const LaunchEvents& ev = LaunchEvents());
 
+// ---------------------------------------------------------------------------------------------
+// greedy translation: one new query per sentence over cached keys/values; next-token pick
+// ---------------------------------------------------------------------------------------------
+// o[b, h*dh..] = softmax(q_b K_b^T / sqrt(dh)) V_b.  q row b at q + b*q_stride, o likewise.
+// Keys/values: rows of stride ldkv; sentence b owns rows cu[b]..cu[b+1] or, with cu null, rows
+// b*seq_rows .. b*seq_rows + len_uniform.  max_len bounds every sentence's key count.
+void launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_stride, const void* k, const void* v,
+                        int64_t ldkv, const int32_t* cu, int64_t seq_rows, int len_uniform, int max_len,
+                        void* o, int64_t o_stride, int B, int H, int dh);
+// Row-wise arg-max of z [B, V] (lowest index among equal entries) for the sentences with
+// done[b] == 0: out_ids[b, t] = cur_tok[b] = token, out_len[b] = t+1; EOS sets done[b] and
+// adds one to n_done[0].
+void launch_greedy_pick(hipStream_t st, Dtype dt, const void* z, int B, int V, int t, int max_new, int eos,
+                        int32_t* cur_tok, int32_t* done, int32_t* out_ids, int32_t* out_len, int32_t* n_done);
+
 // fp32 -> bf16 copy (working weights) and fill
 void launch_to_bf16(hipStream_t st, const float* src, bf16_t* dst, int64_t n);
 void launch_fill_f32(hipStream_t st, float* dst, int64_t n, float v);

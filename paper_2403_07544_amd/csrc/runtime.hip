@@ -748,6 +748,155 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
 
 bool valid_module(mm_ctx* c, int id) { return id >= 0 && id < (int)c->mods.size(); }
 
+// ---------------------------------------------------------------------------------------------
+// Greedy translation of one batch of one task (section 3.2: only the task's own modules are
+// read).  The encoder runs once; each decoder layer keeps the q|k|v rows of the tokens written
+// so far ([B][max_new][3d]) and the key/value projection of the encoder output, so a step
+// works on one new row per sentence.  Runs twice like the training step: measuring, then real.
+// ---------------------------------------------------------------------------------------------
+struct TranslateOut { int32_t* ids; int32_t* len; };
+
+mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src_lens, int max_new,
+                        TranslateOut& out) {
+  Step s;
+  s.c = c; s.run = Run{c, dry}; s.rt = &rt;
+  s.d = c->cfg.d_model; s.H = c->cfg.n_heads; s.F = c->cfg.d_ff; s.V = c->cfg.vocab; s.dh = s.d / s.H;
+  s.S = c->S; s.U = c->B; s.B = c->B; s.esz = c->dt == BF16 ? 2 : 4;
+  s.max_s = 0; s.max_u = 1;
+  for (int b = 0; b < c->B; ++b) {
+    const double sl = src_lens[b];
+    s.sum_ss += sl * sl; s.sum_us += sl; s.sum_uu += 1;
+    if (sl > s.max_s) s.max_s = (int)sl;
+  }
+  const int d = s.d, S = s.S, B = s.B, V = s.V, H = s.H, dh = s.dh;
+  const size_t esz = s.esz;
+  Run& run = s.run;
+  if (!dry) run.mark();
+  c->ws.reset(dry);
+  const float sqrt_d = sqrtf((float)d);
+  Module& m_src = c->mods[rt.src];
+  Module& m_tgt = c->mods[rt.tgt];
+  Module& m_gen = c->mods[rt.gen];
+  auto emb_w = [&](Module& m) -> const void* { return c->dt == BF16 ? (const void*)m.w16 : (const void*)m.theta; };
+
+  // ---------------- encoder, once ----------------
+  float* x = s.f32((size_t)S * d);
+  if (!dry) launch_embed_fwd(c->st, c->dt, emb_w(m_src), c->pe, c->src_tok, c->src_pos, x, S, d, sqrt_d);
+  int li = 0;
+  for (int mid : rt.enc) {
+    Module& m = c->mods[mid];
+    for (int l = 0; l < m.n_layers; ++l, ++li) {
+      PV pv{c, &m, l * ENC_T};
+      x = s.self_fwd(pv, 0, x, S, false).x_out;
+      x = s.ffn_fwd(pv, 10, x, S, s.F).x_out;
+      if (rt.ad_enc >= 0) x = s.ffn_fwd(PV{c, &c->mods[rt.ad_enc], li * ADP_T}, 0, x, S, c->mods[rt.ad_enc].adapter_dim).x_out;
+    }
+  }
+  Module& m_enc_last = c->mods[rt.enc.back()];
+  PV pv_encf{c, &m_enc_last, m_enc_last.n_layers * ENC_T};
+  void* mem = s.act((size_t)S * d);
+  run.ln_fwd(x, pv_encf.V(0), pv_encf.V(1), mem, s.f32(S), s.f32(S), S);
+
+  // ---------------- per decoder layer: key/value projection of the encoder output, token cache ----
+  struct DecLayer { PV pv; bool has_adapter; PV apv; char* kv_mem; char* cache; };
+  std::vector<DecLayer> layers;
+  li = 0;
+  for (int mid : rt.dec) {
+    Module& m = c->mods[mid];
+    for (int l = 0; l < m.n_layers; ++l, ++li) {
+      DecLayer L;
+      L.pv = PV{c, &m, l * DEC_T};
+      L.has_adapter = rt.ad_dec >= 0;
+      if (L.has_adapter) L.apv = PV{c, &c->mods[rt.ad_dec], li * ADP_T};
+      L.kv_mem = (char*)s.act((size_t)S * 2 * d);
+      L.cache = (char*)s.act((size_t)B * max_new * 3 * d);
+      const int64_t seg = L.pv.off(10 + 6) - L.pv.off(10 + 4);
+      GemmParams p = s.gp(mem, d, L.pv.W(10 + 4), d, L.kv_mem, 2 * d, S, 2 * d, d);
+      p.b_split = d; p.b_seg_stride = seg; p.bias = L.pv.V(10 + 5); p.bias_split = d; p.bias_seg_stride = seg;
+      run.gemm(p);
+      layers.push_back(L);
+    }
+  }
+  Module& m_dec_last = c->mods[rt.dec.back()];
+  PV pv_decf{c, &m_dec_last, m_dec_last.n_layers * DEC_T};
+  PV pv_gen{c, &m_gen, 0};
+
+  // ---------------- decoding state ----------------
+  int32_t* state = (int32_t*)c->ws.take(((size_t)4 * B + 1 + (size_t)B * max_new) * 4);
+  int32_t* cur_tok = state;            // next decoder input (BOS first)
+  int32_t* cur_pos = state + B;        // its position, the same for every sentence
+  int32_t* done = state + 2 * B;
+  out.len = state + 3 * B;
+  int32_t* n_done = state + 4 * B;
+  out.ids = n_done + 1;
+  if (!dry) {
+    launch_fill_i32(c->st, cur_tok, B, 1 /* BOS */);
+    launch_fill_i32(c->st, done, 2 * (size_t)B + 1 + (size_t)B * max_new, 0);   // done, len, n_done, ids
+  }
+  int32_t* n_done_host = (int32_t*)c->result_host + 8;
+  const int64_t row3 = (int64_t)3 * d;                 // one cached row: q | k | v
+  const int64_t seq3 = row3 * max_new;                 // one sentence's cache
+  const size_t step_mark = c->ws.off;
+  for (int t = 0; t < max_new; ++t) {
+    c->ws.off = step_mark;                             // every step reuses the same buffers
+    float* y = s.f32((size_t)B * d);
+    if (!dry) {
+      launch_fill_i32(c->st, cur_pos, B, t);
+      launch_embed_fwd(c->st, c->dt, emb_w(m_tgt), c->pe, cur_tok, cur_pos, y, B, d, sqrt_d);
+    }
+    for (DecLayer& L : layers) {
+      const PV& pv = L.pv;
+      // self-attention over the tokens so far (row t of the cache is written by the projection)
+      void* a = s.act((size_t)B * d);
+      run.ln_fwd(y, pv.V(0), pv.V(1), a, s.f32(B), s.f32(B), B);
+      char* row_t = L.cache + (size_t)t * row3 * esz;
+      int64_t seg = pv.off(4) - pv.off(2);
+      GemmParams p = s.gp(a, d, pv.W(2), d, row_t, seq3, B, 3 * d, d);
+      p.b_split = d; p.b_seg_stride = seg; p.bias = pv.V(3); p.bias_split = d; p.bias_seg_stride = seg;
+      run.gemm(p);
+      void* o = s.act((size_t)B * d);
+      if (!dry)
+        launch_attn_decode(c->st, c->dt, row_t, seq3, L.cache + (size_t)d * esz, L.cache + (size_t)2 * d * esz, row3,
+                           nullptr, max_new, t + 1, max_new, o, d, B, H, dh);
+      float* y1 = s.f32((size_t)B * d);
+      p = s.gp(o, d, pv.W(8), d, y1, d, B, d, d);
+      p.bias = pv.V(9); p.residual = y; p.ldr = d; p.out_f32 = 1;
+      run.gemm(p);
+      // attention over the encoder output
+      a = s.act((size_t)B * d);
+      run.ln_fwd(y1, pv.V(10), pv.V(11), a, s.f32(B), s.f32(B), B);
+      void* q = s.act((size_t)B * d);
+      p = s.gp(a, d, pv.W(12), d, q, d, B, d, d);
+      p.bias = pv.V(13);
+      run.gemm(p);
+      o = s.act((size_t)B * d);
+      if (!dry)
+        launch_attn_decode(c->st, c->dt, q, d, L.kv_mem, L.kv_mem + (size_t)d * esz, 2 * d, c->cu_s, 0, 0, s.max_s, o,
+                           d, B, H, dh);
+      float* y2 = s.f32((size_t)B * d);
+      p = s.gp(o, d, pv.W(18), d, y2, d, B, d, d);
+      p.bias = pv.V(19); p.residual = y1; p.ldr = d; p.out_f32 = 1;
+      run.gemm(p);
+      y = s.ffn_fwd(pv, 20, y2, B, s.F).x_out;
+      if (L.has_adapter) y = s.ffn_fwd(L.apv, 0, y, B, c->mods[rt.ad_dec].adapter_dim).x_out;
+    }
+    void* h = s.act((size_t)B * d);
+    run.ln_fwd(y, pv_decf.V(0), pv_decf.V(1), h, s.f32(B), s.f32(B), B);
+    void* z = s.act((size_t)B * V);
+    GemmParams p = s.gp(h, d, pv_gen.W(0), V, z, V, B, V, d);
+    p.bias = pv_gen.V(1);
+    run.gemm(p);
+    if (dry) break;                                    // one step measures them all
+    launch_greedy_pick(c->st, c->dt, z, B, V, t, max_new, 2 /* EOS */, cur_tok, done, out.ids, out.len, n_done);
+    if ((t & 7) == 7 && t + 1 < max_new) {             // now and then: has every sentence finished?
+      HIP_TRY(c, hipMemcpyAsync(n_done_host, n_done, 4, hipMemcpyDeviceToHost, c->st));
+      HIP_TRY(c, hipStreamSynchronize(c->st));
+      if (*n_done_host >= B) break;
+    }
+  }
+  return MM_OK;
+}
+
 mm_status parse_route(mm_ctx* c, const int32_t* ids, int n, Route& r) {
   for (int i = 0; i < n; ++i)
     if (!valid_module(c, ids[i])) return fail(c, MM_EINVAL, "route names unknown module id %d", ids[i]);
@@ -1060,6 +1209,88 @@ mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const i
     *out_loss = c->last_loss;
     return s;
   }
+  return MM_OK;
+}
+
+mm_status mm_translate_greedy(mm_ctx* c, int32_t task, const int32_t* src_ids, const int32_t* src_lengths, int32_t B,
+                              int32_t S_max, int32_t max_new, int32_t ids_mem, int32_t* out_ids, int32_t* out_lengths) {
+  if (!c) return MM_EINVAL;
+  if (!src_ids || !src_lengths || !out_ids || !out_lengths) return fail(c, MM_EINVAL, "null pointer");
+  if (task < 0 || task >= (int)c->routes.size()) return fail(c, MM_EINVAL, "unknown task %d", task);
+  if (ids_mem != MM_HOST && ids_mem != MM_DEVICE) return fail(c, MM_EINVAL, "ids_mem must be MM_HOST or MM_DEVICE");
+  if (B < 1 || S_max < 1 || max_new < 1) return fail(c, MM_EINVAL, "empty batch");
+  if (S_max > c->cfg.max_len || max_new > c->cfg.max_len)
+    return fail(c, MM_ERANGE, "padded width or output limit exceeds max_len %d", c->cfg.max_len);
+  int64_t S = 0;
+  for (int b = 0; b < B; ++b) {
+    const int sl = src_lengths[b];
+    if (sl < 1 || sl > S_max) return fail(c, MM_ERANGE, "sentence %d has length %d outside [1,%d]", b, sl, S_max);
+    S += sl;
+  }
+  if (S > c->cfg.max_batch_tokens || B > c->cfg.max_batch_tokens)
+    return fail(c, MM_ERANGE, "batch holds %lld source tokens, limit %d", (long long)S, c->cfg.max_batch_tokens);
+  if (ids_mem == MM_HOST) {
+    const int V = c->cfg.vocab;
+    for (int b = 0; b < B; ++b)
+      for (int i = 0; i < S_max; ++i) {
+        const int id = src_ids[(size_t)b * S_max + i];
+        if (i < src_lengths[b] ? (id < 0 || id >= V) : id != 0)
+          return fail(c, MM_ERANGE, "source id %d at sentence %d position %d", id, b, i);
+      }
+  }
+  if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context cannot compute");
+  resolve_pending(c);   // a training step still in flight owns the workspace and the id tables
+
+  // The packing kernel of the training step is reused with a two-token target (BOS EOS) per
+  // sentence: one decoder row each, whose token it sets to BOS.
+  const size_t n_meta = (size_t)2 * B + 2 * ((size_t)B + 1);
+  const size_t n_src = ids_mem == MM_HOST ? (size_t)B * S_max : 0;
+  const size_t n_ids = n_src + (size_t)2 * B;
+  HIP_TRY(c, hipEventSynchronize(c->ev_stage));
+  mm_status s = ensure_stage(c, n_meta + n_ids);
+  if (s != MM_OK) return s;
+  s = ensure_ids_dev(c, n_ids);
+  if (s != MM_OK) return s;
+  int32_t* st_lens = c->stage;
+  int32_t* st_cu_s = st_lens + 2 * B;
+  int32_t* st_cu_u = st_cu_s + B + 1;
+  int32_t* st_ids = st_cu_u + B + 1;
+  st_cu_s[0] = 0; st_cu_u[0] = 0;
+  for (int b = 0; b < B; ++b) {
+    st_lens[2 * b] = src_lengths[b]; st_lens[2 * b + 1] = 2;
+    st_cu_s[b + 1] = st_cu_s[b] + src_lengths[b];
+    st_cu_u[b + 1] = b + 1;
+    st_ids[n_src + 2 * b] = 1; st_ids[n_src + 2 * b + 1] = 2;
+  }
+  if (ids_mem == MM_HOST) memcpy(st_ids, src_ids, n_src * 4);
+  HIP_TRY(c, hipMemcpyAsync(c->ids_dev, st_ids, n_ids * 4, hipMemcpyHostToDevice, c->st));
+  const int32_t* src_dev = ids_mem == MM_HOST ? c->ids_dev : src_ids;
+  const int32_t* tgt_dev = c->ids_dev + n_src;
+  c->B = B; c->S_max = S_max; c->T_max = 2; c->S = (int)S; c->U = B;
+  const Route& rt = c->routes[task];
+  TranslateOut out{nullptr, nullptr};
+  run_translate(c, rt, true, src_lengths, max_new, out);
+  s = ensure_ws(c, c->ws.high);
+  if (s != MM_OK) return s;
+  HIP_TRY(c, hipMemcpyAsync(c->lens, st_lens, (size_t)2 * B * 4, hipMemcpyHostToDevice, c->st));
+  HIP_TRY(c, hipMemcpyAsync(c->cu_s, st_cu_s, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, c->st));
+  HIP_TRY(c, hipMemcpyAsync(c->cu_u, st_cu_u, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, c->st));
+  HIP_TRY(c, hipEventRecord(c->ev_stage, c->st));
+  launch_fill_i32(c->st, c->flag, 1, 0);
+  launch_pack_ids(c->st, src_dev, tgt_dev, c->lens, c->cu_s, c->cu_u, B, S_max, 2, c->cfg.vocab, c->src_tok,
+                  c->src_pos, c->dec_tok, c->dec_pos, c->label, c->flag);
+  s = run_translate(c, rt, false, src_lengths, max_new, out);
+  if (s != MM_OK) return s;
+  HIP_TRY(c, hipGetLastError());
+  int32_t* flag_host = (int32_t*)c->result_host + 9;
+  HIP_TRY(c, hipMemcpyAsync(flag_host, c->flag, 4, hipMemcpyDeviceToHost, c->st));
+  HIP_TRY(c, hipMemcpyAsync(out_ids, out.ids, (size_t)B * max_new * 4, hipMemcpyDeviceToHost, c->st));
+  HIP_TRY(c, hipMemcpyAsync(out_lengths, out.len, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  if (c->prof && c->prof_recs.size() > 8192) collect_profile(c);
+  if (*flag_host != 0)
+    return fail(c, MM_ERANGE, *flag_host & 1 ? "token id outside [0, vocab) (found on the device); output is meaningless"
+                                             : "non-pad id after the end of a sentence (found on the device); output is meaningless");
   return MM_OK;
 }
 
