@@ -55,6 +55,46 @@ def cpu_baseline(setup, batch, target_tokens=4096):
                       f"({tok} target tokens) of one batch, {dt:.1f} s"}
 
 
+def bench_translate(args, setup, ctx, batch):
+    """One step = one call of mm_translate_greedy on one batch's source sentences."""
+    import numpy as np
+    import torch
+    sh = setup.shape
+    max_new = args.translate
+    tasks = list(range(min(len(setup.tasks), 4)))
+    for gen in sorted({j for t in tasks for j in ctx.mm_get_route(t) if setup.modules[j].kind == "gen"}):
+        layout, _ = ctx.mm_get_layout(gen)               # generator bucket: matrix [d, V], then bias [V]
+        w = ctx.mm_get_params(gen)
+        w[layout[1][1] + 2] = -1e3                       # no EOS: every sentence runs every step
+        ctx.mm_set_params(gen, w)
+    src = torch.tensor(batch.src_ids, dtype=torch.int32, device="cuda")
+    s_len = batch.lengths[:, 0].copy()
+    B = len(s_len)
+    directions = [tasks[k % len(tasks)] for k in range(args.warmup + args.steps)]
+    for k in range(args.warmup):
+        ctx.mm_translate_greedy(directions[k], src, s_len, max_new)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.warmup, args.warmup + args.steps):
+        ids, n = ctx.mm_translate_greedy(directions[k], src, s_len, max_new)
+    elapsed = time.perf_counter() - t0
+    assert (n == max_new).all()
+    ctx.mm_profile(True)
+    ctx.mm_translate_greedy(directions[0], src, s_len, max_new)
+    prof = ctx.mm_profile_read()
+    ctx.mm_profile(False)
+    classes = {name: {"ms_per_call": r["ms"], "launches_per_call": r["launches"]}
+               for name, r in prof.items() if r["launches"]}
+    print(json.dumps({
+        "metric": "greedy translation tokens/s per MI355X (routed inference)", "value": B * max_new * args.steps / elapsed,
+        "unit": "generated tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / args.steps, "ms_per_decoding_step": 1e3 * elapsed / args.steps / max_new,
+        "higher_is_better": True, "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}]: {setup.title}; {B} sentences, {int(s_len.sum())} source "
+                               f"tokens, {max_new} tokens written per sentence"},
+        "kernel_classes": classes}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,6 +103,9 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--accumulate", type=int, default=1, help="routed passes per update")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--translate", type=int, default=0, metavar="MAX_NEW",
+                    help="time routed greedy translation instead of training: every sentence of one batch "
+                         "writes MAX_NEW tokens (EOS is suppressed so the work is fixed)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a kernel of known traffic, used to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -87,6 +130,9 @@ def main():
     batches = mm_synth.make_batches(setup)
     directions = mm_synth.sample_directions(setup, n_steps)
     ctx = context_from_setup(setup, fill_params=mm_synth.fill_params)
+
+    if args.translate:
+        return bench_translate(args, setup, ctx, batches[0])
 
     # inputs resident in HBM before timing
     dev = []

@@ -59,6 +59,129 @@ attn_decode_kernel(const T* __restrict__ q, int64_t q_stride, const T* __restric
   }
 }
 
+// 16 bytes of a row as floats: 8 bf16 or 4 fp32.
+template <typename T> struct Vec16;
+template <> struct Vec16<bf16_t> {
+  static constexpr int N = 8;
+  __device__ static void ld(const bf16_t* p, float* out) {
+    const uint4 r = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[2 * i] = __uint_as_float(w[i] << 16);
+      out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  __device__ static void ld(const float* p, float* out) {
+    const float4 r = *reinterpret_cast<const float4*>(p);
+    out[0] = r.x; out[1] = r.y; out[2] = r.z; out[3] = r.w;
+  }
+};
+
+// Same contract as attn_decode_kernel for head sizes that are a power of two of 16-byte chunks.
+// LPK = dh / Vec16::N lanes share one key, so a wavefront covers 64/LPK keys per pass with
+// 16-byte loads that neighbouring lanes take from neighbouring addresses; four wavefronts and
+// two passes in flight make a chunk of 8 * 64/LPK keys whose loads are all issued before the
+// first is used (a sentence's keys are few: the kernel's time is memory latency, paid once
+// per chunk instead of once per key).  The first chunk's values are fetched with its keys.
+template <typename T, int LPK>
+__global__ void __launch_bounds__(256)
+attn_decode_vec_kernel(const T* __restrict__ q, int64_t q_stride, const T* __restrict__ k, const T* __restrict__ v,
+                       int64_t ldkv, const int32_t* __restrict__ cu, int64_t seq_rows, int len_uniform,
+                       T* __restrict__ o, int64_t o_stride, float scale) {
+  constexpr int N = Vec16<T>::N, KPP = 64 / LPK, dh = LPK * N, WAVES = 4, UNR = 2, CH = KPP * WAVES * UNR;
+  extern __shared__ float smem[];
+  float* red = smem;               // [2][WAVES] maxima, sums
+  float* accs = smem + 2 * WAVES;  // [WAVES][dh]
+  float* p = accs + WAVES * dh;    // [len] scaled scores
+  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane % LPK, g = lane / LPK;
+  const int64_t row0 = cu ? (int64_t)cu[b] : (int64_t)b * seq_rows;
+  const int len = cu ? cu[b + 1] - cu[b] : len_uniform;
+  const int64_t col = (int64_t)h * dh + c * N;
+  float qv[N], vv0[UNR][N];
+  Vec16<T>::ld(q + (int64_t)b * q_stride + col, qv);
+#pragma unroll
+  for (int u = 0; u < UNR; ++u) {
+    const int j = (u * WAVES + wave) * KPP + g;
+    Vec16<T>::ld(v + (row0 + (j < len ? j : len - 1)) * ldkv + col, vv0[u]);
+  }
+  float mx = -INFINITY;
+  for (int j0 = 0; j0 < len; j0 += CH) {
+    float kv[UNR][N];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int j = j0 + (u * WAVES + wave) * KPP + g;
+      Vec16<T>::ld(k + (row0 + (j < len ? j : len - 1)) * ldkv + col, kv[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int j = j0 + (u * WAVES + wave) * KPP + g;
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < N; ++e) s = fmaf(qv[e], kv[u][e], s);
+#pragma unroll
+      for (int off = LPK / 2; off; off >>= 1) s += __shfl_xor(s, off);
+      s *= scale;
+      if (j < len) {
+        if (c == 0) p[j] = s;
+        mx = fmaxf(mx, s);
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float acc[N];
+#pragma unroll
+  for (int e = 0; e < N; ++e) acc[e] = 0.f;
+  float sum = 0.f;
+  for (int j0 = 0; j0 < len; j0 += CH) {
+    float vv[UNR][N];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int j = j0 + (u * WAVES + wave) * KPP + g;
+      if (j0 == 0) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) vv[u][e] = vv0[u][e];
+      } else {
+        Vec16<T>::ld(v + (row0 + (j < len ? j : len - 1)) * ldkv + col, vv[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int j = j0 + (u * WAVES + wave) * KPP + g;
+      const float w = j < len ? __expf(p[j] - mx) : 0.f;
+#pragma unroll
+      for (int e = 0; e < N; ++e) acc[e] = fmaf(w, vv[u][e], acc[e]);
+      if (c == 0) sum += w;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off; off >>= 1) sum += __shfl_xor(sum, off);
+#pragma unroll
+  for (int off = 32; off >= LPK; off >>= 1) {
+#pragma unroll
+    for (int e = 0; e < N; ++e) acc[e] += __shfl_xor(acc[e], off);
+  }
+  if (g == 0) {
+#pragma unroll
+    for (int e = 0; e < N; ++e) accs[wave * dh + c * N + e] = acc[e];
+  }
+  if (lane == 0) red[WAVES + wave] = sum;
+  __syncthreads();
+  for (int e = tid; e < dh; e += 256) {
+    const float tot = (red[WAVES] + red[WAVES + 1]) + (red[WAVES + 2] + red[WAVES + 3]);
+    const float val = (accs[e] + accs[dh + e]) + (accs[2 * dh + e] + accs[3 * dh + e]);
+    stf(o + (int64_t)b * o_stride + h * dh + e, val / tot);
+  }
+}
+
 // One workgroup per sentence: the largest logit of row b, lowest index among equal ones.
 // A sentence that has finished is left alone.  Otherwise the token is written to out_ids[b, t],
 // becomes the next decoder input, and EOS marks the sentence finished (n_done counts them).
@@ -74,9 +197,30 @@ greedy_pick_kernel(const T* __restrict__ z, int V, int t, int max_new, int eos, 
   const T* row = z + (int64_t)b * V;
   float best = -INFINITY;
   int best_i = V;   // stays V only if the row holds nothing comparable (all NaN)
-  for (int i = tid; i < V; i += 256) {
-    const float x = ldf(row + i);
-    if (x > best || (x == best && i < best_i)) { best = x; best_i = i; }
+  constexpr int N = Vec16<T>::N;
+  if (V % N == 0 && (reinterpret_cast<uintptr_t>(z) & 15) == 0) {   // rows start on 16-byte boundaries
+    for (int i0 = tid * N; i0 < V; i0 += 4 * 256 * N) {       // four loads in flight
+      float x[4][N];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * 256 * N;
+        Vec16<T>::ld(row + (i < V ? i : i0), x[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * 256 * N;
+        if (i < V) {
+#pragma unroll
+          for (int e = 0; e < N; ++e)
+            if (x[u][e] > best || (x[u][e] == best && i + e < best_i)) { best = x[u][e]; best_i = i + e; }
+        }
+      }
+    }
+  } else {
+    for (int i = tid; i < V; i += 256) {
+      const float x = ldf(row + i);
+      if (x > best || (x == best && i < best_i)) { best = x; best_i = i; }
+    }
   }
   s_val[tid] = best; s_idx[tid] = best_i;
   __syncthreads();
@@ -104,8 +248,27 @@ void launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_strid
                         int64_t ldkv, const int32_t* cu, int64_t seq_rows, int len_uniform, int max_len,
                         void* o, int64_t o_stride, int B, int H, int dh) {
   const float scale = 1.0f / sqrtf((float)dh);
-  const size_t lds = (size_t)(dh + max_len) * sizeof(float);
   const dim3 grid(H, B);
+  const int n = dt == BF16 ? 8 : 4;                       // elements per 16 bytes
+  const int lpk = dh % n == 0 ? dh / n : 0;
+  const auto al = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  const bool vec = lpk >= 1 && lpk <= 64 && (lpk & (lpk - 1)) == 0 && al(q) && al(k) && al(v) && q_stride % n == 0 &&
+                   ldkv % n == 0;
+  if (vec) {
+    const size_t lds = (size_t)(8 + 4 * dh + max_len) * sizeof(float);
+#define MM_AD(T, L)                                                                                              \
+  case L:                                                                                                        \
+    attn_decode_vec_kernel<T, L><<<grid, 256, lds, st>>>((const T*)q, q_stride, (const T*)k, (const T*)v, ldkv, cu, \
+                                                        seq_rows, len_uniform, (T*)o, o_stride, scale);          \
+    return;
+    if (dt == BF16) {
+      switch (lpk) { MM_AD(bf16_t, 1) MM_AD(bf16_t, 2) MM_AD(bf16_t, 4) MM_AD(bf16_t, 8) MM_AD(bf16_t, 16) MM_AD(bf16_t, 32) MM_AD(bf16_t, 64) }
+    } else {
+      switch (lpk) { MM_AD(float, 1) MM_AD(float, 2) MM_AD(float, 4) MM_AD(float, 8) MM_AD(float, 16) MM_AD(float, 32) MM_AD(float, 64) }
+    }
+#undef MM_AD
+  }
+  const size_t lds = (size_t)(dh + max_len) * sizeof(float);
   if (dt == BF16)
     attn_decode_kernel<bf16_t><<<grid, 64, lds, st>>>((const bf16_t*)q, q_stride, (const bf16_t*)k, (const bf16_t*)v,
                                                       ldkv, cu, seq_rows, len_uniform, (bf16_t*)o, o_stride, dh, scale);

@@ -117,13 +117,13 @@ __global__ void mask_dump_kernel(const int32_t* __restrict__ cu_q, const int32_t
 template <typename T>
 __global__ void embed_fwd_kernel(const T* __restrict__ E, const float* __restrict__ pe,
                                  const int32_t* __restrict__ tok, const int32_t* __restrict__ pos,
-                                 float* __restrict__ x, int rows, int d, float sqrt_d) {
+                                 float* __restrict__ x, int rows, int d, float sqrt_d, int pos_all) {
   const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one float4 each
   const int per_row = d >> 2;
   if (q >= (int64_t)rows * per_row) return;
   const int row = (int)(q / per_row), c = (int)(q % per_row) << 2;
   const float4 e = Io<T>::ld4(E + (int64_t)tok[row] * d + c);
-  const float4 p = Io<float>::ld4(pe + (int64_t)pos[row] * d + c);
+  const float4 p = Io<float>::ld4(pe + (int64_t)(pos ? pos[row] : pos_all) * d + c);
   float4 o;  // product rounded, then sum rounded (no fused multiply-add)
   o.x = __fadd_rn(__fmul_rn(sqrt_d, e.x), p.x);
   o.y = __fadd_rn(__fmul_rn(sqrt_d, e.y), p.y);
@@ -294,7 +294,8 @@ __global__ void __launch_bounds__(256) layernorm_fwd_kernel(const float* __restr
                                                             const float* __restrict__ beta,
                                                             T* __restrict__ y, float* __restrict__ mean,
                                                             float* __restrict__ rstd, int rows, int d,
-                                                            float eps) {
+                                                            float eps, int x_parts, int64_t x_part_stride,
+                                                            float* __restrict__ x_sum) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (row >= rows) return;
@@ -304,6 +305,37 @@ __global__ void __launch_bounds__(256) layernorm_fwd_kernel(const float* __restr
   for (int k = 0; k < NV; ++k) {
     const int c = (lane << 2) + k * 256;
     v[k] = c < d ? Io<float>::ld4(x + (int64_t)row * d + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  if (x_parts > 1) {   // x arrives as partial sums: add them in order, keep the sum
+    for (int p0 = 1; p0 < x_parts; p0 += 4) {          // up to 4 * NV loads in flight
+      float4 u[4][NV];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int pt = p0 + i < x_parts ? p0 + i : p0;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+          const int c = (lane << 2) + k * 256;
+          u[i][k] = c < d ? Io<float>::ld4(x + pt * x_part_stride + (int64_t)row * d + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (p0 + i < x_parts) {
+#pragma unroll
+          for (int k = 0; k < NV; ++k) { v[k].x += u[i][k].x; v[k].y += u[i][k].y; v[k].z += u[i][k].z; v[k].w += u[i][k].w; }
+        }
+      }
+    }
+    if (x_sum) {
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        const int c = (lane << 2) + k * 256;
+        if (c < d) Io<float>::st4(x_sum + (int64_t)row * d + c, v[k]);
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
     s += (v[k].x + v[k].y) + (v[k].z + v[k].w);
   }
   const float mu = wave_sum(s) / (float)d;
@@ -766,13 +798,13 @@ void launch_mask_dump(hipStream_t st, const int32_t* cu_q, const int32_t* cu_k, 
 }
 
 void launch_embed_fwd(hipStream_t st, Dtype dt, const void* E, const float* pe, const int32_t* tok,
-                      const int32_t* pos, float* x, int rows, int d, float sqrt_d) {
+                      const int32_t* pos, float* x, int rows, int d, float sqrt_d, int pos_all) {
   const int64_t n4 = (int64_t)rows * (d / 4);
   const int grid = (int)((n4 + 255) / 256);
   if (dt == BF16)
-    embed_fwd_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)E, pe, tok, pos, x, rows, d, sqrt_d);
+    embed_fwd_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)E, pe, tok, pos, x, rows, d, sqrt_d, pos_all);
   else
-    embed_fwd_kernel<float><<<grid, 256, 0, st>>>((const float*)E, pe, tok, pos, x, rows, d, sqrt_d);
+    embed_fwd_kernel<float><<<grid, 256, 0, st>>>((const float*)E, pe, tok, pos, x, rows, d, sqrt_d, pos_all);
 }
 
 void launch_sort_tokens(hipStream_t st, const int32_t* tok, int rows, uint32_t* keys) {
@@ -804,12 +836,15 @@ void launch_embed_grad(hipStream_t st, const uint32_t* keys, const float* dx, fl
   }
 
 void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float* gamma, const float* beta,
-                          void* y, float* mean, float* rstd, int rows, int d, float eps, const LaunchEvents& ev) {
+                          void* y, float* mean, float* rstd, int rows, int d, float eps, const LaunchEvents& ev,
+                          int x_parts, int64_t x_part_stride, float* x_sum) {
   const int grid = (rows + 3) / 4;
   if (dt == BF16) {
-    MM_LN_DISPATCH(layernorm_fwd_kernel, bf16_t, x, gamma, beta, (bf16_t*)y, mean, rstd, rows, d, eps)
+    MM_LN_DISPATCH(layernorm_fwd_kernel, bf16_t, x, gamma, beta, (bf16_t*)y, mean, rstd, rows, d, eps, x_parts,
+                   x_part_stride, x_sum)
   } else {
-    MM_LN_DISPATCH(layernorm_fwd_kernel, float, x, gamma, beta, (float*)y, mean, rstd, rows, d, eps)
+    MM_LN_DISPATCH(layernorm_fwd_kernel, float, x, gamma, beta, (float*)y, mean, rstd, rows, d, eps, x_parts,
+                   x_part_stride, x_sum)
   }
 }
 

@@ -109,9 +109,10 @@ void launch_pack_ids(hipStream_t st, const int32_t* src_ids, const int32_t* tgt_
 void launch_mask_dump(hipStream_t st, const int32_t* cu_q, const int32_t* cu_k, int B, int Lq,
                       int Lk, int mode, uint8_t* out);
 
-// x[row,:] = sqrt_d * E[tok[row],:] + pe[pos[row],:]   (multiply, then add; fp32 out)
+// x[row,:] = sqrt_d * E[tok[row],:] + pe[pos[row],:]   (multiply, then add; fp32 out).
+// pos null: every row sits at position pos_all.
 void launch_embed_fwd(hipStream_t st, Dtype dt, const void* E, const float* pe, const int32_t* tok,
-                      const int32_t* pos, float* x, int rows, int d, float sqrt_d);
+                      const int32_t* pos, float* x, int rows, int d, float sqrt_d, int pos_all = 0);
 // keys[i] = (token << 14 | row), sorted ascending; keys holds the next power of two >= rows entries
 // (at least 64).  Depends on the token ids only, so it can run ahead of the step on another stream.
 void launch_sort_tokens(hipStream_t st, const int32_t* tok, int rows, uint32_t* keys);
@@ -123,9 +124,12 @@ void launch_embed_grad(hipStream_t st, const uint32_t* keys, const float* dx, fl
 // ---------------------------------------------------------------------------------------------
 // LayerNorm over the last axis, one row per wavefront
 // ---------------------------------------------------------------------------------------------
+// x may arrive as x_parts partial sums (x + s * x_part_stride, s < x_parts); they are added here
+// and, with x_sum given, the sum is also written there.
 void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float* gamma,
                           const float* beta, void* y, float* mean, float* rstd, int rows, int d,
-                          float eps, const LaunchEvents& ev = LaunchEvents());
+                          float eps, const LaunchEvents& ev = LaunchEvents(), int x_parts = 1,
+                          int64_t x_part_stride = 0, float* x_sum = nullptr);
 // dx_out = dres + LN'(dy);  dxT_out (working dtype, may be null) = same, rounded.
 // The column sums for the gain and shift gradients leave as ln_bwd_partial_rows(rows) partial
 // rows, partial[p][0][d] (gain) and partial[p][1][d] (shift); launch_ln_reduce_grouped adds them

@@ -822,12 +822,11 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
   PV pv_gen{c, &m_gen, 0};
 
   // ---------------- decoding state ----------------
-  int32_t* state = (int32_t*)c->ws.take(((size_t)4 * B + 1 + (size_t)B * max_new) * 4);
+  int32_t* state = (int32_t*)c->ws.take(((size_t)3 * B + 1 + (size_t)B * max_new) * 4);
   int32_t* cur_tok = state;            // next decoder input (BOS first)
-  int32_t* cur_pos = state + B;        // its position, the same for every sentence
-  int32_t* done = state + 2 * B;
-  out.len = state + 3 * B;
-  int32_t* n_done = state + 4 * B;
+  int32_t* done = state + B;
+  out.len = state + 2 * B;
+  int32_t* n_done = state + 3 * B;
   out.ids = n_done + 1;
   if (!dry) {
     launch_fill_i32(c->st, cur_tok, B, 1 /* BOS */);
@@ -836,21 +835,59 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
   int32_t* n_done_host = (int32_t*)c->result_host + 8;
   const int64_t row3 = (int64_t)3 * d;                 // one cached row: q | k | v
   const int64_t seq3 = row3 * max_new;                 // one sentence's cache
+  // One row per sentence leaves few tiles per product, so the products that write the residual
+  // stream (d outputs from d or d_ff inputs) split their K range over several workgroups per
+  // tile; the LayerNorm that reads the stream next adds the partial sums (and keeps the sum).
+  struct Res { float* x; int parts; };
+  const int64_t part_stride = (int64_t)B * d;
+  constexpr int MAX_PARTS = 8;
+  auto ln_in = [&](Res r, const float* g, const float* bta, float*& x_full) -> void* {
+    void* a = s.act((size_t)B * d);
+    x_full = r.parts > 1 ? s.f32((size_t)B * d) : r.x;
+    float* mean = s.f32(B);
+    float* rstd = s.f32(B);
+    if (!dry)
+      launch_layernorm_fwd(c->st, c->dt, r.x, g, bta, a, mean, rstd, B, d, c->cfg.ln_eps,
+                           run.begin_timed(MM_K_LAYERNORM_FWD, (double)B * d * (4 * r.parts + esz)), r.parts,
+                           part_stride, r.parts > 1 ? x_full : nullptr);
+    return a;
+  };
+  // resid + A[B,K] W[K,d] + bias
+  auto proj_out = [&](const void* A, int K, const void* W, const float* bias, const float* resid) -> Res {
+    Res r{s.f32((size_t)B * d * MAX_PARTS), 1};
+    GemmParams p = s.gp(A, K, W, d, r.x, d, B, d, K);
+    p.bias = bias; p.residual = resid; p.ldr = d; p.out_f32 = 1;
+    const int want = K >= 2048 ? 8 : K >= 512 ? 4 : 1;
+    if (want > 1) {
+      p.k_splits = want;
+      p.k_chunk = (((K + want - 1) / want) + 63) / 64 * 64;
+      p.c_part_stride = part_stride;
+      if (gemm_can_split_k(c->dt, p)) r.parts = want; else p.k_splits = 0;
+    }
+    run.gemm(p);
+    return r;
+  };
+  auto ffn_block = [&](const PV& pv, int t0, Res in, int hidden) -> Res {
+    float* x_full;
+    void* a = ln_in(in, pv.V(t0), pv.V(t0 + 1), x_full);
+    void* hbuf = s.act((size_t)B * hidden);
+    GemmParams p = s.gp(a, d, pv.W(t0 + 2), hidden, hbuf, hidden, B, hidden, d);
+    p.bias = pv.V(t0 + 3); p.relu = 1;
+    run.gemm(p);
+    return proj_out(hbuf, hidden, pv.W(t0 + 4), pv.V(t0 + 5), x_full);
+  };
   const size_t step_mark = c->ws.off;
   for (int t = 0; t < max_new; ++t) {
     c->ws.off = step_mark;                             // every step reuses the same buffers
-    float* y = s.f32((size_t)B * d);
-    if (!dry) {
-      launch_fill_i32(c->st, cur_pos, B, t);
-      launch_embed_fwd(c->st, c->dt, emb_w(m_tgt), c->pe, cur_tok, cur_pos, y, B, d, sqrt_d);
-    }
+    Res y{s.f32((size_t)B * d), 1};
+    if (!dry) launch_embed_fwd(c->st, c->dt, emb_w(m_tgt), c->pe, cur_tok, nullptr, y.x, B, d, sqrt_d, t);
     for (DecLayer& L : layers) {
       const PV& pv = L.pv;
       // self-attention over the tokens so far (row t of the cache is written by the projection)
-      void* a = s.act((size_t)B * d);
-      run.ln_fwd(y, pv.V(0), pv.V(1), a, s.f32(B), s.f32(B), B);
+      float* x_full;
+      void* a = ln_in(y, pv.V(0), pv.V(1), x_full);
       char* row_t = L.cache + (size_t)t * row3 * esz;
-      int64_t seg = pv.off(4) - pv.off(2);
+      const int64_t seg = pv.off(4) - pv.off(2);
       GemmParams p = s.gp(a, d, pv.W(2), d, row_t, seq3, B, 3 * d, d);
       p.b_split = d; p.b_seg_stride = seg; p.bias = pv.V(3); p.bias_split = d; p.bias_seg_stride = seg;
       run.gemm(p);
@@ -858,13 +895,9 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
       if (!dry)
         launch_attn_decode(c->st, c->dt, row_t, seq3, L.cache + (size_t)d * esz, L.cache + (size_t)2 * d * esz, row3,
                            nullptr, max_new, t + 1, max_new, o, d, B, H, dh);
-      float* y1 = s.f32((size_t)B * d);
-      p = s.gp(o, d, pv.W(8), d, y1, d, B, d, d);
-      p.bias = pv.V(9); p.residual = y; p.ldr = d; p.out_f32 = 1;
-      run.gemm(p);
+      y = proj_out(o, d, pv.W(8), pv.V(9), x_full);
       // attention over the encoder output
-      a = s.act((size_t)B * d);
-      run.ln_fwd(y1, pv.V(10), pv.V(11), a, s.f32(B), s.f32(B), B);
+      a = ln_in(y, pv.V(10), pv.V(11), x_full);
       void* q = s.act((size_t)B * d);
       p = s.gp(a, d, pv.W(12), d, q, d, B, d, d);
       p.bias = pv.V(13);
@@ -873,15 +906,12 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
       if (!dry)
         launch_attn_decode(c->st, c->dt, q, d, L.kv_mem, L.kv_mem + (size_t)d * esz, 2 * d, c->cu_s, 0, 0, s.max_s, o,
                            d, B, H, dh);
-      float* y2 = s.f32((size_t)B * d);
-      p = s.gp(o, d, pv.W(18), d, y2, d, B, d, d);
-      p.bias = pv.V(19); p.residual = y1; p.ldr = d; p.out_f32 = 1;
-      run.gemm(p);
-      y = s.ffn_fwd(pv, 20, y2, B, s.F).x_out;
-      if (L.has_adapter) y = s.ffn_fwd(L.apv, 0, y, B, c->mods[rt.ad_dec].adapter_dim).x_out;
+      y = proj_out(o, d, pv.W(18), pv.V(19), x_full);
+      y = ffn_block(pv, 20, y, s.F);
+      if (L.has_adapter) y = ffn_block(L.apv, 0, y, c->mods[rt.ad_dec].adapter_dim);
     }
-    void* h = s.act((size_t)B * d);
-    run.ln_fwd(y, pv_decf.V(0), pv_decf.V(1), h, s.f32(B), s.f32(B), B);
+    float* x_full;
+    void* h = ln_in(y, pv_decf.V(0), pv_decf.V(1), x_full);
     void* z = s.act((size_t)B * V);
     GemmParams p = s.gp(h, d, pv_gen.W(0), V, z, V, B, V, d);
     p.bias = pv_gen.V(1);
