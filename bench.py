@@ -85,6 +85,18 @@ def bench_translate(args, setup, ctx, batch):
     ctx.mm_profile(False)
     classes = {name: {"ms_per_call": r["ms"], "launches_per_call": r["launches"]}
                for name, r in prof.items() if r["launches"]}
+    # HBM bytes a decoding step has to read: the decoder stack's and the generator's working weights
+    # once, plus every layer's keys/values of the encoder output
+    route = ctx.mm_get_route(tasks[0])
+    esz = 2 if sh.dtype == "bf16" else 4
+    n_dec = sum(setup.modules[j].n_layers for j in route if setup.modules[j].kind == "dec")
+    w_params = sum(ctx.mm_get_layout(j)[1] for j in route if setup.modules[j].kind in ("dec", "gen"))
+    w_params -= 2 * sh.d_model * sh.d_model * n_dec      # the encoder-side key/value projections ran once
+    step_bytes = w_params * esz + int(s_len.sum()) * 2 * sh.d_model * esz * n_dec
+    step_s = elapsed / args.steps / max_new
+    roofline = {"bound": "hbm", "kernel": "one decoding step (71 launches at set-up 2; no single kernel dominates)",
+                "achieved": step_bytes / step_s / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                "frac": step_bytes / step_s / PEAK_HBM, "traffic": None, "bytes_per_step": step_bytes}
     print(json.dumps({
         "metric": "greedy translation tokens/s per MI355X (routed inference)", "value": B * max_new * args.steps / elapsed,
         "unit": "generated tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -92,7 +104,7 @@ def bench_translate(args, setup, ctx, batch):
         "higher_is_better": True, "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}]: {setup.title}; {B} sentences, {int(s_len.sum())} source "
                                f"tokens, {max_new} tokens written per sentence"},
-        "kernel_classes": classes}))
+        "roofline": roofline, "kernel_classes": classes}))
 
 
 def main():

@@ -17,8 +17,8 @@ pytestmark = pytest.mark.gpu
 # A logit row's error as a fraction of the row's spread (max - min).  fp32: rounding of a few
 # hundred length-d sums, ~1e-6 relative, with margin.  bf16: every activation is rounded to 8
 # significant bits (2^-9 relative) through up to a dozen residual blocks, and the logits
-# themselves are stored in bf16; the training-step parity bound of a few percent applies.
-TOL = {"f32": 2e-4, "bf16": 5e-2}
+# themselves are stored in bf16: about 1e-2 of the spread; the worst seen is 2.6e-3 (full size).
+TOL = {"f32": 2e-4, "bf16": 1e-2}
 LENGTHS = ((5, 4), (3, 7), (8, 2), (1, 5), (6, 3), (2, 3), (7, 3), (4, 3), (24, 2), (13, 2))
 
 
@@ -210,5 +210,10 @@ def test_config2_translation_at_full_size():
     ids, n = ctx.mm_translate_greedy(0, src, s_len, 10)
     check_structure(ids, n, 10)
     worst = check_valid(orc, 0, src, s_len, ids, n, TOL["bf16"], "config2")
-    say(f"  counts {n.tolist()}, {len({tuple(r) for r in ids.tolist()})} distinct outputs, worst gap {worst:.2e}")
+    ref_ids, ref_n = orc.greedy_decode(0, src, s_len, 10)
+    same = (ids == ref_ids).all(axis=1)
+    say(f"  counts {n.tolist()}, {len({tuple(r) for r in ids.tolist()})} distinct outputs, worst gap {worst:.2e}, "
+        f"{int(same.sum())}/{B} sentences identical to the oracle's")
+    assert len({tuple(r) for r in ref_ids.tolist()}) >= 6      # the source decides the output
+    assert same.mean() >= 0.75       # the others left it at a near-tie (checked above)
     ctx.close()
