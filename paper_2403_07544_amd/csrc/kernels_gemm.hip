@@ -106,16 +106,16 @@ __global__ void __launch_bounds__(256) gemm_simt_kernel(const GemmParams p) {
 
 // =================================================================================================
 // bf16 MFMA kernel (v_mfma_f32_32x32x16_bf16), 256 threads = 4 wavefronts, K step 64, LDS double
-// buffered.  Both operand tiles sit in LDS as [row][64 k] = 8 chunks of 16 bytes per row, where
-// row = m (A) or n (B); chunk c of row r lives in slot c ^ swz(r) so that
+// buffered.  An operand that is k-contiguous in memory sits in LDS as [row][64 k] = 8 chunks of 16
+// bytes per row, row = m (A) or n (B); chunk c of row r lives in slot c ^ swz(r) so that
 //   * a wavefront's fragment reads (32 consecutive rows, one chunk each, 16 bytes per lane) and
-//   * the k-contiguous loader's writes (8 lanes cover one row)
-// touch every bank group once, and the transposing loader's 8-byte writes (16 lanes write rows
-// 8 apart) collide at most pairwise.
-// Operands that are k-contiguous in memory are copied 16 bytes at a time.  Operands whose
-// contiguous axis is m or n (forward weights [K,N]; both operands of a weight gradient, whose
-// reduction runs over tokens) are transposed on the way: a thread loads a 4(k) x 8(col) patch
-// with four 16-byte loads, regroups it in registers and writes eight 8-byte k-quads.
+//   * the loader's writes (8 lanes cover one row)
+// touch every bank group once.  An operand whose contiguous axis is m or n (forward weights
+// [K,N]; both operands of a weight gradient, whose reduction runs over tokens) is kept as it lies
+// in memory, [64 k][rows], copied 16 bytes at a time like the other kind, and the MFMA fragments
+// (8 consecutive k of one row per lane) are formed by the transposing LDS read ds_read_b64_tr_b16
+// (two per fragment); chunk c of k row r lives in slot c ^ tr_swz(r).  Nothing is regrouped in
+// registers and no transposed copy of a weight or an activation exists in HBM.
 // =================================================================================================
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
@@ -149,6 +149,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 7); }
+// Chunk swizzle of a tile kept as it lies in memory, [64 k][R] (see gemm_mfma_tile): the four k rows
+// that one transposing LDS read touches land in different banks.
+template <int R>
+__device__ __forceinline__ int tr_swz(int krow) { return R >= 128 ? (krow & 3) << 2 : ((krow >> 1) & 1) << 2; }
 
 // Loads one operand tile (R rows x 64 k) from global memory into registers, then into LDS.
 // KC: operand is k-contiguous in memory (element (row,k) at base + row*ld + k), else
@@ -161,7 +165,7 @@ struct TileLoader {
   static constexpr int NV = KC ? NL : NL * 4;                          // 16-byte registers per K step
   const bf16_t* ptr[NL];      // item address at k = 0
   int klim[NL];               // KC: item valid while k0 < klim; else: k row j valid while k0 + j < klim
-  int off[KC ? NL : NL * 8];  // LDS byte offsets inside the tile
+  int off[KC ? NL : NL * 4];  // LDS byte offsets inside the tile (row-contiguous operand: one per k row)
   int64_t ld;
   int ksplit; int64_t seg_stride;  // KC only: segments along k (multiple of 64)
   const bf16_t* safe;              // any valid address: out-of-range items read it and are zeroed
@@ -200,9 +204,9 @@ struct TileLoader {
         voff[i] = kq < 16 ? (uint32_t)((ptr[i] - base) * 2) : 0u;
         klim[i] = (gc < row_lim && kq < 16) ? K - kq * 4 : 0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int row = cg * 8 + e;
-          off[i * 8 + e] = kq < 16 ? row * 128 + (((kq >> 1) ^ swz(row)) << 4) + ((kq & 1) << 3) : -1;
+        for (int j = 0; j < 4; ++j) {
+          const int krow = kq * 4 + j;
+          off[i * 4 + j] = kq < 16 ? krow * (R * 2) + ((cg ^ tr_swz<R>(krow)) << 4) : -1;
         }
       }
     }
@@ -254,19 +258,9 @@ struct TileLoader {
     } else {
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
-        if (off[i * 8] < 0) continue;
+        if (off[i * 4] < 0) continue;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          uint2 o;
-          if (e & 1) {
-            o.x = (v[i * 4 + 0][e >> 1] >> 16) | (v[i * 4 + 1][e >> 1] & 0xffff0000u);
-            o.y = (v[i * 4 + 2][e >> 1] >> 16) | (v[i * 4 + 3][e >> 1] & 0xffff0000u);
-          } else {
-            o.x = (v[i * 4 + 0][e >> 1] & 0xffffu) | (v[i * 4 + 1][e >> 1] << 16);
-            o.y = (v[i * 4 + 2][e >> 1] & 0xffffu) | (v[i * 4 + 3][e >> 1] << 16);
-          }
-          *reinterpret_cast<uint2*>(lds + off[i * 8 + e]) = o;
-        }
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4_t*>(lds + off[i * 4 + j]) = v[i * 4 + j];
       }
     }
   }
@@ -293,11 +287,14 @@ struct TileLoader {
         else v[i] = load16_global(k_ld < klim[i] ? ptr[i] + koff : safe);
       }
     } else {
-      // all of it in the first quarter: every store needs all four k rows of its item, and the
-      // reloads, which can only follow the stores, then have the rest of the K step to land
-      if (Q == 0) {
-        if (F) { store_fast(lds, v); load_fast(k_ld, v); }
-        else { store(lds, k_st, v); load(k_ld, v); }
+      // quarter Q moves k row Q of every item
+      const char* b = ubase + ((int64_t)(k_ld + Q) * ld) * 2;
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        if (off[i * 4] >= 0)
+          *reinterpret_cast<u32x4_t*>(lds + off[i * 4 + Q]) = (F || k_st + Q < klim[i]) ? v[i * 4 + Q] : zero;
+        if (F) v[i * 4 + Q] = *(global_u4_ptr)(b + voff[i]);
+        else v[i * 4 + Q] = load16_global(k_ld + Q < klim[i] ? ptr[i] + (int64_t)(k_ld + Q) * ld : safe);
       }
     }
   }
@@ -311,21 +308,10 @@ struct TileLoader {
     } else {
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
-        if (off[i * 8] < 0) continue;
-        const u32x4_t w0 = k0 + 0 < klim[i] ? v[i * 4 + 0] : zero, w1 = k0 + 1 < klim[i] ? v[i * 4 + 1] : zero;
-        const u32x4_t w2 = k0 + 2 < klim[i] ? v[i * 4 + 2] : zero, w3 = k0 + 3 < klim[i] ? v[i * 4 + 3] : zero;
+        if (off[i * 4] < 0) continue;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          uint2 o;
-          if (e & 1) {
-            o.x = (w0[e >> 1] >> 16) | (w1[e >> 1] & 0xffff0000u);
-            o.y = (w2[e >> 1] >> 16) | (w3[e >> 1] & 0xffff0000u);
-          } else {
-            o.x = (w0[e >> 1] & 0xffffu) | (w1[e >> 1] << 16);
-            o.y = (w2[e >> 1] & 0xffffu) | (w3[e >> 1] << 16);
-          }
-          *reinterpret_cast<uint2*>(lds + off[i * 8 + e]) = o;
-        }
+        for (int j = 0; j < 4; ++j)
+          *reinterpret_cast<u32x4_t*>(lds + off[i * 4 + j]) = k0 + j < klim[i] ? v[i * 4 + j] : zero;
       }
     }
   }
@@ -333,7 +319,7 @@ struct TileLoader {
 
 // CS: also produce the column sums of B over the whole K range (the bias gradient that goes with a
 // weight gradient: dW = X^T dY, db = column sums of dY).  Only the tiles of the first tile row do
-// it, from the registers the transposing loader has just filled (4 k x 8 columns per thread).
+// it, from the registers the loader has just filled (4 k rows x 8 columns per thread).
 // PF: K steps whose global loads are in flight ahead of the one being multiplied (register staged).
 // DMA (both operands k-contiguous, K a multiple of 128): the tiles go from global memory straight
 // into LDS (global_load_lds_dwordx4: lane l of a wavefront deposits its 16 bytes at base + 16 l, so
@@ -350,15 +336,16 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   const int wm = wave / (BN / WN), wn = wave % (BN / WN);
 
   static_assert(!DMA || (KCA && !CS), "direct-to-LDS loads need a k-contiguous A");
-  // DMA with a B whose contiguous axis is n (forward weights [K, N]): the B tile is kept in LDS as it
-  // lies in memory, [64 k][BN] with 16-byte chunk c of k row r in slot c ^ bt_swz(r), and the MFMA
-  // fragments (8 consecutive k of one column per lane) are formed by the transposing LDS read
-  // ds_read_b64_tr_b16: within 16 lanes, lane j supplies the address of 4 columns of row j / 4 and
-  // lane i receives rows 0..3 of column i.  The slot swizzle spreads the four rows of one read over
-  // different banks.
+  // An operand whose contiguous axis is m or n is kept in LDS as it lies in memory, [64 k][rows]
+  // with 16-byte chunk c of k row r in slot c ^ tr_swz(r), and its MFMA fragments (8 consecutive k
+  // of one row per lane) are formed by the transposing LDS read ds_read_b64_tr_b16: within 16
+  // lanes, lane j supplies the address of 4 columns of k row j / 4 and lane i receives k rows 0..3
+  // of column i.  The slot swizzle spreads the four k rows of one read over different banks.
+  // (Register-staged and direct-to-LDS loads fill the same layout.)
   constexpr bool BTR = DMA && !KCB;
-  constexpr int BT_ROW = BN * 2;                        // bytes per k row of the B tile
-  auto bt_swz = [](int krow) { return BN >= 128 ? (krow & 3) << 2 : ((krow >> 1) & 1) << 2; };
+  constexpr bool TRA = !KCA, TRB = !KCB;                // operands kept [64 k][rows] in LDS (register path too)
+  constexpr int AT_ROW = BM * 2, BT_ROW = BN * 2;       // bytes per k row of such a tile
+  auto bt_swz = [](int krow) { return tr_swz<BN>(krow); };
   TileLoader<BM, KCA> la;
   TileLoader<BN, KCB> lb;
   if constexpr (!DMA) {
@@ -458,19 +445,31 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   const int nk = (p.K + BK - 1) / BK;
   const int lrow = lane & 31, lhalf = lane >> 5;
   int a_off[MT][BK / 16], b_off[NT][BK / 16];
-  int bt_off[BTR ? NT : 1][BK / 16][2];   // BTR: the two transposing reads (k 0..3, k 4..7) of a fragment
-  if constexpr (BTR) {
+  // [64 k][rows] tiles: the two transposing reads (k 0..3, k 4..7) of a fragment
+  int bt_off[TRB ? NT : 1][BK / 16][2];
+  int at_off[TRA ? MT : 1][BK / 16][2];
+  if constexpr (TRA || TRB) {
     const int jj = lane & 15, g2 = (lane >> 4) & 1;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk)
 #pragma unroll
-      for (int j = 0; j < NT; ++j)
+      for (int r = 0; r < 2; ++r) {
+        const int krow = kk * 16 + lhalf * 8 + r * 4 + (jj >> 2);
+        if constexpr (TRB) {
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-          const int krow = kk * 16 + lhalf * 8 + r * 4 + (jj >> 2);
-          const int col = wn * WN + j * 32 + 16 * g2 + 4 * (jj & 3);
-          bt_off[j][kk][r] = A_BYTES + krow * BT_ROW + ((((col >> 3) ^ bt_swz(krow))) << 4) + (((col >> 2) & 1) << 3);
+          for (int j = 0; j < NT; ++j) {
+            const int col = wn * WN + j * 32 + 16 * g2 + 4 * (jj & 3);
+            bt_off[j][kk][r] = A_BYTES + krow * BT_ROW + ((((col >> 3) ^ tr_swz<BN>(krow))) << 4) + (((col >> 2) & 1) << 3);
+          }
         }
+        if constexpr (TRA) {
+#pragma unroll
+          for (int i = 0; i < MT; ++i) {
+            const int col = wm * WM + i * 32 + 16 * g2 + 4 * (jj & 3);
+            at_off[i][kk][r] = krow * AT_ROW + ((((col >> 3) ^ tr_swz<BM>(krow))) << 4) + (((col >> 2) & 1) << 3);
+          }
+        }
+      }
   }
 #pragma unroll
   for (int kk = 0; kk < BK / 16; ++kk) {
@@ -497,13 +496,22 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     bf16x8_t af[NBUF][MT], bfr[NBUF][NT];
     auto read_frags = [&](auto buf_tag, int kk) {
       constexpr int BUF = decltype(buf_tag)::value % NBUF;
+      typedef short s16x4_t __attribute__((ext_vector_type(4)));
+      typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
 #pragma unroll
-      for (int i = 0; i < MT; ++i) af[BUF][i] = *reinterpret_cast<const bf16x8_t*>(lds + a_off[i][kk] + SOFF);
+      for (int i = 0; i < MT; ++i) {
+        if constexpr (TRA) {
+          union { s16x4_t h[2]; bf16x8_t f; } u;
+          u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + at_off[i][kk][0] + SOFF));
+          u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + at_off[i][kk][1] + SOFF));
+          af[BUF][i] = u.f;
+        } else {
+          af[BUF][i] = *reinterpret_cast<const bf16x8_t*>(lds + a_off[i][kk] + SOFF);
+        }
+      }
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
-        if constexpr (BTR) {
-          typedef short s16x4_t __attribute__((ext_vector_type(4)));
-          typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+        if constexpr (TRB) {
           union { s16x4_t h[2]; bf16x8_t f; } u;
           u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + bt_off[j][kk][0] + SOFF));
           u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + bt_off[j][kk][1] + SOFF));
@@ -858,6 +866,9 @@ bool gemm_groupable(Dtype dt, const GemmParams& p) {
   return dt == BF16 && p.transA == 1 && p.transB == 0 && mfma_eligible(p);
 }
 
+#ifndef MM_GROUPED_PF
+#define MM_GROUPED_PF 2
+#endif
 int gemm_grouped_tiles(const GemmParams& p) { return ((p.M + 127) / 128) * ((p.N + 127) / 128); }
 
 void gemm_prepare_grouped(GemmParams& p) { set_wide(p); }
@@ -870,11 +881,11 @@ void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const i
   constexpr int LDS = 2 * (128 + 128) * 128;
   static bool attr_set = false;
   if (!attr_set) {
-    hipFuncSetAttribute((const void*)gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false, 2>,
+    hipFuncSetAttribute((const void*)gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false, MM_GROUPED_PF>,
                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     attr_set = true;
   }
-  hipExtLaunchKernelGGL((gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false, 2>), dim3(total_tiles), dim3(256), LDS,
+  hipExtLaunchKernelGGL((gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false, MM_GROUPED_PF>), dim3(total_tiles), dim3(256), LDS,
                         st, ev.start, ev.stop, 0, table_dev, tile_start_dev, n_problems);
 }
 
