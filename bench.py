@@ -114,6 +114,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--accumulate", type=int, default=1, help="routed passes per update")
+    ap.add_argument("--task-temperature", type=float, default=None,
+                    help="draw each pass's task with probability proportional to (corpus size)^(1/T), "
+                         "corpus sizes falling off as 1/rank, instead of uniformly")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--translate", type=int, default=0, metavar="MAX_NEW",
                     help="time routed greedy translation instead of training: every sentence of one batch "
@@ -140,7 +143,7 @@ def main():
     A = max(1, args.accumulate)
     n_steps = (args.warmup + args.steps) * A      # routed passes; A of them per update
     batches = mm_synth.make_batches(setup)
-    directions = mm_synth.sample_directions(setup, n_steps)
+    directions = mm_synth.sample_directions(setup, n_steps, temperature=args.task_temperature)
     ctx = context_from_setup(setup, fill_params=mm_synth.fill_params)
 
     if args.translate:
@@ -226,7 +229,8 @@ def main():
         "config": {"workload": f"configs[{args.config - 1}]: {setup.title}; d={sh.d_model} heads={sh.n_heads} "
                                f"ffn={sh.d_ff} vocab={sh.vocab}, {len(setup.modules)} modules resident, "
                                f"{len(setup.tasks)} task(s), ~{sh.batch_tokens}-token length-bucketed batches"
-                               + (f", {A} routed passes per update" if A > 1 else ""),
+                               + (f", {A} routed passes per update" if A > 1 else "")
+                               + (f", tasks drawn with temperature {args.task_temperature}" if args.task_temperature else ""),
                    "target_tokens_per_step": tokens / args.steps, "source_tokens_per_step": src_tokens / args.steps,
                    "src_plus_tgt_tokens_per_s": (tokens + src_tokens) / elapsed, "last_loss": last_loss},
         "roofline": roofline,

@@ -14,6 +14,7 @@ from .data import (  # noqa: F401
     make_batches,
     make_pool,
     sample_directions,
+    task_probabilities,
     zipf_cdf,
 )
 from .init import fill_params  # noqa: F401

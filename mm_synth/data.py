@@ -123,7 +123,21 @@ def small_batch(vocab: int, lengths, seed: int) -> Batch:
     return _fill_batch(rng, zipf_cdf(vocab), np.asarray(lengths, dtype=np.int32).reshape(-1, 2))
 
 
-def sample_directions(setup: Setup, n_steps: int) -> np.ndarray:
-    """Task index per step, uniform over the set-up's tasks."""
+def task_probabilities(n_tasks: int, temperature: float, skew: float = 1.0) -> np.ndarray:
+    """Sampling weights for skewed data: task k (in the set-up's order) stands for a corpus of size
+    proportional to (k+1)^-skew, and is drawn with probability proportional to size^(1/temperature):
+    temperature 1 follows the corpus sizes, a large temperature tends to uniform."""
+    size = (np.arange(n_tasks, dtype=np.float64) + 1.0) ** (-skew)
+    w = size ** (1.0 / temperature)
+    return w / w.sum()
+
+
+def sample_directions(setup: Setup, n_steps: int, temperature: float = None, skew: float = 1.0) -> np.ndarray:
+    """Task index per step: uniform over the set-up's tasks, or, with a temperature, drawn from
+    task_probabilities (the single-GPU stand-in for temperature-based sampling over corpora of
+    unequal size)."""
     rng = _rng(setup.direction_seed + 1)
-    return rng.integers(0, len(setup.tasks), size=n_steps).astype(np.int32)
+    if temperature is None:
+        return rng.integers(0, len(setup.tasks), size=n_steps).astype(np.int32)
+    p = task_probabilities(len(setup.tasks), temperature, skew)
+    return rng.choice(len(setup.tasks), size=n_steps, p=p).astype(np.int32)

@@ -134,3 +134,19 @@ def test_create_rejects_bad_shapes():
     with pytest.raises(MMError):
         ctx.mm_register_module("gen", "g", init=np.zeros(10, dtype=np.float32))  # wrong length
     assert ctx.mm_get_layout(j)[1] == 32 * 56 + 64
+
+
+def test_temperature_task_sampling():
+    """Skewed-data sampling of the bench: probabilities follow size^(1/T) with sizes ~ 1/rank."""
+    p1 = mm_synth.task_probabilities(4, 1.0)
+    assert np.allclose(p1, np.array([1, 1 / 2, 1 / 3, 1 / 4]) / (25 / 12))
+    p2 = mm_synth.task_probabilities(4, 2.0)
+    assert np.allclose(p2 / p2[0], np.array([1, 2 ** -0.5, 3 ** -0.5, 0.5]))
+    assert np.allclose(mm_synth.task_probabilities(7, 1e9), 1 / 7, atol=1e-6)
+    st = mm_synth.build_setup(3)
+    d = mm_synth.sample_directions(st, 20000, temperature=1.0)
+    assert d.min() >= 0 and d.max() < len(st.tasks)
+    freq = np.bincount(d, minlength=len(st.tasks)) / len(d)
+    assert np.abs(freq - mm_synth.task_probabilities(len(st.tasks), 1.0)).max() < 0.01
+    assert np.array_equal(d, mm_synth.sample_directions(st, 20000, temperature=1.0))     # seeded
+    assert np.array_equal(mm_synth.sample_directions(st, 50), mm_synth.sample_directions(st, 50))
