@@ -242,8 +242,8 @@ __global__ void __launch_bounds__(256) attn_bwd_kernel(const AttnParams p) {
 // statistics are a register reduction plus one exchange with lane ^ 32.  The probabilities are
 // already laid out as the B operand of O^T = V^T P^T: accumulator registers 8s..8s+7 of a key
 // tile are the eight k-slots of MFMA step s.  Their key order within a block of 16 is
-// 0-3, 8-11 (lanes 0-31) and 4-7, 12-15 (lanes 32-63); the transposed V tile in LDS stores keys
-// in that same order, so no cross-lane shuffle is needed between the two products.
+// 0-3, 8-11 (lanes 0-31) and 4-7, 12-15 (lanes 32-63); the fragments of V^T are read from the V
+// tile in that same order (frag_tr), so no cross-lane shuffle is needed between the two products.
 // =================================================================================================
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
@@ -254,11 +254,9 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }
 // Tile loading.  One work item = 4 consecutive rows x one 16-byte chunk (8 columns); a workgroup
 // issues the loads of all its tiles back to back and only then starts storing, so a sentence costs
-// one global-memory round trip rather than one per loop iteration.  The same four registers feed
-// both LDS forms of a tile:
-//   natural:    [rows][64] bf16, 128-byte rows, 16-byte chunk c of row r in slot c ^ swz64(r)
-//   transposed: [64 columns][rows_pad + 8] bf16; within each block of 16 source rows the four
-//               row-quads are stored in the order 0,2,1,3 (the k-slot order described above)
+// one global-memory round trip rather than one per loop iteration.  A tile sits in LDS as
+// [rows][64] bf16, 128-byte rows, 16-byte chunk c of row r in slot c ^ swz64(r); products that
+// need its transpose read it with frag_tr, so each tile is kept once.
 __device__ __forceinline__ void tile_fetch(uint4 (&v)[4], const bf16_t* g, int64_t ld, int row0, int len, int item) {
   const int cg = item & 7, tq = item >> 3;
 #pragma unroll
@@ -276,24 +274,6 @@ __device__ __forceinline__ void tile_store_natural(unsigned char* lds, const uin
     *reinterpret_cast<uint4*>(lds + row * 128 + ((cg ^ swz64(row)) << 4)) = v[j];
   }
 }
-__device__ __forceinline__ void tile_store_transposed(unsigned char* lds, int stride, const uint4 (&v)[4], int item) {
-  const int cg = item & 7, tq = item >> 3;
-  const int qd = tq & 3;
-  const int pos = (tq >> 2) * 16 + (((qd & 1) << 1) | (qd >> 1)) * 4;
-  const uint32_t* w0 = &v[0].x; const uint32_t* w1 = &v[1].x; const uint32_t* w2 = &v[2].x; const uint32_t* w3 = &v[3].x;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    uint2 o;
-    if (e & 1) {
-      o.x = (w0[e >> 1] >> 16) | (w1[e >> 1] & 0xffff0000u);
-      o.y = (w2[e >> 1] >> 16) | (w3[e >> 1] & 0xffff0000u);
-    } else {
-      o.x = (w0[e >> 1] & 0xffffu) | (w1[e >> 1] << 16);
-      o.y = (w2[e >> 1] & 0xffffu) | (w3[e >> 1] << 16);
-    }
-    *reinterpret_cast<uint2*>(lds + (cg * 8 + e) * stride + pos * 2) = o;
-  }
-}
 // dot product of two 8-element bf16 chunks
 __device__ __forceinline__ float dot8(const uint4& a, const uint4& b) {
   const uint32_t* aw = &a.x; const uint32_t* bw = &b.x;
@@ -308,8 +288,25 @@ __device__ __forceinline__ float dot8(const uint4& a, const uint4& b) {
 __device__ __forceinline__ bf16x8_t frag_natural(const unsigned char* lds, int row, int chunk) {
   return *reinterpret_cast<const bf16x8_t*>(lds + row * 128 + ((chunk ^ swz64(row)) << 4));
 }
-__device__ __forceinline__ bf16x8_t frag_transposed(const unsigned char* lds, int stride, int col, int pos) {
-  return *reinterpret_cast<const bf16x8_t*>(lds + col * stride + pos * 2);
+// A-operand fragment of the transpose of a natural tile, formed by the transposing LDS read
+// ds_read_b64_tr_b16 (within 16 lanes, lane j supplies the address of 4 columns of row j / 4 and
+// lane i receives rows 0..3 of column i).  The lane that owns tile column ct*32 + (lane & 31)
+// gets, for e = 0..7, the element of tile row rbase + 8 (e >> 2) + 4 hh + (e & 3), hh = lane >> 5:
+// the order in which the accumulators of a 32x32 product hold their 16 rows (8 s2 .. 8 s2 + 7 of
+// them make the other operand, see frag_from_regs), so the two k orders agree.
+__device__ __forceinline__ bf16x8_t frag_tr(const unsigned char* lds, int rbase, int ct, int lane) {
+  typedef short s16x4_t __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+  const int jj = lane & 15, g2 = (lane >> 4) & 1, hh = lane >> 5;
+  const int col = ct * 32 + 16 * g2 + 4 * (jj & 3);
+  union { s16x4_t h[2]; bf16x8_t f; } u;
+#pragma unroll
+  for (int rd = 0; rd < 2; ++rd) {
+    const int row = rbase + 8 * rd + 4 * hh + (jj >> 2);
+    u.h[rd] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_s16x4_ptr)(lds + row * 128 + (((col >> 3) ^ swz64(row)) << 4) + (((col >> 2) & 1) << 3)));
+  }
+  return u.f;
 }
 __device__ __forceinline__ bf16x8_t frag_global(const bf16_t* g) {
   return *reinterpret_cast<const bf16x8_t*>(g);
@@ -330,8 +327,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams 
   const int nkt = (lk + 31) >> 5, Lp = nkt * 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lcol = lane & 31, hh = lane >> 5;
   unsigned char* Kn = smem_raw;
-  unsigned char* Vt = Kn + Lp * 128;
-  const int vstride = (Lp + 8) * 2;
+  unsigned char* Vn = Kn + Lp * 128;
   const bf16_t* qg = (const bf16_t*)p.q + h * 64;
   const float scale = 0.125f;  // 1 / sqrt(64)
   const int nqt = (lq + 31) >> 5;
@@ -351,7 +347,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams 
       tile_fetch(vk, (const bf16_t*)p.k + h * 64, p.ldk, k0, lk, it);
       tile_fetch(vv, (const bf16_t*)p.v + h * 64, p.ldv, k0, lk, it);
       tile_store_natural(Kn, vk, it);
-      tile_store_transposed(Vt, vstride, vv, it);
+      tile_store_natural(Vn, vv, it);
     }
   }
   __syncthreads();
@@ -425,8 +421,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams 
           const bf16x8_t pf = frag_from_regs(pv);
 #pragma unroll
           for (int ct = 0; ct < 2; ++ct)
-            oc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_transposed(Vt, vstride, ct * 32 + lcol, kt * 32 + s2 * 16 + hh * 8), pf, oc[ct], 0, 0, 0);
+            oc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Vn, kt * 32 + s2 * 16, ct, lane), pf, oc[ct], 0, 0, 0);
         }
       }
     }
@@ -451,15 +446,15 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams 
 
 inline size_t mfma_fwd_lds(int max_lk) {
   const int Lp = ((max_lk + 31) / 32) * 32;
-  return (size_t)Lp * 128 + (size_t)64 * (Lp + 8) * 2;
+  return (size_t)2 * Lp * 128;
 }
 
 // Backward with the same layouts, as two kinds of workgroup per (sentence, head), told apart by
 // blockIdx.y, which run side by side.  Kind 0 (dQ): a wavefront owns 32 queries and walks the key
 // tiles: S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D) * scale, dQ^T += K^T dS^T.  Kind 1
 // (dK, dV): a wavefront owns 32 keys and walks the query tiles: S = Q K^T, dP = dO V^T, then
-// dV^T += dO^T P and dK^T += Q^T dS.  Each kind keeps its A operands in LDS (natural and
-// transposed tiles, both written from one set of loads) and takes its B operands straight from
+// dV^T += dO^T P and dK^T += Q^T dS.  Each kind keeps its A operands in LDS (one tile each; the
+// products that need a transpose read it with frag_tr) and takes its B operands straight from
 // global memory (its own 32 rows) or from the accumulators of the previous product.
 // D_i = sum_c dO[i][c] O[i][c]: kind 0 forms it in registers from the fragments of its own
 // queries; kind 1 needs it for every query and builds a table in LDS while loading the dO tile.
@@ -485,8 +480,6 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
     // ---------------- dQ ----------------
     unsigned char* Kn = smem_raw;
     unsigned char* Vn = Kn + Lkp * 128;
-    unsigned char* Kt = Vn + Lkp * 128;
-    const int tstride = (Lkp + 8) * 2;
     bf16x8_t qf[4], dof[4], of[4];
     float lse_q = 0.f;
     auto load_rows = [&](int qt) {   // fragments of this wavefront's 32 queries
@@ -508,7 +501,6 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
         tile_fetch(vk, kg, p.ldk, k0, lk, it);
         tile_fetch(vv, vg, p.ldv, k0, lk, it);
         tile_store_natural(Kn, vk, it);
-        tile_store_transposed(Kt, tstride, vk, it);
         tile_store_natural(Vn, vv, it);
       }
     }
@@ -560,8 +552,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
           const bf16x8_t dsf = frag_from_regs(&ds[8 * s2]);
 #pragma unroll
           for (int ct = 0; ct < 2; ++ct)
-            dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_transposed(Kt, tstride, ct * 32 + lcol, kt * 32 + s2 * 16 + hh * 8), dsf, dq[ct], 0, 0, 0);
+            dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Kn, kt * 32 + s2 * 16, ct, lane), dsf, dq[ct], 0, 0, 0);
         }
       }
       if (valid_q) {
@@ -585,9 +576,6 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
   float* Ls = Dd + Lqp;
   unsigned char* Qn = reinterpret_cast<unsigned char*>(Ls + Lqp);
   unsigned char* dOn = Qn + Lqp * 128;
-  unsigned char* Qt = dOn + Lqp * 128;
-  const int tstride = (Lqp + 8) * 2;
-  unsigned char* dOt = Qt + 64 * tstride;
   bf16x8_t kf[4], vf[4];
   auto load_rows = [&](int kt) {   // fragments of this wavefront's 32 keys
     const int64_t grow = k0 + min(kt * 32 + lcol, lk - 1);
@@ -610,9 +598,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
 #pragma unroll
       for (int j = 0; j < 4; ++j) lse_r[j] = (cg == 0 && tq * 4 + j < lq) ? lseg[tq * 4 + j] : 0.f;
       tile_store_natural(Qn, vq, it);
-      tile_store_transposed(Qt, tstride, vq, it);
       tile_store_natural(dOn, vdo, it);
-      tile_store_transposed(dOt, tstride, vdo, it);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         float part = dot8(vdo[j], vo[j]);   // rows past lq were loaded as zeros
@@ -674,10 +660,8 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
         const bf16x8_t dsf = frag_from_regs(&ds[8 * s2]);
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
-          dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_transposed(dOt, tstride, ct * 32 + lcol, qt * 32 + s2 * 16 + hh * 8), pf, dv[ct], 0, 0, 0);
-          dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_transposed(Qt, tstride, ct * 32 + lcol, qt * 32 + s2 * 16 + hh * 8), dsf, dk[ct], 0, 0, 0);
+          dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(dOn, qt * 32 + s2 * 16, ct, lane), pf, dv[ct], 0, 0, 0);
+          dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Qn, qt * 32 + s2 * 16, ct, lane), dsf, dk[ct], 0, 0, 0);
         }
       }
     }
@@ -702,9 +686,9 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
 
 inline size_t mfma_bwd_lds(int max_lq, int max_lk) {
   const size_t Lq = ((max_lq + 31) / 32) * 32, Lk = ((max_lk + 31) / 32) * 32;
-  const size_t a = 2 * Lk * 128 + 64 * (Lk + 8) * 2;
-  const size_t bq = 2 * Lq * 128 + 2 * 64 * (Lq + 8) * 2;
-  return 2 * Lq * sizeof(float) + (a > bq ? a : bq);
+  const size_t a = 2 * Lk * 128;                           // dQ workgroups: K and V tiles
+  const size_t bq = 2 * Lq * sizeof(float) + 2 * Lq * 128;   // dK/dV workgroups: D and lse tables, Q and dO tiles
+  return a > bq ? a : bq;
 }
 
 template <typename T>
