@@ -319,7 +319,7 @@ __device__ __forceinline__ bf16x8_t frag_from_regs(const float* v) {
 }
 
 template <int NKT>
-__global__ void __launch_bounds__(256, 2) attn_fwd_mfma_kernel(const AttnParams p) {
+__global__ void __launch_bounds__(512, 1) attn_fwd_mfma_kernel(const AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int b = blockIdx.x / p.H, h = blockIdx.x % p.H;
   const int q0 = p.cu_q[b], lq = p.cu_q[b + 1] - q0;
@@ -449,16 +449,16 @@ inline size_t mfma_fwd_lds(int max_lk) {
   return (size_t)2 * Lp * 128;
 }
 
-// Backward with the same layouts, as two kinds of workgroup per (sentence, head), told apart by
-// blockIdx.y, which run side by side.  Kind 0 (dQ): a wavefront owns 32 queries and walks the key
-// tiles: S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D) * scale, dQ^T += K^T dS^T.  Kind 1
-// (dK, dV): a wavefront owns 32 keys and walks the query tiles: S = Q K^T, dP = dO V^T, then
-// dV^T += dO^T P and dK^T += Q^T dS.  Each kind keeps its A operands in LDS (one tile each; the
-// products that need a transpose read it with frag_tr) and takes its B operands straight from
-// global memory (its own 32 rows) or from the accumulators of the previous product.
-// D_i = sum_c dO[i][c] O[i][c]: kind 0 forms it in registers from the fragments of its own
-// queries; kind 1 needs it for every query and builds a table in LDS while loading the dO tile.
-__global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams p) {
+// Backward with the same layouts, one workgroup per (sentence, head).  The Q, dO, K and V tiles of
+// the sentence go to LDS once, with coalesced loads (D_i = sum_c dO[i][c] O[i][c] and the row
+// log-sum-exp become two small tables on the way; O itself is not kept).  Every operand fragment
+// then comes from LDS: rows of a tile with frag_natural, rows of its transpose with frag_tr.
+// Phase A (dQ): a wavefront owns 32 queries and walks the key tiles: S^T = K Q^T, dP^T = V dO^T,
+// dS^T = P^T * (dP^T - D) * scale, dQ^T += K^T dS^T.  Phase B (dK, dV): the wavefront owns 32 keys
+// and walks the query tiles: S = Q K^T, dP = dO V^T, then dV^T += dO^T P and dK^T += Q^T dS.
+// P is recomputed from the saved log-sum-exp in both phases; nothing is exchanged between them, and
+// nothing is accumulated with atomics.
+__global__ void __launch_bounds__(512, 1) attn_bwd_mfma_kernel(const AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int b = blockIdx.x / p.H, h = blockIdx.x % p.H;
   const int q0 = p.cu_q[b], lq = p.cu_q[b + 1] - q0;
@@ -476,127 +476,33 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
   const float cexp = scale * 1.44269504088896341f;   // exp(s * scale) = exp2(s * cexp)
   const int nwave = blockDim.x >> 6;
 
-  if (blockIdx.y == 0) {
-    // ---------------- dQ ----------------
-    unsigned char* Kn = smem_raw;
-    unsigned char* Vn = Kn + Lkp * 128;
-    bf16x8_t qf[4], dof[4], of[4];
-    float lse_q = 0.f;
-    auto load_rows = [&](int qt) {   // fragments of this wavefront's 32 queries
-      const int rl = min(qt * 32 + lcol, lq - 1);
-      const int64_t grow = q0 + rl;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        qf[s] = frag_global(qg + grow * p.ldq + (2 * s + hh) * 8);
-        dof[s] = frag_global(dog + grow * p.lddo + (2 * s + hh) * 8);
-        of[s] = frag_global(og + grow * p.ldo + (2 * s + hh) * 8);
-      }
-      lse_q = lseg[rl] * 1.44269504088896341f;   // in the exponent's base-2 units
-    };
-    if (wave < nqt) load_rows(wave);
-    for (int base = 0; base < Lkp * 2; base += blockDim.x) {
-      const int it = base + tid;
-      if (it < Lkp * 2) {
-        uint4 vk[4], vv[4];
-        tile_fetch(vk, kg, p.ldk, k0, lk, it);
-        tile_fetch(vv, vg, p.ldv, k0, lk, it);
-        tile_store_natural(Kn, vk, it);
-        tile_store_natural(Vn, vv, it);
-      }
-    }
-    __syncthreads();
-    for (int qt = wave; qt < nqt; qt += nwave) {
-      if (qt != wave) load_rows(qt);
-      const int ql = qt * 32 + lcol;
-      const bool valid_q = ql < lq;
-      const int64_t grow = q0 + (valid_q ? ql : lq - 1);
-      float Dq = 0.f;
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) Dq += (float)dof[s][e] * (float)of[s][e];
-      Dq += __shfl_xor(Dq, 32, WAVE);
-      Dq *= scale;   // dS = P * (dP - D) * scale = P * (dP * scale - D * scale)
-      f32x16_t dq[2];
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dq[ct][r] = 0.f;
-      const int kt_end = p.causal ? min(nkt, qt + 1) : nkt;
-      for (int kt = 0; kt < kt_end; ++kt) {
-        f32x16_t sc, dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Kn, kt * 32 + lcol, 2 * s + hh), qf[s], sc, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Vn, kt * 32 + lcol, 2 * s + hh), dof[s], dp, 0, 0, 0);
-        }
-        // Keys past the sentence end need no mask here: their rows of K are zeros in LDS, so
-        // whatever dS holds for them adds nothing to dQ.  Only the causal diagonal tile is masked.
-        float ds[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float pr = __builtin_amdgcn_exp2f(fmaf(sc[r], cexp, -lse_q));
-          ds[r] = pr * fmaf(dp[r], scale, -Dq);
-        }
-        if (p.causal && kt == qt) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-            if (key > ql) ds[r] = 0.f;
-          }
-        }
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8_t dsf = frag_from_regs(&ds[8 * s2]);
-#pragma unroll
-          for (int ct = 0; ct < 2; ++ct)
-            dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Kn, kt * 32 + s2 * 16, ct, lane), dsf, dq[ct], 0, 0, 0);
-        }
-      }
-      if (valid_q) {
-        bf16_t* dst = (bf16_t*)p.dq + grow * p.lddq + h * 64;
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            uint2 o;
-            o.x = pack_bf16(dq[ct][4 * g4 + 0], dq[ct][4 * g4 + 1]);
-            o.y = pack_bf16(dq[ct][4 * g4 + 2], dq[ct][4 * g4 + 3]);
-            *reinterpret_cast<uint2*>(dst + ct * 32 + 8 * g4 + 4 * hh) = o;
-          }
-      }
-    }
-    return;
-  }
-
-  // ---------------- dK, dV ----------------
-  float* Dd = reinterpret_cast<float*>(smem_raw);   // [Lqp]
-  float* Ls = Dd + Lqp;
+  float* Dd = reinterpret_cast<float*>(smem_raw);   // [Lqp] D_i * scale
+  float* Ls = Dd + Lqp;                             // [Lqp] lse_i in base-2 units
   unsigned char* Qn = reinterpret_cast<unsigned char*>(Ls + Lqp);
   unsigned char* dOn = Qn + Lqp * 128;
-  bf16x8_t kf[4], vf[4];
-  auto load_rows = [&](int kt) {   // fragments of this wavefront's 32 keys
-    const int64_t grow = k0 + min(kt * 32 + lcol, lk - 1);
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      kf[s] = frag_global(kg + grow * p.ldk + (2 * s + hh) * 8);
-      vf[s] = frag_global(vg + grow * p.ldv + (2 * s + hh) * 8);
-    }
-  };
-  if (wave < nkt) load_rows(wave);
-  for (int base = 0; base < Lqp * 2; base += blockDim.x) {
+  unsigned char* Kn = dOn + Lqp * 128;
+  unsigned char* Vn = Kn + Lkp * 128;
+
+  // all loads of an iteration are issued before the first store
+  const int n_items = (Lqp > Lkp ? Lqp : Lkp) * 2;
+  for (int base = 0; base < n_items; base += blockDim.x) {
     const int it = base + tid;
-    if (it < Lqp * 2) {
-      uint4 vq[4], vdo[4], vo[4];
+    const bool has_q = it < Lqp * 2, has_k = it < Lkp * 2;
+    uint4 vq[4], vdo[4], vo[4], vk[4], vv[4];
+    float lse_r[4] = {0.f, 0.f, 0.f, 0.f};
+    const int cg = it & 7, tq = it >> 3;
+    if (has_q) {
       tile_fetch(vq, qg, p.ldq, q0, lq, it);
       tile_fetch(vdo, dog, p.lddo, q0, lq, it);
       tile_fetch(vo, og, p.ldo, q0, lq, it);
-      const int cg = it & 7, tq = it >> 3;
-      float lse_r[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) lse_r[j] = (cg == 0 && tq * 4 + j < lq) ? lseg[tq * 4 + j] : 0.f;
+    }
+    if (has_k) {
+      tile_fetch(vk, kg, p.ldk, k0, lk, it);
+      tile_fetch(vv, vg, p.ldv, k0, lk, it);
+    }
+    if (has_q) {
       tile_store_natural(Qn, vq, it);
       tile_store_natural(dOn, vdo, it);
 #pragma unroll
@@ -608,13 +514,86 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
         if (cg == 0) { Dd[tq * 4 + j] = part * scale; Ls[tq * 4 + j] = lse_r[j] * 1.44269504088896341f; }
       }
     }
+    if (has_k) {
+      tile_store_natural(Kn, vk, it);
+      tile_store_natural(Vn, vv, it);
+    }
   }
   __syncthreads();
+
+  // ---------------- phase A: dQ ----------------
+  for (int qt = wave; qt < nqt; qt += nwave) {
+    const int ql = qt * 32 + lcol;
+    const bool valid_q = ql < lq;
+    bf16x8_t qf[4], dof[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      qf[s] = frag_natural(Qn, ql, 2 * s + hh);
+      dof[s] = frag_natural(dOn, ql, 2 * s + hh);
+    }
+    const float lse_q = Ls[ql], Dq = Dd[ql];   // dS = P * (dP - D) * scale = P * (dP * scale - D * scale)
+    f32x16_t dq[2];
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dq[ct][r] = 0.f;
+    const int kt_end = p.causal ? min(nkt, qt + 1) : nkt;
+    for (int kt = 0; kt < kt_end; ++kt) {
+      f32x16_t sc, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Kn, kt * 32 + lcol, 2 * s + hh), qf[s], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Vn, kt * 32 + lcol, 2 * s + hh), dof[s], dp, 0, 0, 0);
+      }
+      // Keys past the sentence end need no mask here: their rows of K are zeros in LDS, so
+      // whatever dS holds for them adds nothing to dQ.  Only the causal diagonal tile is masked.
+      float ds[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float pr = __builtin_amdgcn_exp2f(fmaf(sc[r], cexp, -lse_q));
+        ds[r] = pr * fmaf(dp[r], scale, -Dq);
+      }
+      if (p.causal && kt == qt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          if (key > ql) ds[r] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8_t dsf = frag_from_regs(&ds[8 * s2]);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+          dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Kn, kt * 32 + s2 * 16, ct, lane), dsf, dq[ct], 0, 0, 0);
+      }
+    }
+    if (valid_q) {
+      bf16_t* dst = (bf16_t*)p.dq + (int64_t)(q0 + ql) * p.lddq + h * 64;
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          uint2 o;
+          o.x = pack_bf16(dq[ct][4 * g4 + 0], dq[ct][4 * g4 + 1]);
+          o.y = pack_bf16(dq[ct][4 * g4 + 2], dq[ct][4 * g4 + 3]);
+          *reinterpret_cast<uint2*>(dst + ct * 32 + 8 * g4 + 4 * hh) = o;
+        }
+    }
+  }
+
+  // ---------------- phase B: dK, dV ----------------
   for (int kt = wave; kt < nkt; kt += nwave) {
-    if (kt != wave) load_rows(kt);
     const int kl = kt * 32 + lcol;
     const bool valid_k = kl < lk;
-    const int64_t grow = k0 + (valid_k ? kl : lk - 1);
+    bf16x8_t kf[4], vf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      kf[s] = frag_natural(Kn, kl, 2 * s + hh);
+      vf[s] = frag_natural(Vn, kl, 2 * s + hh);
+    }
     f32x16_t dk[2], dv[2];
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
@@ -639,12 +618,12 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
         // accumulator registers 4 g4 .. 4 g4 + 3 are four consecutive queries: one 16-byte read each
         const float4 l4 = *reinterpret_cast<const float4*>(Ls + qt * 32 + 8 * g4 + 4 * hh);
         const float4 d4 = *reinterpret_cast<const float4*>(Dd + qt * 32 + 8 * g4 + 4 * hh);
-        const float lq[4] = {l4.x, l4.y, l4.z, l4.w}, dq_[4] = {d4.x, d4.y, d4.z, d4.w};
+        const float lq4[4] = {l4.x, l4.y, l4.z, l4.w}, dq4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * g4 + e;
-          pr[r] = __builtin_amdgcn_exp2f(fmaf(sc[r], cexp, -lq[e]));
-          ds[r] = pr[r] * fmaf(dp[r], scale, -dq_[e]);
+          pr[r] = __builtin_amdgcn_exp2f(fmaf(sc[r], cexp, -lq4[e]));
+          ds[r] = pr[r] * fmaf(dp[r], scale, -dq4[e]);
         }
       }
       if (p.causal && qt == kt) {
@@ -666,8 +645,8 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
       }
     }
     if (valid_k) {
-      bf16_t* dkd = (bf16_t*)p.dk + grow * p.lddk + h * 64;
-      bf16_t* dvd = (bf16_t*)p.dv + grow * p.lddv + h * 64;
+      bf16_t* dkd = (bf16_t*)p.dk + (int64_t)(k0 + kl) * p.lddk + h * 64;
+      bf16_t* dvd = (bf16_t*)p.dv + (int64_t)(k0 + kl) * p.lddv + h * 64;
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
@@ -686,9 +665,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_mfma_kernel(const AttnParams 
 
 inline size_t mfma_bwd_lds(int max_lq, int max_lk) {
   const size_t Lq = ((max_lq + 31) / 32) * 32, Lk = ((max_lk + 31) / 32) * 32;
-  const size_t a = 2 * Lk * 128;                           // dQ workgroups: K and V tiles
-  const size_t bq = 2 * Lq * sizeof(float) + 2 * Lq * 128;   // dK/dV workgroups: D and lse tables, Q and dO tiles
-  return a > bq ? a : bq;
+  return 2 * Lq * sizeof(float) + 2 * Lq * 128 + 2 * Lk * 128;   // D and lse tables; Q, dO, K, V tiles
 }
 
 template <typename T>
@@ -715,8 +692,8 @@ static bool mfma_ok(Dtype dt, const AttnParams& p) {
 void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p, const LaunchEvents& ev) {
   if (mfma_ok(dt, p)) {
     const size_t lds = mfma_fwd_lds(p.max_lk);
-    // one wavefront per 32 queries: short sentences get small workgroups, so more of them share a CU
-    const int threads = 64 * std::min(4, (p.max_lq + 31) / 32);
+    // one wavefront per 32 queries, up to eight: short sentences get small workgroups, so more of them share a CU
+    const int threads = 64 * std::min(8, (p.max_lq + 31) / 32);
     if (p.max_lk <= 128) {
       hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       hipExtLaunchKernelGGL(attn_fwd_mfma_kernel<4>, dim3(p.B * p.H), dim3(threads), lds, st, ev.start, ev.stop, 0, p);
@@ -740,8 +717,8 @@ void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p, const Launch
   if (mfma_ok(dt, p) && p.lddo % 8 == 0 && p.lddq % 4 == 0 && p.lddk % 4 == 0 && p.lddv % 4 == 0) {
     const size_t lds = mfma_bwd_lds(p.max_lq, p.max_lk);
     hipFuncSetAttribute((const void*)attn_bwd_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    const int threads = 64 * std::min(4, (std::max(p.max_lq, p.max_lk) + 31) / 32);
-    hipExtLaunchKernelGGL(attn_bwd_mfma_kernel, dim3(p.B * p.H, 2), dim3(threads), lds, st, ev.start, ev.stop, 0, p);
+    const int threads = 64 * std::min(8, (std::max(p.max_lq, p.max_lk) + 31) / 32);
+    hipExtLaunchKernelGGL(attn_bwd_mfma_kernel, dim3(p.B * p.H), dim3(threads), lds, st, ev.start, ev.stop, 0, p);
     return;
   }
   const size_t lds = attn_lds_bytes(dt, p.dh, p.max_lq, p.max_lk, true);
