@@ -55,8 +55,8 @@ def cpu_baseline(setup, batch, target_tokens=4096):
                       f"({tok} target tokens) of one batch, {dt:.1f} s"}
 
 
-def bench_translate(args, setup, ctx, batch):
-    """One step = one call of mm_translate_greedy on one batch's source sentences."""
+def bench_translate(args, setup, ctx, batches):
+    """One step = one call of mm_translate_greedy on the source sentences of one (or several) batches."""
     import numpy as np
     import torch
     sh = setup.shape
@@ -67,8 +67,13 @@ def bench_translate(args, setup, ctx, batch):
         w = ctx.mm_get_params(gen)
         w[layout[1][1] + 2] = -1e3                       # no EOS: every sentence runs every step
         ctx.mm_set_params(gen, w)
-    src = torch.tensor(batch.src_ids, dtype=torch.int32, device="cuda")
-    s_len = batch.lengths[:, 0].copy()
+    s_len = np.concatenate([b.lengths[:, 0] for b in batches]).astype(np.int32)
+    src_host = np.zeros((len(s_len), max(b.src_ids.shape[1] for b in batches)), dtype=np.int32)
+    row = 0
+    for b in batches:
+        src_host[row:row + len(b.lengths), :b.src_ids.shape[1]] = b.src_ids
+        row += len(b.lengths)
+    src = torch.tensor(src_host, dtype=torch.int32, device="cuda")
     B = len(s_len)
     directions = [tasks[k % len(tasks)] for k in range(args.warmup + args.steps)]
     for k in range(args.warmup):
@@ -114,6 +119,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--accumulate", type=int, default=1, help="routed passes per update")
+    ap.add_argument("--translate-batches", type=int, default=1,
+                    help="with --translate: merge the source sentences of this many batches into one call")
     ap.add_argument("--task-temperature", type=float, default=None,
                     help="draw each pass's task with probability proportional to (corpus size)^(1/T), "
                          "corpus sizes falling off as 1/rank, instead of uniformly")
@@ -144,10 +151,11 @@ def main():
     n_steps = (args.warmup + args.steps) * A      # routed passes; A of them per update
     batches = mm_synth.make_batches(setup)
     directions = mm_synth.sample_directions(setup, n_steps, temperature=args.task_temperature)
-    ctx = context_from_setup(setup, fill_params=mm_synth.fill_params)
+    ctx = context_from_setup(setup, fill_params=mm_synth.fill_params,
+                             max_batch_tokens=16384 if args.translate else None)
 
     if args.translate:
-        return bench_translate(args, setup, ctx, batches[0])
+        return bench_translate(args, setup, ctx, batches[:max(1, args.translate_batches)])
 
     # inputs resident in HBM before timing
     dev = []
