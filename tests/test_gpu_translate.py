@@ -217,3 +217,33 @@ def test_config2_translation_at_full_size():
     assert len({tuple(r) for r in ref_ids.tolist()}) >= 6      # the source decides the output
     assert same.mean() >= 0.75       # the others left it at a near-tie (checked above)
     ctx.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_only_the_tasks_modules_are_read(dtype):
+    """Section 3.2: a task needs only its own modules.  Every parameter of every module off the
+    task's route is overwritten with NaN; translation and a training step of that task must give
+    the same bits as before (one stray read of another module's memory would turn them into NaN)."""
+    d = 32 if dtype == "f32" else 128
+    setup = tiny_setup(d=d, H=2, F_=64, V=56, n_lang=3, adapter_dim=16, dtype=dtype, max_len=24)
+    ctx, orc = sharpened_pair(setup, 6.0, 1.0)
+    batch = tiny_batch(setup, lengths=LENGTHS)
+    src, s_len = batch.src_ids, batch.lengths[:, 0].copy()
+    task = 3
+    route = set(ctx.mm_get_route(task))
+    assert 0 < len(route) < ctx.mm_num_modules()
+    before = ctx.mm_translate_greedy(task, src, s_len, 8)
+    loss0 = ctx.mm_train_step(task, batch.src_ids, batch.tgt_ids, batch.lengths)
+    grads0 = {j: ctx.mm_get_grads(j) for j in route}
+    for j in range(ctx.mm_num_modules()):
+        if j not in route:
+            ctx.mm_set_params(j, np.full_like(ctx.mm_get_params(j), np.nan))
+    after = ctx.mm_translate_greedy(task, src, s_len, 8)
+    assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])
+    for j in route:                                  # same step again from empty buckets
+        ctx.mm_set_grads(j, np.zeros_like(grads0[j]), 0)
+    loss1 = ctx.mm_train_step(task, batch.src_ids, batch.tgt_ids, batch.lengths)
+    assert loss1 == loss0 and np.isfinite(loss1)
+    for j in route:
+        assert np.array_equal(ctx.mm_get_grads(j), grads0[j])
+    ctx.close()
