@@ -82,9 +82,9 @@ struct mm_ctx {
   AdamSegment* seg_host = nullptr; AdamSegment* seg_dev = nullptr; int seg_cap = 0;
   hipEvent_t ev_seg = nullptr;
   // table of the step's deferred weight-gradient products (pinned host copy, device copy)
-  GemmParams* gtab_host = nullptr; GemmParams* gtab_dev = nullptr;
-  int32_t* gstart_host = nullptr; int32_t* gstart_dev = nullptr;
-  LnReduceJob* ljob_host = nullptr; LnReduceJob* ljob_dev = nullptr;
+  // (one pinned block and one device block: product table, first-tile table and the LayerNorm
+  // reduction jobs are packed back to back and travel in one copy)
+  unsigned char* tab_host = nullptr; unsigned char* tab_dev = nullptr;
   hipEvent_t ev_gtab = nullptr;
   Arena ws;
   // last step
@@ -224,21 +224,6 @@ struct Run {
     jb.partial = partial; jb.dgamma = gg; jb.dbeta = gb; jb.n_partial = n_partial; jb.d = d;
     jb.first_block = 0; jb.pad = 0;
     ln_jobs->push_back(jb);
-  }
-  void flush_ln_jobs() {
-    if (dry || ln_jobs->empty()) return;
-    int blocks = 0;
-    size_t n = ln_jobs->size() < (size_t)MAX_GROUPED_C ? ln_jobs->size() : (size_t)MAX_GROUPED_C;
-    for (size_t i = 0; i < n; ++i) {
-      (*ln_jobs)[i].first_block = blocks;
-      blocks += (2 * (*ln_jobs)[i].d + 63) / 64;
-      c->ljob_host[i] = (*ln_jobs)[i];
-    }
-    hipMemcpyAsync(c->ljob_dev, c->ljob_host, n * sizeof(LnReduceJob), hipMemcpyHostToDevice, c->st);
-    begin(MM_K_LAYERNORM_BWD, 0.0);
-    launch_ln_reduce_grouped(c->st, c->ljob_dev, (int)n, blocks);
-    end();
-    ln_jobs->clear();
   }
   void colsum(const void* Y, int y_f32, int64_t ldy, int M, int N, float* partial, float* dst, int split,
               int64_t seg) {
@@ -398,24 +383,48 @@ struct Step {
     if (Yf32) run.colsum(Yf32, 1, p.ldb, p.K, p.N, partial, gb, p.c_split, p.c_seg_stride);
     else run.colsum(p.B, 0, p.ldb, p.K, p.N, partial, gb, p.c_split, p.c_seg_stride);
   }
-  void flush_wgrads() {
-    if (deferred.empty()) return;
-    hipEventSynchronize(c->ev_gtab);  // the previous step's upload has left the pinned table
-    int tiles = 0;
+  // End of the step: the deferred weight-gradient products as one grouped launch, then the
+  // LayerNorm gain/shift partial sums as one launch.  Their tables go up in a single copy.
+  void flush_deferred() {
+    if (dry()) return;
+    std::vector<LnReduceJob>& jobs = *run.ln_jobs;
+    const size_t ng = deferred.size();
+    const size_t nl = jobs.size() < (size_t)MAX_GROUPED_C ? jobs.size() : (size_t)MAX_GROUPED_C;
+    if (!ng && !nl) return;
+    hipEventSynchronize(c->ev_gtab);  // the previous step's upload has left the pinned block
+    const size_t off_start = (ng * sizeof(GemmParams) + 15) & ~(size_t)15;
+    const size_t off_jobs = (off_start + ng * sizeof(int32_t) + 15) & ~(size_t)15;
+    const size_t total = off_jobs + nl * sizeof(LnReduceJob);
+    GemmParams* gtab = reinterpret_cast<GemmParams*>(c->tab_host);
+    int32_t* gstart = reinterpret_cast<int32_t*>(c->tab_host + off_start);
+    LnReduceJob* ljob = reinterpret_cast<LnReduceJob*>(c->tab_host + off_jobs);
+    int tiles = 0, blocks = 0;
     double flops = 0;
-    for (size_t i = 0; i < deferred.size(); ++i) {
+    for (size_t i = 0; i < ng; ++i) {
       gemm_prepare_grouped(deferred[i]);
-      c->gtab_host[i] = deferred[i];
-      c->gstart_host[i] = tiles;
+      gtab[i] = deferred[i];
+      gstart[i] = tiles;
       tiles += gemm_grouped_tiles(deferred[i]);
       flops += 2.0 * deferred[i].M * deferred[i].N * deferred[i].K;
     }
-    hipMemcpyAsync(c->gtab_dev, c->gtab_host, deferred.size() * sizeof(GemmParams), hipMemcpyHostToDevice, c->st);
-    hipMemcpyAsync(c->gstart_dev, c->gstart_host, deferred.size() * sizeof(int32_t), hipMemcpyHostToDevice, c->st);
+    for (size_t i = 0; i < nl; ++i) {
+      jobs[i].first_block = blocks;
+      blocks += (2 * jobs[i].d + 63) / 64;
+      ljob[i] = jobs[i];
+    }
+    hipMemcpyAsync(c->tab_dev, c->tab_host, total, hipMemcpyHostToDevice, c->st);
     hipEventRecord(c->ev_gtab, c->st);
-    launch_gemm_grouped_tn(c->st, c->gtab_dev, c->gstart_dev, (int)deferred.size(), tiles,
-                           run.begin_timed(MM_K_GEMM, flops));
+    if (ng)
+      launch_gemm_grouped_tn(c->st, reinterpret_cast<const GemmParams*>(c->tab_dev),
+                             reinterpret_cast<const int32_t*>(c->tab_dev + off_start), (int)ng, tiles,
+                             run.begin_timed(MM_K_GEMM, flops));
+    if (nl) {
+      run.begin(MM_K_LAYERNORM_BWD, 0.0);
+      launch_ln_reduce_grouped(c->st, reinterpret_cast<const LnReduceJob*>(c->tab_dev + off_jobs), (int)nl, blocks);
+      run.end();
+    }
     deferred.clear();
+    jobs.clear();
   }
 
   Grad ffn_bwd(const PV& pv, int t0, const FfnSave& s, Grad g, int R, int hidden) {
@@ -742,8 +751,7 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
     launch_embed_grad(c->st, c->sort_keys, ge.dx, m_src.g, eg_partial, S, d, sqrt_d);
     run.end();
   }
-  s.flush_wgrads();
-  s.run.flush_ln_jobs();
+  s.flush_deferred();
 }
 
 bool valid_module(mm_ctx* c, int id) { return id >= 0 && id < (int)c->mods.size(); }
@@ -1027,22 +1035,19 @@ mm_status mm_create(const mm_config* cfg, mm_ctx** out) {
   guard(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking), "hipStreamCreate");
   guard(hipEventCreateWithFlags(&c->ev_packed, hipEventDisableTiming), "hipEventCreate");
   guard(hipEventCreateWithFlags(&c->ev_sorted, hipEventDisableTiming), "hipEventCreate");
-  guard(hipMalloc((void**)&c->flag, 64), "hipMalloc(flag)");
   guard(hipMalloc((void**)&c->loss_dev, 64), "hipMalloc(loss)");
   guard(hipHostMalloc((void**)&c->result_host, 64, hipHostMallocDefault), "hipHostMalloc(result)");
   guard(hipEventCreateWithFlags(&c->ev_stage, hipEventDisableTiming), "hipEventCreate");
   guard(hipEventCreateWithFlags(&c->ev_done, hipEventDisableTiming), "hipEventCreate");
   guard(hipEventCreateWithFlags(&c->ev_seg, hipEventDisableTiming), "hipEventCreate");
   guard(hipEventCreateWithFlags(&c->ev_gtab, hipEventDisableTiming), "hipEventCreate");
-  guard(hipHostMalloc((void**)&c->gtab_host, MAX_GROUPED * sizeof(GemmParams), hipHostMallocDefault), "hipHostMalloc(table)");
-  guard(hipHostMalloc((void**)&c->gstart_host, MAX_GROUPED * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(table)");
-  guard(hipMalloc((void**)&c->gtab_dev, MAX_GROUPED * sizeof(GemmParams)), "hipMalloc(table)");
-  guard(hipMalloc((void**)&c->gstart_dev, MAX_GROUPED * sizeof(int32_t)), "hipMalloc(table)");
-  guard(hipHostMalloc((void**)&c->ljob_host, MAX_GROUPED_C * sizeof(LnReduceJob), hipHostMallocDefault), "hipHostMalloc(table)");
-  guard(hipMalloc((void**)&c->ljob_dev, MAX_GROUPED_C * sizeof(LnReduceJob)), "hipMalloc(table)");
+  const size_t tab_bytes = MAX_GROUPED * (sizeof(GemmParams) + sizeof(int32_t)) + MAX_GROUPED_C * sizeof(LnReduceJob) + 64;
+  guard(hipHostMalloc((void**)&c->tab_host, tab_bytes, hipHostMallocDefault), "hipHostMalloc(table)");
+  guard(hipMalloc((void**)&c->tab_dev, tab_bytes), "hipMalloc(table)");
   if (s != MM_OK) return s;
   guard(hipMemcpy(c->pe, pe.data(), pe.size() * 4, hipMemcpyHostToDevice), "hipMemcpy(pe)");
-  guard(hipMemset(c->flag, 0, 64), "hipMemset");
+  c->flag = reinterpret_cast<int32_t*>(c->loss_dev + 1);   // loss and id-check flag leave in one copy
+  guard(hipMemset(c->loss_dev, 0, 64), "hipMemset");
   if (s != MM_OK) return s;
   int32_t* p = c->meta;
   c->cu_s = p; p += T + 1; c->cu_u = p; p += T + 1; c->lens = p; p += 2 * T;
@@ -1055,7 +1060,7 @@ mm_status mm_destroy(mm_ctx* c) {
   if (!c->plan_only) {
     hipStreamSynchronize(c->st);
     for (auto& m : c->mods) { hipFree(m.theta); hipFree(m.m); hipFree(m.v); hipFree(m.g); if (m.w16) hipFree(m.w16); }
-    hipFree(c->pe); hipFree(c->meta); hipFree(c->sort_keys); hipFree(c->flag); hipFree(c->loss_dev);
+    hipFree(c->pe); hipFree(c->meta); hipFree(c->sort_keys); hipFree(c->loss_dev);
     if (c->ids_dev) hipFree(c->ids_dev);
     if (c->stage) hipHostFree(c->stage);
     if (c->result_host) hipHostFree(c->result_host);
@@ -1071,12 +1076,8 @@ mm_status mm_destroy(mm_ctx* c) {
     if (c->aux) { hipStreamSynchronize(c->aux); hipStreamDestroy(c->aux); }
     if (c->ev_packed) hipEventDestroy(c->ev_packed);
     if (c->ev_sorted) hipEventDestroy(c->ev_sorted);
-    if (c->gtab_host) hipHostFree(c->gtab_host);
-    if (c->gstart_host) hipHostFree(c->gstart_host);
-    if (c->gtab_dev) hipFree(c->gtab_dev);
-    if (c->gstart_dev) hipFree(c->gstart_dev);
-    if (c->ljob_host) hipHostFree(c->ljob_host);
-    if (c->ljob_dev) hipFree(c->ljob_dev);
+    if (c->tab_host) hipHostFree(c->tab_host);
+    if (c->tab_dev) hipFree(c->tab_dev);
   }
   delete c;
   return MM_OK;
@@ -1213,9 +1214,9 @@ mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const i
   s = ensure_ws(c, c->ws.high);
   if (s != MM_OK) return s;
 
-  HIP_TRY(c, hipMemcpyAsync(c->lens, st_lens, (size_t)2 * B * 4, hipMemcpyHostToDevice, c->st));
-  HIP_TRY(c, hipMemcpyAsync(c->cu_s, st_cu_s, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, c->st));
-  HIP_TRY(c, hipMemcpyAsync(c->cu_u, st_cu_u, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, c->st));
+  // lengths and both prefix sums lie back to back in the staging block and travel in one copy
+  c->lens = c->meta; c->cu_s = c->meta + 2 * B; c->cu_u = c->cu_s + B + 1;
+  HIP_TRY(c, hipMemcpyAsync(c->meta, st_lens, n_meta * 4, hipMemcpyHostToDevice, c->st));
   HIP_TRY(c, hipEventRecord(c->ev_stage, c->st));
   launch_fill_i32(c->st, c->flag, 1, 0);
   launch_pack_ids(c->st, src_dev, tgt_dev, c->lens, c->cu_s, c->cu_u, B, S_max, T_max, c->cfg.vocab, c->src_tok,
@@ -1228,8 +1229,7 @@ mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const i
   HIP_TRY(c, hipEventRecord(c->ev_sorted, c->aux));
   run_step(c, rt, false, lengths);
   HIP_TRY(c, hipGetLastError());
-  HIP_TRY(c, hipMemcpyAsync(&c->result_host[0], c->loss_dev, 4, hipMemcpyDeviceToHost, c->st));
-  HIP_TRY(c, hipMemcpyAsync(&c->result_host[1], c->flag, 4, hipMemcpyDeviceToHost, c->st));
+  HIP_TRY(c, hipMemcpyAsync(&c->result_host[0], c->loss_dev, 8, hipMemcpyDeviceToHost, c->st));   // loss, flag
   HIP_TRY(c, hipEventRecord(c->ev_done, c->st));
   for (int j : rt.ids) c->mods[j].touched += 1;
   c->pending = true; c->pending_task = task; c->pending_counted = true;
@@ -1302,9 +1302,9 @@ mm_status mm_translate_greedy(mm_ctx* c, int32_t task, const int32_t* src_ids, c
   run_translate(c, rt, true, src_lengths, max_new, out);
   s = ensure_ws(c, c->ws.high);
   if (s != MM_OK) return s;
-  HIP_TRY(c, hipMemcpyAsync(c->lens, st_lens, (size_t)2 * B * 4, hipMemcpyHostToDevice, c->st));
-  HIP_TRY(c, hipMemcpyAsync(c->cu_s, st_cu_s, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, c->st));
-  HIP_TRY(c, hipMemcpyAsync(c->cu_u, st_cu_u, ((size_t)B + 1) * 4, hipMemcpyHostToDevice, c->st));
+  // lengths and both prefix sums lie back to back in the staging block and travel in one copy
+  c->lens = c->meta; c->cu_s = c->meta + 2 * B; c->cu_u = c->cu_s + B + 1;
+  HIP_TRY(c, hipMemcpyAsync(c->meta, st_lens, n_meta * 4, hipMemcpyHostToDevice, c->st));
   HIP_TRY(c, hipEventRecord(c->ev_stage, c->st));
   launch_fill_i32(c->st, c->flag, 1, 0);
   launch_pack_ids(c->st, src_dev, tgt_dev, c->lens, c->cu_s, c->cu_u, B, S_max, 2, c->cfg.vocab, c->src_tok,
