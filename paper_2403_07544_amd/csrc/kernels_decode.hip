@@ -3,6 +3,9 @@
 // pick of the next token.  Everything else of a decoding step reuses the training kernels.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+#include <cstdlib>
+
 #include "mm_kernels.h"
 
 namespace mm {
@@ -14,50 +17,6 @@ template <> __device__ inline float ldf<bf16_t>(const bf16_t* p) { return bf16_t
 template <typename T> __device__ inline void stf(T* p, float v);
 template <> __device__ inline void stf<float>(float* p, float v) { *p = v; }
 template <> __device__ inline void stf<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
-
-// One workgroup (64 lanes) per (head, sentence).  o = softmax(q K^T / sqrt(dh)) V over the
-// sentence's `len` keys: scores one key per lane, the weighted sum one output element per lane.
-// Keys of sentence b start at row cu[b] (len = cu[b+1]-cu[b]) or, with cu == null, at row
-// b*seq_rows with len_uniform keys.  Scores and the sum are fp32; p[] lives in LDS.
-template <typename T>
-__global__ void __launch_bounds__(64)
-attn_decode_kernel(const T* __restrict__ q, int64_t q_stride, const T* __restrict__ k, const T* __restrict__ v,
-                   int64_t ldkv, const int32_t* __restrict__ cu, int64_t seq_rows, int len_uniform,
-                   T* __restrict__ o, int64_t o_stride, int dh, float scale) {
-  extern __shared__ float smem[];
-  const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
-  const int64_t row0 = cu ? (int64_t)cu[b] : (int64_t)b * seq_rows;
-  const int len = cu ? cu[b + 1] - cu[b] : len_uniform;
-  float* qs = smem;        // [dh]
-  float* p = smem + dh;    // [len]
-  for (int e = lane; e < dh; e += 64) qs[e] = ldf(q + (int64_t)b * q_stride + h * dh + e);
-  __syncthreads();
-  float mx = -INFINITY;
-  for (int j = lane; j < len; j += 64) {
-    const T* kr = k + (row0 + j) * ldkv + h * dh;
-    float s = 0.f;
-    for (int e = 0; e < dh; ++e) s = fmaf(qs[e], ldf(kr + e), s);
-    s *= scale;
-    p[j] = s;
-    mx = fmaxf(mx, s);
-  }
-  for (int off = 32; off; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-  float sum = 0.f;
-  for (int j = lane; j < len; j += 64) {
-    const float w = __expf(p[j] - mx);
-    p[j] = w;
-    sum += w;
-  }
-  for (int off = 32; off; off >>= 1) sum += __shfl_xor(sum, off);
-  __syncthreads();
-  const float inv = 1.f / sum;
-  for (int e = lane; e < dh; e += 64) {
-    const T* vc = v + row0 * ldkv + h * dh + e;
-    float acc = 0.f;
-    for (int j = 0; j < len; ++j) acc = fmaf(p[j], ldf(vc + (int64_t)j * ldkv), acc);
-    stf(o + (int64_t)b * o_stride + h * dh + e, acc * inv);
-  }
-}
 
 // 16 bytes of a row as floats: 8 bf16 or 4 fp32.
 template <typename T> struct Vec16;
@@ -81,7 +40,10 @@ template <> struct Vec16<float> {
   }
 };
 
-// Same contract as attn_decode_kernel for head sizes that are a power of two of 16-byte chunks.
+// One workgroup per (head, sentence).  o = softmax(q K^T / sqrt(dh)) V over the sentence's `len`
+// keys.  Keys of sentence b start at row cu[b] (len = cu[b+1]-cu[b]) or, with cu == null, at row
+// b*seq_rows with len_uniform keys.  Scores and sums are fp32; the scores live in LDS.
+// The head size is a power of two of 16-byte chunks (the library admits 16, 32 and 64):
 // LPK = dh / Vec16::N lanes share one key, so a wavefront covers 64/LPK keys per pass with
 // 16-byte loads that neighbouring lanes take from neighbouring addresses; four wavefronts and
 // two passes in flight make a chunk of 8 * 64/LPK keys whose loads are all issued before the
@@ -250,31 +212,25 @@ void launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_strid
   const float scale = 1.0f / sqrtf((float)dh);
   const dim3 grid(H, B);
   const int n = dt == BF16 ? 8 : 4;                       // elements per 16 bytes
-  const int lpk = dh % n == 0 ? dh / n : 0;
+  const int lpk = dh / n;
   const auto al = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-  const bool vec = lpk >= 1 && lpk <= 64 && (lpk & (lpk - 1)) == 0 && al(q) && al(k) && al(v) && q_stride % n == 0 &&
-                   ldkv % n == 0;
-  if (vec) {
-    const size_t lds = (size_t)(8 + 4 * dh + max_len) * sizeof(float);
+  const bool ok = (dh == 16 || dh == 32 || dh == 64) && al(q) && al(k) && al(v) && q_stride % n == 0 && ldkv % n == 0;
+  if (!ok) {   // mm_create admits no other head size and the runtime's buffers are 256-byte aligned
+    fprintf(stderr, "launch_attn_decode: unsupported head size %d or unaligned operands\n", dh);
+    abort();
+  }
+  const size_t lds = (size_t)(8 + 4 * dh + max_len) * sizeof(float);
 #define MM_AD(T, L)                                                                                              \
   case L:                                                                                                        \
     attn_decode_vec_kernel<T, L><<<grid, 256, lds, st>>>((const T*)q, q_stride, (const T*)k, (const T*)v, ldkv, cu, \
-                                                        seq_rows, len_uniform, (T*)o, o_stride, scale);          \
-    return;
-    if (dt == BF16) {
-      switch (lpk) { MM_AD(bf16_t, 1) MM_AD(bf16_t, 2) MM_AD(bf16_t, 4) MM_AD(bf16_t, 8) MM_AD(bf16_t, 16) MM_AD(bf16_t, 32) MM_AD(bf16_t, 64) }
-    } else {
-      switch (lpk) { MM_AD(float, 1) MM_AD(float, 2) MM_AD(float, 4) MM_AD(float, 8) MM_AD(float, 16) MM_AD(float, 32) MM_AD(float, 64) }
-    }
-#undef MM_AD
+                                                         seq_rows, len_uniform, (T*)o, o_stride, scale);         \
+    break;
+  if (dt == BF16) {
+    switch (lpk) { MM_AD(bf16_t, 2) MM_AD(bf16_t, 4) MM_AD(bf16_t, 8) }
+  } else {
+    switch (lpk) { MM_AD(float, 4) MM_AD(float, 8) MM_AD(float, 16) }
   }
-  const size_t lds = (size_t)(dh + max_len) * sizeof(float);
-  if (dt == BF16)
-    attn_decode_kernel<bf16_t><<<grid, 64, lds, st>>>((const bf16_t*)q, q_stride, (const bf16_t*)k, (const bf16_t*)v,
-                                                      ldkv, cu, seq_rows, len_uniform, (bf16_t*)o, o_stride, dh, scale);
-  else
-    attn_decode_kernel<float><<<grid, 64, lds, st>>>((const float*)q, q_stride, (const float*)k, (const float*)v,
-                                                     ldkv, cu, seq_rows, len_uniform, (float*)o, o_stride, dh, scale);
+#undef MM_AD
 }
 
 void launch_greedy_pick(hipStream_t st, Dtype dt, const void* z, int B, int V, int t, int max_new, int eos,

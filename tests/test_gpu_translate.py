@@ -97,6 +97,17 @@ def test_translation_without_adapters_and_unsplit_stack():
     ctx.close()
 
 
+def test_translation_with_head_size_32():
+    """d = 64, two heads of 32 (the small-model cases use 16 and 64)."""
+    setup = tiny_setup(d=64, H=2, F_=64, V=56, adapter_dim=16, dtype="f32", max_len=24)
+    ctx, orc = sharpened_pair(setup, 6.0, 1.0)
+    batch = tiny_batch(setup, lengths=LENGTHS)
+    say("[case] f32, head size 32")
+    ids, n, ref_ids, ref_n = compare(ctx, orc, 0, batch.src_ids, batch.lengths[:, 0].copy(), 10, "f32", "dh=32")
+    assert np.array_equal(ids, ref_ids) and np.array_equal(n, ref_n)
+    ctx.close()
+
+
 def test_translation_edge_shapes():
     setup = tiny_setup(d=32, H=2, F_=64, V=56, adapter_dim=16, dtype="f32", max_len=24)
     ctx, orc = sharpened_pair(setup, 6.0, 1.0)
