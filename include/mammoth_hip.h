@@ -134,7 +134,10 @@ mm_status mm_train_step(mm_ctx* ctx, int32_t task, const int32_t* src_ids, const
  *   out_ids [B, max_new] int32 (host, caller-owned): produced ids, EOS included, then pad (0).
  *   out_lengths [B] int32 (host): number of ids produced per sentence.
  * Synchronous: returns when the outputs are written.  A training step still in flight is
- * waited for first.  Errors as for mm_train_step; on error the outputs are unspecified. */
+ * waited for first.  Errors as for mm_train_step; on error the outputs are unspecified.
+ * The call reuses the training step's workspace and id tables: mm_debug_dump afterwards
+ * describes this call's batch (with a two-token target BOS EOS per sentence), not the last
+ * training step's. */
 mm_status mm_translate_greedy(mm_ctx* ctx, int32_t task, const int32_t* src_ids, const int32_t* src_lengths,
                               int32_t B, int32_t S_max, int32_t max_new, int32_t ids_mem,
                               int32_t* out_ids, int32_t* out_lengths);
