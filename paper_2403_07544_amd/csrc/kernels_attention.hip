@@ -308,9 +308,6 @@ __device__ __forceinline__ bf16x8_t frag_tr(const unsigned char* lds, int rbase,
   }
   return u.f;
 }
-__device__ __forceinline__ bf16x8_t frag_global(const bf16_t* g) {
-  return *reinterpret_cast<const bf16x8_t*>(g);
-}
 __device__ __forceinline__ bf16x8_t frag_from_regs(const float* v) {
   union { uint32_t u[4]; bf16x8_t f; } c;
   c.u[0] = pack_bf16(v[0], v[1]); c.u[1] = pack_bf16(v[2], v[3]);
@@ -326,36 +323,37 @@ __global__ void __launch_bounds__(512, 1) attn_fwd_mfma_kernel(const AttnParams 
   const int k0 = p.cu_k[b], lk = p.cu_k[b + 1] - k0;
   const int nkt = (lk + 31) >> 5, Lp = nkt * 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lcol = lane & 31, hh = lane >> 5;
+  const int nqt = (lq + 31) >> 5, Lqp = nqt * 32;
   unsigned char* Kn = smem_raw;
   unsigned char* Vn = Kn + Lp * 128;
+  unsigned char* Qn = Vn + Lp * 128;
   const bf16_t* qg = (const bf16_t*)p.q + h * 64;
   const float scale = 0.125f;  // 1 / sqrt(64)
-  const int nqt = (lq + 31) >> 5;
   const int nwave = blockDim.x >> 6;
-  // this wavefront's first Q fragments travel while the K and V tiles are fetched
-  bf16x8_t qf[4];
-  auto load_q = [&](int qt) {
-    const int64_t grow = q0 + min(qt * 32 + lcol, lq - 1);
-#pragma unroll
-    for (int s = 0; s < 4; ++s) qf[s] = frag_global(qg + grow * p.ldq + (2 * s + hh) * 8);
-  };
-  if (wave < nqt) load_q(wave);
-  for (int base = 0; base < Lp * 2; base += blockDim.x) {
+  // K, V and Q tiles of the sentence go to LDS with coalesced loads, all issued before the first store
+  const int n_items = (Lp > Lqp ? Lp : Lqp) * 2;
+  for (int base = 0; base < n_items; base += blockDim.x) {
     const int it = base + tid;
+    uint4 vk[4], vv[4], vq[4];
     if (it < Lp * 2) {
-      uint4 vk[4], vv[4];
       tile_fetch(vk, (const bf16_t*)p.k + h * 64, p.ldk, k0, lk, it);
       tile_fetch(vv, (const bf16_t*)p.v + h * 64, p.ldv, k0, lk, it);
+    }
+    if (it < Lqp * 2) tile_fetch(vq, qg, p.ldq, q0, lq, it);
+    if (it < Lp * 2) {
       tile_store_natural(Kn, vk, it);
       tile_store_natural(Vn, vv, it);
     }
+    if (it < Lqp * 2) tile_store_natural(Qn, vq, it);
   }
   __syncthreads();
   for (int qt = wave; qt < nqt; qt += nwave) {
     const int ql = qt * 32 + lcol;
     const bool valid_q = ql < lq;
     const int64_t grow = q0 + (valid_q ? ql : lq - 1);
-    if (qt != wave) load_q(qt);
+    bf16x8_t qf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) qf[s] = frag_natural(Qn, ql, 2 * s + hh);
     const int kt_end = p.causal ? min(nkt, qt + 1) : nkt;
     f32x16_t sc[NKT];
 #pragma unroll
@@ -444,9 +442,9 @@ __global__ void __launch_bounds__(512, 1) attn_fwd_mfma_kernel(const AttnParams 
   }
 }
 
-inline size_t mfma_fwd_lds(int max_lk) {
-  const int Lp = ((max_lk + 31) / 32) * 32;
-  return (size_t)2 * Lp * 128;
+inline size_t mfma_fwd_lds(int max_lq, int max_lk) {
+  const int Lq = ((max_lq + 31) / 32) * 32, Lk = ((max_lk + 31) / 32) * 32;
+  return (size_t)(2 * Lk + Lq) * 128;   // K, V and Q tiles
 }
 
 // Backward with the same layouts, one workgroup per (sentence, head).  The Q, dO, K and V tiles of
@@ -691,7 +689,7 @@ static bool mfma_ok(Dtype dt, const AttnParams& p) {
 
 void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p, const LaunchEvents& ev) {
   if (mfma_ok(dt, p)) {
-    const size_t lds = mfma_fwd_lds(p.max_lk);
+    const size_t lds = mfma_fwd_lds(p.max_lq, p.max_lk);
     // one wavefront per 32 queries, up to eight: short sentences get small workgroups, so more of them share a CU
     const int threads = 64 * std::min(8, (p.max_lq + 31) / 32);
     if (p.max_lk <= 128) {
