@@ -102,6 +102,23 @@ def bench_translate(args, setup, ctx, batches):
     roofline = {"bound": "hbm", "kernel": "one decoding step (71 launches at set-up 2; no single kernel dominates)",
                 "achieved": step_bytes / step_s / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                 "frac": step_bytes / step_s / PEAK_HBM, "traffic": None, "bytes_per_step": step_bytes}
+    cpu = None
+    if not args.no_cpu_baseline:
+        # the oracle's greedy translation (whole model recomputed per token, fp64 numpy) on a few sentences
+        from oracle.mammoth_oracle import build_from_setup
+        import mm_synth
+        needed = set(ctx.mm_get_route(tasks[0]))
+        orc = build_from_setup(setup, dtype=np.float64, fill_params=mm_synth.fill_params, needed=needed)
+        gen = [j for j in needed if setup.modules[j].kind == "gen"][0]
+        orc.modules[gen].p("bg")[2] = -1e3
+        nb, steps_cpu = min(32, B), min(20, max_new)   # about 10 s
+        t1 = time.perf_counter()
+        _, n_cpu = orc.greedy_decode(tasks[0], src_host[:nb], s_len[:nb], steps_cpu)
+        dt = time.perf_counter() - t1
+        from threadpoolctl import threadpool_info
+        threads = max([q.get("num_threads", 1) for q in threadpool_info()] or [1])
+        cpu = {"value": float(n_cpu.sum()) / dt, "unit": "generated tokens/s", "cores": int(threads), "kind": "oracle",
+               "sample": f"{nb} sentences x {steps_cpu} tokens of the same batch, {dt:.1f} s"}
     print(json.dumps({
         "metric": "greedy translation tokens/s per MI355X (routed inference)", "value": B * max_new * args.steps / elapsed,
         "unit": "generated tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -109,7 +126,7 @@ def bench_translate(args, setup, ctx, batches):
         "higher_is_better": True, "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}]: {setup.title}; {B} sentences, {int(s_len.sum())} source "
                                f"tokens, {max_new} tokens written per sentence"},
-        "roofline": roofline, "kernel_classes": classes}))
+        "roofline": roofline, "cpu_baseline": cpu, "kernel_classes": classes}))
 
 
 def main():
