@@ -3,9 +3,6 @@
 // pick of the next token.  Everything else of a decoding step reuses the training kernels.
 #include <hip/hip_runtime.h>
 
-#include <cstdio>
-#include <cstdlib>
-
 #include "mm_kernels.h"
 
 namespace mm {
@@ -206,7 +203,7 @@ greedy_pick_kernel(const T* __restrict__ z, int V, int t, int max_new, int eos, 
 
 }  // namespace
 
-void launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_stride, const void* k, const void* v,
+bool launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_stride, const void* k, const void* v,
                         int64_t ldkv, const int32_t* cu, int64_t seq_rows, int len_uniform, int max_len,
                         void* o, int64_t o_stride, int B, int H, int dh) {
   const float scale = 1.0f / sqrtf((float)dh);
@@ -215,10 +212,7 @@ void launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_strid
   const int lpk = dh / n;
   const auto al = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   const bool ok = (dh == 16 || dh == 32 || dh == 64) && al(q) && al(k) && al(v) && q_stride % n == 0 && ldkv % n == 0;
-  if (!ok) {   // mm_create admits no other head size and the runtime's buffers are 256-byte aligned
-    fprintf(stderr, "launch_attn_decode: unsupported head size %d or unaligned operands\n", dh);
-    abort();
-  }
+  if (!ok) return false;   // (mm_create admits no other head size and the runtime's buffers are aligned)
   const size_t lds = (size_t)(8 + 4 * dh + max_len) * sizeof(float);
 #define MM_AD(T, L)                                                                                              \
   case L:                                                                                                        \
@@ -231,6 +225,7 @@ void launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_strid
     switch (lpk) { MM_AD(float, 4) MM_AD(float, 8) MM_AD(float, 16) }
   }
 #undef MM_AD
+  return true;
 }
 
 void launch_greedy_pick(hipStream_t st, Dtype dt, const void* z, int B, int V, int t, int max_new, int eos,

@@ -200,7 +200,8 @@ void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int to
 // o[b, h*dh..] = softmax(q_b K_b^T / sqrt(dh)) V_b.  q row b at q + b*q_stride, o likewise.
 // Keys/values: rows of stride ldkv; sentence b owns rows cu[b]..cu[b+1] or, with cu null, rows
 // b*seq_rows .. b*seq_rows + len_uniform.  max_len bounds every sentence's key count.
-void launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_stride, const void* k, const void* v,
+// Head sizes 16, 32, 64 with 16-byte aligned operands; anything else returns false and launches nothing.
+bool launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_stride, const void* k, const void* v,
                         int64_t ldkv, const int32_t* cu, int64_t seq_rows, int len_uniform, int max_len,
                         void* o, int64_t o_stride, int B, int H, int dh);
 // Row-wise arg-max of z [B, V] (lowest index among equal entries) for the sentences with

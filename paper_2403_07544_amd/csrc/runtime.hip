@@ -900,9 +900,9 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
       p.b_split = d; p.b_seg_stride = seg; p.bias = pv.V(3); p.bias_split = d; p.bias_seg_stride = seg;
       run.gemm(p);
       void* o = s.act((size_t)B * d);
-      if (!dry)
-        launch_attn_decode(c->st, c->dt, row_t, seq3, L.cache + (size_t)d * esz, L.cache + (size_t)2 * d * esz, row3,
-                           nullptr, max_new, t + 1, max_new, o, d, B, H, dh);
+      if (!dry && !launch_attn_decode(c->st, c->dt, row_t, seq3, L.cache + (size_t)d * esz, L.cache + (size_t)2 * d * esz,
+                                      row3, nullptr, max_new, t + 1, max_new, o, d, B, H, dh))
+        return fail(c, MM_EINVAL, "decoding attention does not support head size %d", dh);
       y = proj_out(o, d, pv.W(8), pv.V(9), x_full);
       // attention over the encoder output
       a = ln_in(y, pv.V(10), pv.V(11), x_full);
@@ -911,9 +911,9 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
       p.bias = pv.V(13);
       run.gemm(p);
       o = s.act((size_t)B * d);
-      if (!dry)
-        launch_attn_decode(c->st, c->dt, q, d, L.kv_mem, L.kv_mem + (size_t)d * esz, 2 * d, c->cu_s, 0, 0, s.max_s, o,
-                           d, B, H, dh);
+      if (!dry && !launch_attn_decode(c->st, c->dt, q, d, L.kv_mem, L.kv_mem + (size_t)d * esz, 2 * d, c->cu_s, 0, 0,
+                                      s.max_s, o, d, B, H, dh))
+        return fail(c, MM_EINVAL, "decoding attention does not support head size %d", dh);
       y = proj_out(o, d, pv.W(18), pv.V(19), x_full);
       y = ffn_block(pv, 20, y, s.F);
       if (L.has_adapter) y = ffn_block(L.apv, 0, y, c->mods[rt.ad_dec].adapter_dim);
