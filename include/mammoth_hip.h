@@ -147,7 +147,7 @@ mm_status mm_last_loss(mm_ctx* ctx, float* out_loss);
 
 /* Renormalise and update (Algorithm 1 last line, then Adam): for every listed module with
  * n_j > 0: g = bucket / n_j; t_j += 1; Adam step on the fp32 master with bias correction for
- * step t_j; working copy refreshed; bucket zeroed; n_j = 0.  Modules with n_j = 0 are skipped:
+ * step t_j; working copy refreshed; bucket emptied; n_j = 0.  Modules with n_j = 0 are skipped:
  * not one byte of theirs is read or written.  module_ids NULL = every module.  Asynchronous. */
 mm_status mm_apply_update(mm_ctx* ctx, const int32_t* module_ids, int32_t n, float lr);
 
@@ -164,7 +164,14 @@ mm_status mm_get_layout(mm_ctx* ctx, int32_t module, int64_t* offsets, int32_t* 
                         int32_t* roles, int32_t* n_tensors, int64_t* bucket_len);
 mm_status mm_get_params(mm_ctx* ctx, int32_t module, float* dst, int64_t n);
 mm_status mm_set_params(mm_ctx* ctx, int32_t module, const float* src, int64_t n);
+/* The module's bucket: the sum of the gradients of its uses since its last update (Algorithm 1),
+ * all zeros when n_j = 0. */
 mm_status mm_get_grads(mm_ctx* ctx, int32_t module, float* dst, int64_t n);
+/* The bucket's memory as it stands.  Differs from mm_get_grads only when n_j = 0: the update
+ * zeroes the buckets of embedding tables but leaves those of stacks, generators and adapters as
+ * they are, because the next step that uses such a module writes every element of its bucket
+ * (first use overwrites, later uses add).  A module that was never used reads all zeros. */
+mm_status mm_get_bucket_memory(mm_ctx* ctx, int32_t module, float* dst, int64_t n);
 /* Overwrites a bucket and its use count (to test the update in isolation). */
 mm_status mm_set_grads(mm_ctx* ctx, int32_t module, const float* src, int64_t n, int32_t n_uses);
 mm_status mm_get_adam(mm_ctx* ctx, int32_t module, float* m, float* v, int64_t n, int64_t* t_j);

@@ -30,7 +30,7 @@ KERNEL_CLASSES = ("gemm", "attn_fwd", "attn_bwd", "layernorm_fwd", "layernorm_bw
 
 EXPORTS = ("mm_create", "mm_destroy", "mm_register_module", "mm_route_task", "mm_train_step", "mm_translate_greedy",
            "mm_last_loss", "mm_apply_update", "mm_num_modules", "mm_get_route", "mm_get_touched",
-           "mm_get_layout", "mm_get_params", "mm_set_params", "mm_get_grads", "mm_set_grads",
+           "mm_get_layout", "mm_get_params", "mm_set_params", "mm_get_grads", "mm_get_bucket_memory", "mm_set_grads",
            "mm_get_adam", "mm_get_working", "mm_debug_dump", "mm_profile", "mm_profile_read",
            "mm_last_error")
 
@@ -84,6 +84,7 @@ def load_library() -> C.CDLL:
         "mm_get_params": [vp, i32, vp, i64],
         "mm_set_params": [vp, i32, vp, i64],
         "mm_get_grads": [vp, i32, vp, i64],
+        "mm_get_bucket_memory": [vp, i32, vp, i64],
         "mm_set_grads": [vp, i32, vp, i64, i32],
         "mm_get_adam": [vp, i32, vp, vp, i64, pi64],
         "mm_get_working": [vp, i32, vp, i64],
@@ -256,6 +257,9 @@ class Context:
 
     def mm_get_grads(self, module: int) -> np.ndarray:
         return self._get(self.lib.mm_get_grads, module)
+
+    def mm_get_bucket_memory(self, module: int) -> np.ndarray:
+        return self._get(self.lib.mm_get_bucket_memory, module)
 
     def mm_get_working(self, module: int) -> np.ndarray:
         return self._get(self.lib.mm_get_working, module)

@@ -655,7 +655,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
           for (int g = 0; g < NKG; ++g) t += red[g * BN + tid];
           int64_t idx = n;
           if (p.c_split) { const int sg = n / p.c_split; idx = (int64_t)sg * p.c_seg_stride + (n - sg * p.c_split); }
-          p.colsum_dst[idx] += t;
+          p.colsum_dst[idx] = p.colsum_overwrite ? t : p.colsum_dst[idx] + t;
         }
       }
     }

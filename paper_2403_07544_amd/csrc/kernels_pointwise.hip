@@ -462,7 +462,7 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(
 __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partial, int n_partial,
                                                               int64_t pstride, int N, float* __restrict__ dst,
                                                               int split, int64_t seg_stride, float* __restrict__ dst2,
-                                                              int n_first) {
+                                                              int n_first, int overwrite) {
   __shared__ float red[4][64];
   const int c = threadIdx.x & 63, r = threadIdx.x >> 6;
   const int n = blockIdx.x * 64 + c;
@@ -484,7 +484,7 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
     float* o;
     if (dst2 && n >= n_first) o = dst2 + (n - n_first);
     else o = split ? dst + (int64_t)(n / split) * seg_stride + (n % split) : dst + n;
-    *o += s;
+    *o = overwrite ? s : *o + s;
   }
 }
 
@@ -520,7 +520,7 @@ __global__ void __launch_bounds__(256) ln_reduce_grouped_kernel(const LnReduceJo
   if (r == 0 && n < N) {
     const float s = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
     float* o = n < jb.d ? jb.dgamma + n : jb.dbeta + (n - jb.d);
-    *o += s;
+    *o = jb.overwrite ? s : *o + s;
   }
 }
 
@@ -758,7 +758,7 @@ __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict
       nt_st4(sg.theta + i, th[it]);
       nt_st4(sg.m + i, m[it]);
       nt_st4(sg.v + i, v[it]);
-      nt_st4(sg.g + i, make_float4(0.f, 0.f, 0.f, 0.f));
+      if (!sg.keep_g) nt_st4(sg.g + i, make_float4(0.f, 0.f, 0.f, 0.f));
       if (sg.w16) Io<bf16_t>::st4(sg.w16 + i, th[it]);
     }
   }
@@ -877,7 +877,7 @@ int colsum_partial_rows(int M) {
 }
 
 void launch_colsum(hipStream_t st, Dtype dt, const void* Y, int y_f32, int64_t ldy, int M, int N,
-                   float* partial, float* dst, int split, int64_t seg_stride) {
+                   float* partial, float* dst, int split, int64_t seg_stride, int overwrite) {
   const int chunks = colsum_partial_rows(M);
   const int rows_per_chunk = (M + chunks - 1) / chunks;
   dim3 grid((N + 255) / 256, chunks);
@@ -885,7 +885,7 @@ void launch_colsum(hipStream_t st, Dtype dt, const void* Y, int y_f32, int64_t l
     colsum_kernel<float><<<grid, 256, 0, st>>>((const float*)Y, ldy, M, N, rows_per_chunk, partial);
   else
     colsum_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)Y, ldy, M, N, rows_per_chunk, partial);
-  reduce_partials_kernel<<<(N + 63) / 64, 256, 0, st>>>(partial, chunks, N, N, dst, split, seg_stride, nullptr, 0);
+  reduce_partials_kernel<<<(N + 63) / 64, 256, 0, st>>>(partial, chunks, N, N, dst, split, seg_stride, nullptr, 0, overwrite);
 }
 
 void launch_ce(hipStream_t st, Dtype dt, void* z, const int32_t* label, float* loss_rows, int U, int V,

@@ -80,6 +80,7 @@ struct GemmParams {
   int64_t c_part_stride;
   float* colsum_dst;      // grouped weight-gradient launch only: [N] (segmented like C) += column
                           // sums of B over K, i.e. the bias gradient belonging to this product
+  int colsum_overwrite;   // the sums replace colsum_dst instead of being added (first use of a bucket)
 };
 void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p, const LaunchEvents& ev = LaunchEvents());
 // true if a product with k_splits > 1 set can run that way (otherwise launch it with k_splits = 0)
@@ -143,14 +144,14 @@ void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float
                           int64_t dy_part_stride = 0);
 struct LnReduceJob {
   const float* partial; float* dgamma; float* dbeta;
-  int32_t n_partial, d, first_block, pad;   // first_block: running sum of ceil(2d/64)
+  int32_t n_partial, d, first_block, overwrite;   // first_block: running sum of ceil(2d/64); overwrite: = instead of +=
 };
 void launch_ln_reduce_grouped(hipStream_t st, const LnReduceJob* jobs_dev, int n_jobs, int total_blocks);
 
-// dst[n] += sum_m Y[m,n]; Y is fp32 (y_f32=1) or working dtype; dst segmented like GemmParams C.
+// dst[n] += sum_m Y[m,n] (= with overwrite); Y is fp32 (y_f32=1) or working dtype; dst segmented like GemmParams C.
 int colsum_partial_rows(int M);
 void launch_colsum(hipStream_t st, Dtype dt, const void* Y, int y_f32, int64_t ldy, int M, int N,
-                   float* partial, float* dst, int split, int64_t seg_stride);
+                   float* partial, float* dst, int split, int64_t seg_stride, int overwrite = 0);
 
 // ---------------------------------------------------------------------------------------------
 // attention, one (sentence, head) per workgroup; q/k/v/o rows are packed tokens
@@ -188,7 +189,7 @@ struct AdamSegment {
   int64_t len;                                               // multiple of 64
   float n_uses, bc1, bc2;                                    // n_j, 1-beta1^t, 1-beta2^t
   int32_t first_chunk;                                       // running chunk index of this segment
-  int32_t pad;
+  int32_t keep_g;                                            // leave g as it is (its next use overwrites it)
 };
 static const int ADAM_CHUNK = 4096;
 void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int total_chunks,

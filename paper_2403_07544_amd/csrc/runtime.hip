@@ -211,7 +211,7 @@ struct Run {
   // The gain/shift gradient sums of all LayerNorms of the step are reduced in one launch at the end.
   std::vector<LnReduceJob>* ln_jobs = nullptr;
   void ln_bwd(const float* dy, const float* x, const float* mean, const float* rstd, const float* g,
-              const float* dres, float* dx, void* dxT, float* gg, float* gb, int rows, int dy_parts = 1,
+              const float* dres, float* dx, void* dxT, float* gg, float* gb, int rows, bool fresh, int dy_parts = 1,
               int64_t dy_part_stride = 0) {
     const int d = c->cfg.d_model;
     const int n_partial = ln_bwd_partial_rows(rows);
@@ -222,14 +222,14 @@ struct Run {
                          dy_parts, dy_part_stride);
     LnReduceJob jb;
     jb.partial = partial; jb.dgamma = gg; jb.dbeta = gb; jb.n_partial = n_partial; jb.d = d;
-    jb.first_block = 0; jb.pad = 0;
+    jb.first_block = 0; jb.overwrite = fresh;
     ln_jobs->push_back(jb);
   }
   void colsum(const void* Y, int y_f32, int64_t ldy, int M, int N, float* partial, float* dst, int split,
-              int64_t seg) {
+              int64_t seg, bool overwrite) {
     if (dry) return;
     begin(MM_K_COLSUM, (double)M * N * (y_f32 ? 4 : esz()));
-    launch_colsum(c->st, c->dt, Y, y_f32, ldy, M, N, partial, dst, split, seg);
+    launch_colsum(c->st, c->dt, Y, y_f32, ldy, M, N, partial, dst, split, seg, overwrite);
     end();
   }
   void attn_fwd(const AttnParams& p, double flops) {
@@ -242,6 +242,12 @@ struct Run {
   }
 };
 
+// Buckets of modules whose every element receives a gradient in every step that uses the module
+// (stacks, generator, adapters) are not zeroed by the update: the first step after an update
+// overwrites them and later steps add.  Embedding tables get gradient rows for the batch's tokens
+// only, so the update zeroes their buckets and every step adds.
+inline bool bucket_overwrites(int kind) { return kind != MM_SRC_EMB && kind != MM_TGT_EMB; }
+
 // parameter views of one layer ------------------------------------------------------------------
 struct PV {
   mm_ctx* c; Module* m; int base;
@@ -251,6 +257,9 @@ struct PV {
   }
   const float* V(int i) const { return m->theta + off(i); }  // fp32 vector (bias, gamma, beta)
   float* G(int i) const { return m->g + off(i); }
+  // First use of the module's bucket since its last update: gradients are written, not added
+  // (see bucket_overwrites).
+  bool fresh() const { return bucket_overwrites(m->kind) && m->touched == 0; }
 };
 
 struct LnSave { float* mean; float* rstd; };
@@ -372,16 +381,19 @@ struct Step {
   std::vector<GemmParams> deferred;
   // p: the weight-gradient product dW += X^T dY.  gb: the bias gradient that goes with it
   // (db += column sums of dY, segmented like dW); Yf32: an fp32 version of dY if one exists.
-  void wgrad(GemmParams p, float* gb, const float* Yf32) {
+  // fresh: the bucket holds nothing yet (PV::fresh): both results replace what is there.
+  void wgrad(GemmParams p, float* gb, const float* Yf32, bool fresh) {
     if (dry()) return;
+    if (fresh) p.residual = nullptr;
     if ((int)deferred.size() < MAX_GROUPED && gemm_groupable(c->dt, p)) {
       p.colsum_dst = gb;
+      p.colsum_overwrite = fresh;
       deferred.push_back(p);
       return;
     }
     run.gemm(p);
-    if (Yf32) run.colsum(Yf32, 1, p.ldb, p.K, p.N, partial, gb, p.c_split, p.c_seg_stride);
-    else run.colsum(p.B, 0, p.ldb, p.K, p.N, partial, gb, p.c_split, p.c_seg_stride);
+    if (Yf32) run.colsum(Yf32, 1, p.ldb, p.K, p.N, partial, gb, p.c_split, p.c_seg_stride, fresh);
+    else run.colsum(p.B, 0, p.ldb, p.K, p.N, partial, gb, p.c_split, p.c_seg_stride, fresh);
   }
   // End of the step: the deferred weight-gradient products as one grouped launch, then the
   // LayerNorm gain/shift partial sums as one launch.  Their tables go up in a single copy.
@@ -435,12 +447,12 @@ struct Step {
     GemmParams p = gp_dgrad(g.dxT, d, pv.W(t0 + 4), hidden, d, dh, R);
     p.relu_mask = s.h; p.ldm = hidden;
     run.gemm(p);
-    wgrad(gp_wgrad(s.h, hidden, g.dxT, d, pv.G(t0 + 4), hidden, d, R), pv.G(t0 + 5), g.dx);
+    wgrad(gp_wgrad(s.h, hidden, g.dxT, d, pv.G(t0 + 4), hidden, d, R), pv.G(t0 + 5), g.dx, pv.fresh());
     p = gp_dgrad(dh, hidden, pv.W(t0 + 2), d, hidden, da, R);
     p.out_f32 = 1;
     run.gemm(p);
-    wgrad(gp_wgrad(s.a, d, dh, hidden, pv.G(t0 + 2), d, hidden, R), pv.G(t0 + 3), nullptr);
-    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, pv.G(t0), pv.G(t0 + 1), R);
+    wgrad(gp_wgrad(s.a, d, dh, hidden, pv.G(t0 + 2), d, hidden, R), pv.G(t0 + 3), nullptr, pv.fresh());
+    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, pv.G(t0), pv.G(t0 + 1), R, pv.fresh());
     if (c->dt != BF16) out.dxT = out.dx;
     return out;
   }
@@ -451,7 +463,7 @@ struct Step {
     float* da = f32((size_t)R * d);
     Grad out{f32((size_t)R * d), c->dt == BF16 ? act((size_t)R * d) : nullptr};
     run.gemm(gp_dgrad(g.dxT, d, pv.W(t0 + 8), d, d, d_o, R));
-    wgrad(gp_wgrad(s.o, d, g.dxT, d, pv.G(t0 + 8), d, d, R), pv.G(t0 + 9), g.dx);
+    wgrad(gp_wgrad(s.o, d, g.dxT, d, pv.G(t0 + 8), d, d, R), pv.G(t0 + 9), g.dx, pv.fresh());
     const char* qkv = (const char*)s.qkv;
     char* dq = (char*)dqkv;
     AttnParams a = ap(qkv, 3 * d, dry() ? nullptr : qkv + (size_t)d * esz, dry() ? nullptr : qkv + (size_t)2 * d * esz,
@@ -466,8 +478,8 @@ struct Step {
     run.gemm(p);
     p = gp_wgrad(s.a, d, dqkv, 3 * d, pv.G(t0 + 2), d, 3 * d, R);
     p.ldc = d; p.ldr = d; p.c_split = d; p.c_seg_stride = seg;
-    wgrad(p, pv.G(t0 + 3), nullptr);
-    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, pv.G(t0), pv.G(t0 + 1), R);
+    wgrad(p, pv.G(t0 + 3), nullptr, pv.fresh());
+    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, pv.G(t0), pv.G(t0 + 1), R, pv.fresh());
     if (c->dt != BF16) out.dxT = out.dx;
     return out;
   }
@@ -479,7 +491,7 @@ struct Step {
     float* da = f32((size_t)U * d);
     Grad out{f32((size_t)U * d), c->dt == BF16 ? act((size_t)U * d) : nullptr};
     run.gemm(gp_dgrad(g.dxT, d, pv.W(t0 + 8), d, d, d_o, U));
-    wgrad(gp_wgrad(s.o, d, g.dxT, d, pv.G(t0 + 8), d, d, U), pv.G(t0 + 9), g.dx);
+    wgrad(gp_wgrad(s.o, d, g.dxT, d, pv.G(t0 + 8), d, d, U), pv.G(t0 + 9), g.dx, pv.fresh());
     const char* kv = (const char*)s.kv;
     char* dkvc = (char*)dkv;
     AttnParams a = ap(s.q, d, kv, dry() ? nullptr : kv + (size_t)d * esz, 2 * d, s.o, s.lse, true, false, 0);
@@ -490,7 +502,7 @@ struct Step {
     GemmParams p = gp_dgrad(dq, d, pv.W(t0 + 2), d, d, da, U);
     p.out_f32 = 1;
     run.gemm(p);
-    wgrad(gp_wgrad(s.a, d, dq, d, pv.G(t0 + 2), d, d, U), pv.G(t0 + 3), nullptr);
+    wgrad(gp_wgrad(s.a, d, dq, d, pv.G(t0 + 2), d, d, U), pv.G(t0 + 3), nullptr, pv.fresh());
     // memory side: d mem (+)= dkv [Wk|Wv]^T
     const int64_t seg = pv.off(t0 + 6) - pv.off(t0 + 4);
     p = gp_dgrad(dkv, 2 * d, pv.W(t0 + 4), d, 2 * d, dmem, S);
@@ -499,14 +511,15 @@ struct Step {
     run.gemm(p);
     p = gp_wgrad(mem, d, dkv, 2 * d, pv.G(t0 + 4), d, 2 * d, S);
     p.ldc = d; p.ldr = d; p.c_split = d; p.c_seg_stride = seg;
-    wgrad(p, pv.G(t0 + 5), nullptr);
-    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, pv.G(t0), pv.G(t0 + 1), U);
+    wgrad(p, pv.G(t0 + 5), nullptr, pv.fresh());
+    run.ln_bwd(da, s.x_in, s.ln.mean, s.ln.rstd, pv.V(t0), g.dx, out.dx, out.dxT, pv.G(t0), pv.G(t0 + 1), U, pv.fresh());
     if (c->dt != BF16) out.dxT = out.dx;
     return out;
   }
 };
 
-double work_bytes_adam(const mm_ctx* c, int64_t n) { return (double)n * (c->dt == BF16 ? 34.0 : 32.0); }
+// per parameter: g, theta, m, v read (16 B); theta, m, v written (12 B); bf16 copy (2 B); g zeroed (4 B) unless kept
+double work_bytes_adam(const mm_ctx* c, int64_t n, bool keep_g) { return (double)n * ((c->dt == BF16 ? 30.0 : 28.0) + (keep_g ? 0.0 : 4.0)); }
 
 mm_status collect_profile(mm_ctx* c) {
   if (c->prof_recs.empty()) return MM_OK;
@@ -711,11 +724,11 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
     p.c_part_stride = (int64_t)U * d;
     if (dh_parts < 2 || !gemm_can_split_k(c->dt, p)) { p.k_splits = 0; dh_parts = 1; }
     run.gemm(p);
-    s.wgrad(s.gp_wgrad(h, d, z, V, pv_gen.G(0), d, V, U), pv_gen.G(1), nullptr);
+    s.wgrad(s.gp_wgrad(h, d, z, V, pv_gen.G(0), d, V, U), pv_gen.G(1), nullptr, pv_gen.fresh());
   }
   Step::Grad g{s.f32((size_t)U * d), c->dt == BF16 ? s.act((size_t)U * d) : nullptr};
   run.ln_bwd(dh, y_dec_top, ln_decf.mean, ln_decf.rstd, pv_decf.V(0), nullptr, g.dx, g.dxT,
-             pv_decf.G(0), pv_decf.G(1), U, dh_parts, (int64_t)U * d);
+             pv_decf.G(0), pv_decf.G(1), U, pv_decf.fresh(), dh_parts, (int64_t)U * d);
   if (c->dt != BF16) g.dxT = g.dx;
   float* dmem = s.f32((size_t)S * d);
   bool first = true;
@@ -738,7 +751,7 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
   // ---------------- backward: encoder ----------------
   Step::Grad ge{s.f32((size_t)S * d), c->dt == BF16 ? s.act((size_t)S * d) : nullptr};
   run.ln_bwd(dmem, x_enc_top, ln_encf.mean, ln_encf.rstd, pv_encf.V(0), nullptr, ge.dx, ge.dxT,
-             pv_encf.G(0), pv_encf.G(1), S);
+             pv_encf.G(0), pv_encf.G(1), S, pv_encf.fresh());
   if (c->dt != BF16) ge.dxT = ge.dx;
   for (int i = (int)enc_saves.size() - 1; i >= 0; --i) {
     LayerSave& ls = enc_saves[i];
@@ -1363,6 +1376,7 @@ mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float
   HIP_TRY(c, hipEventSynchronize(c->ev_seg));  // previous upload of the table has left the pinned buffer
   int chunks = 0;
   int64_t total = 0;
+  double work = 0;
   for (size_t i = 0; i < use.size(); ++i) {
     Module& m = c->mods[use[i]];
     m.t += 1;
@@ -1371,9 +1385,10 @@ mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float
     sg.n_uses = (float)m.touched;
     sg.bc1 = (float)(1.0 - std::pow((double)c->cfg.adam_beta1, (double)m.t));
     sg.bc2 = (float)(1.0 - std::pow((double)c->cfg.adam_beta2, (double)m.t));
-    sg.first_chunk = chunks; sg.pad = 0;
+    sg.first_chunk = chunks; sg.keep_g = bucket_overwrites(m.kind);
     chunks += (int)((m.P + ADAM_CHUNK - 1) / ADAM_CHUNK);
     total += m.P;
+    work += work_bytes_adam(c, m.P, sg.keep_g != 0);
     m.touched = 0;
   }
   c->pending_counted = false;  // the step's uses have been consumed
@@ -1382,7 +1397,7 @@ mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float
   Run run{c, false};
   run.mark();
   launch_adam(c->st, c->seg_dev, (int)use.size(), chunks, lr, c->cfg.adam_beta1, c->cfg.adam_beta2, c->cfg.adam_eps,
-              run.begin_timed(MM_K_ADAM, work_bytes_adam(c, total)));
+              run.begin_timed(MM_K_ADAM, work));
   HIP_TRY(c, hipGetLastError());
   return MM_OK;
 }
@@ -1448,6 +1463,18 @@ mm_status mm_get_params(mm_ctx* c, int32_t module, float* dst, int64_t n) {
 }
 
 mm_status mm_get_grads(mm_ctx* c, int32_t module, float* dst, int64_t n) {
+  mm_status s = check_module(c, module, n);
+  if (s != MM_OK) return s;
+  if (!dst) return fail(c, MM_EINVAL, "null destination");
+  resolve_pending(c);
+  if (c->mods[module].touched == 0) {   // an unused bucket is empty, whatever its memory still holds
+    memset(dst, 0, (size_t)n * sizeof(float));
+    return MM_OK;
+  }
+  return copy_out(c, c->mods[module].g, dst, n);
+}
+
+mm_status mm_get_bucket_memory(mm_ctx* c, int32_t module, float* dst, int64_t n) {
   mm_status s = check_module(c, module, n);
   if (s != MM_OK) return s;
   if (!dst) return fail(c, MM_EINVAL, "null destination");

@@ -92,7 +92,12 @@ def check_touched(ctx, orc):
     assert ctx.mm_get_touched().tolist() == [m.touched for m in orc.modules]
 
 
-def check_untouched_zero(ctx, orc, used):
+def check_untouched_zero(ctx, orc, used, never_used=None):
+    """Modules off the route have an empty bucket; `never_used` (default: all of them, right for a
+    context whose modules were not used and updated before) must not have had a byte of their
+    bucket's memory written either."""
     for j in range(len(orc.modules)):
         if j not in used:
             assert not ctx.mm_get_grads(j).any(), f"module {j} is not on the route but has a gradient"
+            if never_used is None or j in never_used:
+                assert not ctx.mm_get_bucket_memory(j).any(), f"module {j} was never used but its bucket was written"

@@ -217,3 +217,60 @@ def test_accumulate_two_tasks_then_update():
         else:
             assert np.array_equal(after, before[j])
     assert ctx.mm_get_touched().sum() == 0
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_steps_and_updates_interleaved(dtype):
+    """Buckets over several steps: first use after an update, a second use that must add, an update
+    of some modules only (the others keep bucket and count and go on adding), tasks that share a
+    module.  After every step every bucket on the GPU must match the oracle's (Algorithm 1: sum
+    of the gradients of the uses since the last update); a bucket that kept anything from before
+    its last update would show up here."""
+    setup = _gpu_tiny(dtype, n_lang=3)
+    ctx, orc = make_pair(setup)
+    names = [n for n, _ in setup.tasks]
+    batches = [tiny_batch(setup, lengths=RAGGED, seed=s) for s in (3, 4, 5)]
+    tol = F32_TOL if dtype == "f32" else bf16_tol(min(batches[0].n_src_tokens, batches[0].n_tgt_tokens))
+    lr = 1e-3
+    ever_used = set()
+
+    def sync_oracle(ids):
+        for j in ids:                                   # both sides go on from the GPU's state
+            orc.modules[j].theta[:] = ctx.mm_get_params(j)
+            m, v, _ = ctx.mm_get_adam(j)
+            orc.modules[j].m[:] = m
+            orc.modules[j].v[:] = v
+
+    def step(task_name, k):
+        t, b = names.index(task_name), batches[k % len(batches)]
+        loss = ctx.mm_train_step(t, b.src_ids, b.tgt_ids, b.lengths)
+        ref = orc.train_step(t, b.src_ids, b.tgt_ids, b.lengths)
+        assert abs(loss - ref) <= (1e-4 if dtype == "f32" else 1e-2) * abs(ref)
+        check_touched(ctx, orc)
+        used = [j for j, m in enumerate(orc.modules) if m.touched]
+        worst = check_grads(ctx, orc, used, label=f"{dtype} {task_name} #{k}", **tol)
+        ever_used.update(used)
+        check_untouched_zero(ctx, orc, set(used), never_used=set(range(len(orc.modules))) - ever_used)
+        say(f"  step {k} task {task_name}: loss {loss:.5f}, {len(used)} buckets in use, worst {worst}")
+
+    def update(ids):
+        used = [j for j, m in enumerate(orc.modules) if m.touched and (ids is None or j in ids)]
+        ctx.mm_apply_update(ids, lr)
+        orc.apply_update(ids, lr)
+        check_touched(ctx, orc)
+        sync_oracle(used)
+        for j in used:
+            assert not ctx.mm_get_grads(j).any()
+
+    say(f"[case] interleaved steps and updates, {dtype}")
+    step("0-1", 0); update(None)
+    step("0-1", 1)                                   # first use after an update
+    step("2-1", 2)                                   # shares the second encoder module, decoder 1, generator 1
+    some = orc.routes[names.index("0-1")][:4]        # source side of 0-1 and the target embedding
+    update(some)
+    step("0-1", 3)                                   # updated modules start again, the others add a third use
+    step("1-0", 4)
+    update(None)
+    step("2-1", 5); step("2-1", 6); update(None)
+    step("1-2", 7)
+    ctx.close()
