@@ -150,3 +150,31 @@ def test_temperature_task_sampling():
     assert np.abs(freq - mm_synth.task_probabilities(len(st.tasks), 1.0)).max() < 0.01
     assert np.array_equal(d, mm_synth.sample_directions(st, 20000, temperature=1.0))     # seeded
     assert np.array_equal(mm_synth.sample_directions(st, 50), mm_synth.sample_directions(st, 50))
+
+
+def test_paper_shape_setups_carry_section4_numbers():
+    """Set-ups 6-8 against the figures section 4 of the paper prints (tests/golden)."""
+    gold = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "paper_section4_shapes.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            gold[k.strip()] = int(v)
+    for index, scheme in ((6, 1), (7, 2), (8, 3)):
+        st = mm_synth.build_setup(index)
+        sh = st.shape
+        assert (sh.vocab, sh.d_model, sh.n_heads, sh.d_ff, sh.max_len, sh.batch_tokens) == tuple(
+            gold[k] for k in ("vocab", "d_model", "n_heads", "d_ff", "max_len", "batch_tokens"))
+        for name, ids in st.tasks:
+            enc = [st.modules[j] for j in ids if st.modules[j].kind == "enc"]
+            dec = [st.modules[j] for j in ids if st.modules[j].kind == "dec"]
+            assert sum(m.n_layers for m in enc) == gold[f"scheme{scheme}_enc_layers"], name
+            assert sum(m.n_layers for m in dec) == gold[f"scheme{scheme}_dec_layers"], name
+        names = {m.name for m in st.modules if m.kind == "enc"}
+        if scheme == 1:      # one encoder per language, none shared
+            assert "full" not in names and len(names) == 4
+        if scheme == 2:      # a language-specific first half, a second half shared by all
+            shared = [m for m in st.modules if m.kind == "enc" and m.name == "full"]
+            assert len(shared) == 1 and shared[0].n_layers == gold["scheme2_enc_shared"] and shared[0].position == 1
+        if scheme == 3:      # one encoder for all languages
+            assert names == {"full"}
