@@ -364,11 +364,12 @@ __global__ void __launch_bounds__(256) layernorm_fwd_kernel(const float* __restr
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
 }
 
-// Each wavefront walks rows blockIdx*4+wave, +gridDim*4, ...; column sums for gamma/beta stay in
+// Each wavefront walks rows blockIdx*LNB_WAVES+wave, +gridDim*LNB_WAVES, ...; column sums for gamma/beta stay in
 // registers and leave as one partial row per workgroup: partial[block][0][d] = dgamma part,
 // partial[block][1][d] = dbeta part.
+constexpr int LNB_WAVES = 8;   // wavefronts (rows in flight) per workgroup of the backward kernel
 template <typename T, int NV>
-__global__ void __launch_bounds__(256) layernorm_bwd_kernel(
+__global__ void __launch_bounds__(64 * LNB_WAVES) layernorm_bwd_kernel(
     const float* __restrict__ dy, const float* __restrict__ x, const float* __restrict__ mean,
     const float* __restrict__ rstd, const float* __restrict__ gamma, const float* __restrict__ dres,
     float* __restrict__ dx_out, T* __restrict__ dxT_out, float* __restrict__ partial, int rows, int d, int dy_parts,
@@ -383,7 +384,7 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(
     ab[k] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
   const float inv_d = 1.0f / (float)d;
-  for (int row = blockIdx.x * 4 + wave; row < rows; row += gridDim.x * 4) {
+  for (int row = blockIdx.x * LNB_WAVES + wave; row < rows; row += gridDim.x * LNB_WAVES) {
     const float mu = mean[row], rs = rstd[row];
     float4 xh[NV], dh[NV];
     float s1 = 0.f, s2 = 0.f;
@@ -425,8 +426,8 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(
       }
     }
   }
-  // workgroup reduction of the 4 waves' column sums, fixed order
-  __shared__ float red[3][2][NV * 256];
+  // workgroup reduction of the waves' column sums, fixed order
+  __shared__ float red[LNB_WAVES - 1][2][NV * 256];
   if (wave > 0) {
 #pragma unroll
     for (int k = 0; k < NV; ++k) {
@@ -443,7 +444,7 @@ __global__ void __launch_bounds__(256) layernorm_bwd_kernel(
       const int c = (lane << 2) + k * 256;
       if (c < d) {
         float4 sg = ag[k], sb = ab[k];
-        for (int w = 0; w < 3; ++w) {
+        for (int w = 0; w < LNB_WAVES - 1; ++w) {
           const float* r0 = &red[w][0][k * 256 + (lane << 2)];
           const float* r1 = &red[w][1][k * 256 + (lane << 2)];
           sg.x += r0[0]; sg.y += r0[1]; sg.z += r0[2]; sg.w += r0[3];
@@ -827,12 +828,12 @@ void launch_embed_grad(hipStream_t st, const uint32_t* keys, const float* dx, fl
 #undef MM_EG
 }
 
-#define MM_LN_DISPATCH(KERNEL, T, ...)                                        \
+#define MM_LN_DISPATCH(KERNEL, T, THREADS, ...)                               \
   switch (nv_for(d)) {                                                        \
-    case 1: hipExtLaunchKernelGGL((KERNEL<T, 1>), dim3(grid), dim3(256), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break;  \
-    case 2: hipExtLaunchKernelGGL((KERNEL<T, 2>), dim3(grid), dim3(256), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break;  \
-    case 4: hipExtLaunchKernelGGL((KERNEL<T, 4>), dim3(grid), dim3(256), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break;  \
-    default: hipExtLaunchKernelGGL((KERNEL<T, 8>), dim3(grid), dim3(256), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break; \
+    case 1: hipExtLaunchKernelGGL((KERNEL<T, 1>), dim3(grid), dim3(THREADS), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break;  \
+    case 2: hipExtLaunchKernelGGL((KERNEL<T, 2>), dim3(grid), dim3(THREADS), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break;  \
+    case 4: hipExtLaunchKernelGGL((KERNEL<T, 4>), dim3(grid), dim3(THREADS), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break;  \
+    default: hipExtLaunchKernelGGL((KERNEL<T, 8>), dim3(grid), dim3(THREADS), 0, st, ev.start, ev.stop, 0, __VA_ARGS__); break; \
   }
 
 void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float* gamma, const float* beta,
@@ -840,16 +841,16 @@ void launch_layernorm_fwd(hipStream_t st, Dtype dt, const float* x, const float*
                           int x_parts, int64_t x_part_stride, float* x_sum) {
   const int grid = (rows + 3) / 4;
   if (dt == BF16) {
-    MM_LN_DISPATCH(layernorm_fwd_kernel, bf16_t, x, gamma, beta, (bf16_t*)y, mean, rstd, rows, d, eps, x_parts,
+    MM_LN_DISPATCH(layernorm_fwd_kernel, bf16_t, 256, x, gamma, beta, (bf16_t*)y, mean, rstd, rows, d, eps, x_parts,
                    x_part_stride, x_sum)
   } else {
-    MM_LN_DISPATCH(layernorm_fwd_kernel, float, x, gamma, beta, (float*)y, mean, rstd, rows, d, eps, x_parts,
+    MM_LN_DISPATCH(layernorm_fwd_kernel, float, 256, x, gamma, beta, (float*)y, mean, rstd, rows, d, eps, x_parts,
                    x_part_stride, x_sum)
   }
 }
 
 int ln_bwd_partial_rows(int rows) {
-  const int want = (rows + 3) / 4;
+  const int want = (rows + LNB_WAVES - 1) / LNB_WAVES;
   return want < 1024 ? want : 1024;
 }
 
@@ -859,10 +860,10 @@ void launch_layernorm_bwd(hipStream_t st, Dtype dt, const float* dy, const float
                           int64_t dy_part_stride) {
   const int grid = ln_bwd_partial_rows(rows);
   if (dt == BF16) {
-    MM_LN_DISPATCH(layernorm_bwd_kernel, bf16_t, dy, x, mean, rstd, gamma, dres, dx_out, (bf16_t*)dxT_out,
+    MM_LN_DISPATCH(layernorm_bwd_kernel, bf16_t, 64 * LNB_WAVES, dy, x, mean, rstd, gamma, dres, dx_out, (bf16_t*)dxT_out,
                    partial, rows, d, dy_parts, dy_part_stride)
   } else {
-    MM_LN_DISPATCH(layernorm_bwd_kernel, float, dy, x, mean, rstd, gamma, dres, dx_out, (float*)nullptr,
+    MM_LN_DISPATCH(layernorm_bwd_kernel, float, 64 * LNB_WAVES, dy, x, mean, rstd, gamma, dres, dx_out, (float*)nullptr,
                    partial, rows, d, dy_parts, dy_part_stride)
   }
 }
