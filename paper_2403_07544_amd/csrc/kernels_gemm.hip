@@ -9,6 +9,7 @@
 
 #include <hip/hip_ext.h>
 
+#include <cstring>
 #include <type_traits>
 
 namespace mm {
@@ -794,6 +795,28 @@ __global__ void __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) gemm_mfma
   gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, PF, true>(prm, tm * BM, tn * BN, lds);
 }
 
+// Several independent products in one launch, parameter blocks passed by value.
+struct GemmMulti {
+  GemmParams p[GEMM_MULTI_MAX];
+  int32_t tile_start[GEMM_MULTI_MAX + 1];
+  int32_t n;
+};
+
+template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF, int DMA>
+__global__ void __launch_bounds__(256) gemm_mfma_multi_kernel(const GemmMulti mp) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int t = remap_xcd(blockIdx.x, gridDim.x);
+  int i = 0;
+  while (i + 1 < mp.n && mp.tile_start[i + 1] <= t) ++i;   // uniform over the workgroup
+  const GemmParams p = mp.p[i];
+  const int L = t - mp.tile_start[i];
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  int tm, tn;
+  if ((int64_t)p.M <= (int64_t)p.N) { tm = L % tiles_m; tn = L / tiles_m; }
+  else { tn = L % tiles_n; tm = L / tiles_n; }
+  gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, PF, false, DMA>(p, tm * BM, tn * BN, lds);
+}
+
 // An operand whose extent reaches 2 GiB cannot use the 32-bit per-lane offsets of the fast path.
 void set_wide(GemmParams& p) {
   const int64_t lim = (int64_t)1 << 31;
@@ -887,6 +910,57 @@ void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const i
   }
   hipExtLaunchKernelGGL((gemm_mfma_grouped_kernel<128, 128, 64, 64, false, false, MM_GROUPED_PF>), dim3(total_tiles), dim3(256), LDS,
                         st, ev.start, ev.stop, 0, table_dev, tile_start_dev, n_problems);
+}
+
+template <int BM, int BN, int WM, int WN, int PF, int DMA>
+void launch_mfma_multi_cfg(hipStream_t st, const GemmMulti& mp, bool kcb, const LaunchEvents& ev) {
+  constexpr int LDS = (DMA ? DMA : 2) * (BM + BN) * 128;
+  const dim3 grid(mp.tile_start[mp.n]);
+#define MM_GO(KB)                                                                                            \
+  do {                                                                                                       \
+    static bool attr_set = false;                                                                            \
+    if (!attr_set) {                                                                                         \
+      hipFuncSetAttribute((const void*)gemm_mfma_multi_kernel<BM, BN, WM, WN, true, KB, PF, DMA>,            \
+                          hipFuncAttributeMaxDynamicSharedMemorySize, LDS);                                  \
+      attr_set = true;                                                                                       \
+    }                                                                                                        \
+    hipExtLaunchKernelGGL((gemm_mfma_multi_kernel<BM, BN, WM, WN, true, KB, PF, DMA>), grid, dim3(256), LDS, st, \
+                          ev.start, ev.stop, 0, mp);                                                         \
+  } while (0)
+  if (kcb) MM_GO(true); else MM_GO(false);
+#undef MM_GO
+}
+
+bool launch_gemm_multi(hipStream_t st, Dtype dt, const GemmParams* ps, int n, const LaunchEvents& ev) {
+  if (dt != BF16 || n < 1 || n > GEMM_MULTI_MAX) return false;
+  GemmMulti mp;
+  std::memset(&mp, 0, sizeof mp);
+  long tiles128 = 0;
+  bool k64 = true;
+  int kmax = 0;
+  for (int i = 0; i < n; ++i) {
+    const GemmParams& p = ps[i];
+    if (p.M <= 0 || p.N <= 0 || p.transA || p.transB != ps[0].transB || p.k_splits > 1 || !mfma_eligible(p)) return false;
+    mp.p[i] = p;
+    set_wide(mp.p[i]);
+    tiles128 += (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
+    k64 = k64 && p.K % BK == 0;
+    kmax = p.K > kmax ? p.K : kmax;
+  }
+  mp.n = n;
+  const bool big = tiles128 >= 192;   // the rule of launch_gemm, applied to the whole set
+  if (!big && !k64) return false;
+  const int bm = big ? 128 : 64, bn = big ? 128 : 64;
+  for (int i = 0; i < n; ++i)
+    mp.tile_start[i + 1] = mp.tile_start[i] + ((ps[i].M + bm - 1) / bm) * ((ps[i].N + bn - 1) / bn);
+  const bool kcb = ps[0].transB != 0;
+  if (big) {
+    if (tiles128 >= 1024 || kmax >= 1024) launch_mfma_multi_cfg<128, 128, 64, 64, 2, 0>(st, mp, kcb, ev);
+    else launch_mfma_multi_cfg<128, 128, 64, 64, 1, 0>(st, mp, kcb, ev);
+  } else {
+    launch_mfma_multi_cfg<64, 64, 32, 32, 1, 3>(st, mp, kcb, ev);
+  }
+  return true;
 }
 
 // Tuning hook: run one named tile configuration of the MFMA kernel.

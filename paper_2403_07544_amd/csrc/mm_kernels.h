@@ -93,6 +93,12 @@ int gemm_grouped_tiles(const GemmParams& p);
 void gemm_prepare_grouped(GemmParams& p);  // call on each table entry before upload
 void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const int32_t* tile_start_dev,
                             int n_problems, int total_tiles, const LaunchEvents& ev = LaunchEvents());
+// Up to GEMM_MULTI_MAX independent products of the same kind (transA = 0, same transB, no split K)
+// in one launch; the parameter blocks travel as kernel arguments, no table upload.  Returns false
+// and launches nothing when the set cannot run that way (fp32 context, mixed layouts, a shape the
+// MFMA kernel does not take): the caller then launches the products one by one.
+constexpr int GEMM_MULTI_MAX = 8;
+bool launch_gemm_multi(hipStream_t st, Dtype dt, const GemmParams* ps, int n, const LaunchEvents& ev = LaunchEvents());
 // Tuning hook: one named tile configuration of the MFMA kernel; false if the shape is not eligible.
 bool launch_gemm_variant(hipStream_t st, const GemmParams& p, int variant);
 // Same contract, always the plain FMA kernel (cross-check of the MFMA path).

@@ -202,6 +202,25 @@ struct Run {
     if (dry) return;
     launch_gemm(c->st, c->dt, p, begin_timed(MM_K_GEMM, 2.0 * p.M * p.N * p.K));
   }
+  // Independent products of one kind: one launch for up to GEMM_MULTI_MAX of them where the
+  // kernel allows it, else one by one.
+  void gemm_set(const std::vector<GemmParams>& ps) {
+    if (dry) return;
+    for (size_t i0 = 0; i0 < ps.size(); i0 += GEMM_MULTI_MAX) {
+      const int n = (int)std::min(ps.size() - i0, (size_t)GEMM_MULTI_MAX);
+      double flops = 0;
+      for (int i = 0; i < n; ++i) flops += 2.0 * ps[i0 + i].M * ps[i0 + i].N * ps[i0 + i].K;
+      if (n > 1 && c->dt == BF16) {
+        LaunchEvents ev = begin_timed(MM_K_GEMM, flops);
+        if (launch_gemm_multi(c->st, c->dt, ps.data() + i0, n, ev)) continue;
+        // not taken: hand the timing slot to the first single launch instead
+        launch_gemm(c->st, c->dt, ps[i0], ev);
+        for (int i = 1; i < n; ++i) gemm(ps[i0 + i]);
+        continue;
+      }
+      for (int i = 0; i < n; ++i) gemm(ps[i0 + i]);
+    }
+  }
   void ln_fwd(const float* x, const float* g, const float* b, void* y, float* mean, float* rstd, int rows) {
     if (dry) return;
     const int d = c->cfg.d_model;
@@ -346,18 +365,22 @@ struct Step {
     run.gemm(p);
     return s;
   }
-  CrossSave cross_fwd(const PV& pv, int t0, float* x_in, const void* mem) {
+  // The key/value projection of the encoder output, [S, 2d], for one decoder layer.
+  GemmParams gp_cross_kv(const PV& pv, int t0, const void* mem, void* kv) {
+    const int64_t seg = pv.off(t0 + 6) - pv.off(t0 + 4);
+    GemmParams p = gp(mem, d, pv.W(t0 + 4), d, kv, 2 * d, S, 2 * d, d);
+    p.b_split = d; p.b_seg_stride = seg; p.bias = pv.V(t0 + 5); p.bias_split = d; p.bias_seg_stride = seg;
+    return p;
+  }
+  // kv: the layer's key/value projection, computed beforehand (all layers' in one launch)
+  CrossSave cross_fwd(const PV& pv, int t0, float* x_in, void* kv_ready) {
     CrossSave s;
     s.x_in = x_in; s.ln.mean = f32(U); s.ln.rstd = f32(U);
-    s.a = act((size_t)U * d); s.q = act((size_t)U * d); s.kv = act((size_t)S * 2 * d);
+    s.a = act((size_t)U * d); s.q = act((size_t)U * d); s.kv = kv_ready;
     s.lse = f32((size_t)H * U); s.o = act((size_t)U * d); s.x_out = f32((size_t)U * d);
     run.ln_fwd(x_in, pv.V(t0), pv.V(t0 + 1), s.a, s.ln.mean, s.ln.rstd, U);
     GemmParams p = gp(s.a, d, pv.W(t0 + 2), d, s.q, d, U, d, d);
     p.bias = pv.V(t0 + 3);
-    run.gemm(p);
-    const int64_t seg = pv.off(t0 + 6) - pv.off(t0 + 4);
-    p = gp(mem, d, pv.W(t0 + 4), d, s.kv, 2 * d, S, 2 * d, d);
-    p.b_split = d; p.b_seg_stride = seg; p.bias = pv.V(t0 + 5); p.bias_split = d; p.bias_seg_stride = seg;
     run.gemm(p);
     const char* kv = (const char*)s.kv;
     AttnParams a = ap(s.q, d, kv, dry() ? nullptr : kv + (size_t)d * esz, 2 * d, s.o, s.lse, true, false, 0);
@@ -484,7 +507,10 @@ struct Step {
     return out;
   }
 
-  Grad cross_bwd(const PV& pv, int t0, const CrossSave& s, Grad g, const void* mem, float* dmem, bool first) {
+  // dmem_part: this layer's own fp32 part of the gradient w.r.t. the encoder output; its product is
+  // appended to dmem_jobs and launched with the other layers' once the decoder's backward is done.
+  Grad cross_bwd(const PV& pv, int t0, const CrossSave& s, Grad g, const void* mem, float* dmem_part,
+                 std::vector<GemmParams>& dmem_jobs) {
     void* d_o = act((size_t)U * d);
     void* dq = act((size_t)U * d);
     void* dkv = act((size_t)S * 2 * d);
@@ -503,12 +529,11 @@ struct Step {
     p.out_f32 = 1;
     run.gemm(p);
     wgrad(gp_wgrad(s.a, d, dq, d, pv.G(t0 + 2), d, d, U), pv.G(t0 + 3), nullptr, pv.fresh());
-    // memory side: d mem (+)= dkv [Wk|Wv]^T
+    // memory side: this layer's part of d mem = dkv [Wk|Wv]^T
     const int64_t seg = pv.off(t0 + 6) - pv.off(t0 + 4);
-    p = gp_dgrad(dkv, 2 * d, pv.W(t0 + 4), d, 2 * d, dmem, S);
+    p = gp_dgrad(dkv, 2 * d, pv.W(t0 + 4), d, 2 * d, dmem_part, S);
     p.ldb = d; p.b_split = d; p.b_split_on_k = 1; p.b_seg_stride = seg; p.out_f32 = 1;
-    if (!first) { p.residual = dmem; p.ldr = d; }
-    run.gemm(p);
+    dmem_jobs.push_back(p);
     p = gp_wgrad(mem, d, dkv, 2 * d, pv.G(t0 + 4), d, 2 * d, S);
     p.ldc = d; p.ldr = d; p.c_split = d; p.c_seg_stride = seg;
     wgrad(p, pv.G(t0 + 5), nullptr, pv.fresh());
@@ -667,6 +692,20 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
     launch_embed_fwd(c->st, c->dt, emb_w(m_tgt), c->pe, c->dec_tok, c->dec_pos, y, U, d, sqrt_d);
     run.end();
   }
+  // every decoder layer's key/value projection of the encoder output depends on `mem` only:
+  // all of them in one launch, ahead of the decoder
+  std::vector<void*> kv_all;
+  {
+    std::vector<GemmParams> kv_jobs;
+    for (int mid : rt.dec) {
+      Module& m = c->mods[mid];
+      for (int l = 0; l < m.n_layers; ++l) {
+        kv_all.push_back(s.act((size_t)S * 2 * d));
+        kv_jobs.push_back(s.gp_cross_kv(PV{c, &m, l * DEC_T}, 10, mem, kv_all.back()));
+      }
+    }
+    run.gemm_set(kv_jobs);
+  }
   li = 0;
   for (int mid : rt.dec) {
     Module& m = c->mods[mid];
@@ -674,7 +713,7 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
       LayerSave ls;
       ls.pv = PV{c, &m, l * DEC_T};
       ls.self = s.self_fwd(ls.pv, 0, y, U, true);
-      ls.cross = s.cross_fwd(ls.pv, 10, ls.self.x_out, mem);
+      ls.cross = s.cross_fwd(ls.pv, 10, ls.self.x_out, kv_all[li]);
       ls.ffn = s.ffn_fwd(ls.pv, 20, ls.cross.x_out, U, s.F);
       y = ls.ffn.x_out;
       if (rt.ad_dec >= 0) {
@@ -730,16 +769,20 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
   run.ln_bwd(dh, y_dec_top, ln_decf.mean, ln_decf.rstd, pv_decf.V(0), nullptr, g.dx, g.dxT,
              pv_decf.G(0), pv_decf.G(1), U, pv_decf.fresh(), dh_parts, (int64_t)U * d);
   if (c->dt != BF16) g.dxT = g.dx;
-  float* dmem = s.f32((size_t)S * d);
-  bool first = true;
-  for (int i = (int)dec_saves.size() - 1; i >= 0; --i) {
+  // The gradient w.r.t. the encoder output is the sum of one product per decoder layer.  Each
+  // writes its own part; the products run as one launch after the decoder's backward and the
+  // encoder's closing LayerNorm backward adds the parts.
+  const int n_dec_layers = (int)dec_saves.size();
+  float* dmem = s.f32((size_t)S * d * n_dec_layers);
+  std::vector<GemmParams> dmem_jobs;
+  for (int i = n_dec_layers - 1; i >= 0; --i) {
     LayerSave& ls = dec_saves[i];
     if (ls.has_adapter) g = s.ffn_bwd(ls.apv, 0, ls.ad, g, U, c->mods[rt.ad_dec].adapter_dim);
     g = s.ffn_bwd(ls.pv, 20, ls.ffn, g, U, s.F);
-    g = s.cross_bwd(ls.pv, 10, ls.cross, g, mem, dmem, first);
-    first = false;
+    g = s.cross_bwd(ls.pv, 10, ls.cross, g, mem, dry ? nullptr : dmem + (size_t)i * S * d, dmem_jobs);
     g = s.self_bwd(ls.pv, 0, ls.self, g, U, true);
   }
+  run.gemm_set(dmem_jobs);
   float* eg_partial = s.f32((size_t)Rmax * d);
   if (!dry) {
     hipStreamWaitEvent(c->st, c->ev_sorted, 0);  // the side stream's token sorts
@@ -751,7 +794,7 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
   // ---------------- backward: encoder ----------------
   Step::Grad ge{s.f32((size_t)S * d), c->dt == BF16 ? s.act((size_t)S * d) : nullptr};
   run.ln_bwd(dmem, x_enc_top, ln_encf.mean, ln_encf.rstd, pv_encf.V(0), nullptr, ge.dx, ge.dxT,
-             pv_encf.G(0), pv_encf.G(1), S, pv_encf.fresh());
+             pv_encf.G(0), pv_encf.G(1), S, pv_encf.fresh(), n_dec_layers, (int64_t)S * d);
   if (c->dt != BF16) ge.dxT = ge.dx;
   for (int i = (int)enc_saves.size() - 1; i >= 0; --i) {
     LayerSave& ls = enc_saves[i];
@@ -821,6 +864,7 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
   // ---------------- per decoder layer: key/value projection of the encoder output, token cache ----
   struct DecLayer { PV pv; bool has_adapter; PV apv; char* kv_mem; char* cache; };
   std::vector<DecLayer> layers;
+  std::vector<GemmParams> kv_jobs;
   li = 0;
   for (int mid : rt.dec) {
     Module& m = c->mods[mid];
@@ -831,13 +875,11 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
       if (L.has_adapter) L.apv = PV{c, &c->mods[rt.ad_dec], li * ADP_T};
       L.kv_mem = (char*)s.act((size_t)S * 2 * d);
       L.cache = (char*)s.act((size_t)B * max_new * 3 * d);
-      const int64_t seg = L.pv.off(10 + 6) - L.pv.off(10 + 4);
-      GemmParams p = s.gp(mem, d, L.pv.W(10 + 4), d, L.kv_mem, 2 * d, S, 2 * d, d);
-      p.b_split = d; p.b_seg_stride = seg; p.bias = L.pv.V(10 + 5); p.bias_split = d; p.bias_seg_stride = seg;
-      run.gemm(p);
+      kv_jobs.push_back(s.gp_cross_kv(L.pv, 10, mem, L.kv_mem));
       layers.push_back(L);
     }
   }
+  run.gemm_set(kv_jobs);
   Module& m_dec_last = c->mods[rt.dec.back()];
   PV pv_decf{c, &m_dec_last, m_dec_last.n_layers * DEC_T};
   PV pv_gen{c, &m_gen, 0};
