@@ -759,7 +759,9 @@ __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict
       nt_st4(sg.theta + i, th[it]);
       nt_st4(sg.m + i, m[it]);
       nt_st4(sg.v + i, v[it]);
-      if (!sg.keep_g) nt_st4(sg.g + i, make_float4(0.f, 0.f, 0.f, 0.f));
+      // zero the bucket; a table's rows without gradient (most of them) are zero already
+      const uint32_t any_bits = __float_as_uint(g[it].x) | __float_as_uint(g[it].y) | __float_as_uint(g[it].z) | __float_as_uint(g[it].w);
+      if (!sg.keep_g && any_bits != 0u) nt_st4(sg.g + i, make_float4(0.f, 0.f, 0.f, 0.f));
       if (sg.w16) Io<bf16_t>::st4(sg.w16 + i, th[it]);
     }
   }
