@@ -543,8 +543,9 @@ struct Step {
   }
 };
 
-// per parameter: g, theta, m, v read (16 B); theta, m, v written (12 B); bf16 copy (2 B); g zeroed (4 B) unless kept
-double work_bytes_adam(const mm_ctx* c, int64_t n, bool keep_g) { return (double)n * ((c->dt == BF16 ? 30.0 : 28.0) + (keep_g ? 0.0 : 4.0)); }
+// per parameter: g, theta, m, v read (16 B); theta, m, v written (12 B); bf16 copy (2 B).  The zeroing
+// of an embedding table's bucket is not counted: only the pieces that held a gradient are written.
+double work_bytes_adam(const mm_ctx* c, int64_t n) { return (double)n * (c->dt == BF16 ? 30.0 : 28.0); }
 
 mm_status collect_profile(mm_ctx* c) {
   if (c->prof_recs.empty()) return MM_OK;
@@ -1430,7 +1431,7 @@ mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float
     sg.first_chunk = chunks; sg.keep_g = bucket_overwrites(m.kind);
     chunks += (int)((m.P + ADAM_CHUNK - 1) / ADAM_CHUNK);
     total += m.P;
-    work += work_bytes_adam(c, m.P, sg.keep_g != 0);
+    work += work_bytes_adam(c, m.P);
     m.touched = 0;
   }
   c->pending_counted = false;  // the step's uses have been consumed
