@@ -315,6 +315,41 @@ __device__ __forceinline__ bf16x8_t frag_from_regs(const float* v) {
   return c.f;
 }
 
+// Stores a wavefront's 32 x 64 result tile.  The accumulators hold it transposed: lane (lcol, hh)
+// owns output row lcol and, per register group g4 of column tile ct, the four consecutive columns
+// ct*32 + 8*g4 + 4*hh ...  Written from there each store instruction would put 16 bytes into each
+// of 32 different rows.  Each half of the tile (32 columns) goes through the wavefront's own 2 KB
+// LDS patch instead (rows of 64 bytes, 16-byte chunk c of row r in slot c ^ (r & 3)) and leaves
+// as 64-byte row pieces, four lanes per row.  Only LDS traffic of this wavefront is involved, so
+// a wavefront-level fence orders the patch writes before the reads; no workgroup barrier.
+constexpr int STORE_PATCH_BYTES = 2048;
+__device__ __forceinline__ void store_tile_rows(unsigned char* patch, const f32x16_t (&acc)[2], bf16_t* dst0, int64_t ld,
+                                                int rows_valid, int lane) {
+  const int lcol = lane & 31, hh = lane >> 5;
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct) {
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      uint2 o;
+      o.x = pack_bf16(acc[ct][4 * g4 + 0], acc[ct][4 * g4 + 1]);
+      o.y = pack_bf16(acc[ct][4 * g4 + 2], acc[ct][4 * g4 + 3]);
+      *reinterpret_cast<uint2*>(patch + lcol * 64 + ((g4 ^ (lcol & 3)) << 4) + (hh << 3)) = o;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = 16 * i + (lane >> 2), c = lane & 3;
+      const uint4 v = *reinterpret_cast<const uint4*>(patch + row * 64 + ((c ^ (row & 3)) << 4));
+      if (row < rows_valid) *reinterpret_cast<uint4*>(dst0 + (int64_t)row * ld + ct * 32 + c * 8) = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the patch is free again once these reads are done
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
 template <int NKT>
 __global__ void __launch_bounds__(512, 1) attn_fwd_mfma_kernel(const AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -327,6 +362,7 @@ __global__ void __launch_bounds__(512, 1) attn_fwd_mfma_kernel(const AttnParams 
   unsigned char* Kn = smem_raw;
   unsigned char* Vn = Kn + Lp * 128;
   unsigned char* Qn = Vn + Lp * 128;
+  unsigned char* patch = Qn + Lqp * 128 + wave * STORE_PATCH_BYTES;
   const bf16_t* qg = (const bf16_t*)p.q + h * 64;
   const float scale = 0.125f;  // 1 / sqrt(64)
   const int nwave = blockDim.x >> 6;
@@ -427,24 +463,13 @@ __global__ void __launch_bounds__(512, 1) attn_fwd_mfma_kernel(const AttnParams 
     for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oc[ct][r] *= inv;
-    if (valid_q) {
-      bf16_t* og = (bf16_t*)p.o + grow * p.ldo + h * 64;
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          uint2 o;
-          o.x = pack_bf16(oc[ct][4 * g4 + 0], oc[ct][4 * g4 + 1]);
-          o.y = pack_bf16(oc[ct][4 * g4 + 2], oc[ct][4 * g4 + 3]);
-          *reinterpret_cast<uint2*>(og + ct * 32 + 8 * g4 + 4 * hh) = o;
-        }
-    }
+    store_tile_rows(patch, oc, (bf16_t*)p.o + (int64_t)(q0 + qt * 32) * p.ldo + h * 64, p.ldo, lq - qt * 32, lane);
   }
 }
 
-inline size_t mfma_fwd_lds(int max_lq, int max_lk) {
+inline size_t mfma_fwd_lds(int max_lq, int max_lk, int waves) {
   const int Lq = ((max_lq + 31) / 32) * 32, Lk = ((max_lk + 31) / 32) * 32;
-  return (size_t)(2 * Lk + Lq) * 128;   // K, V and Q tiles
+  return (size_t)(2 * Lk + Lq) * 128 + (size_t)waves * STORE_PATCH_BYTES;   // K, V and Q tiles; one store patch per wavefront
 }
 
 // Backward with the same layouts, one workgroup per (sentence, head).  The Q, dO, K and V tiles of
@@ -480,6 +505,7 @@ __global__ void __launch_bounds__(512, 1) attn_bwd_mfma_kernel(const AttnParams 
   unsigned char* dOn = Qn + Lqp * 128;
   unsigned char* Kn = dOn + Lqp * 128;
   unsigned char* Vn = Kn + Lkp * 128;
+  unsigned char* patch = Vn + Lkp * 128 + wave * STORE_PATCH_BYTES;
 
   // all loads of an iteration are issued before the first store
   const int n_items = (Lqp > Lkp ? Lqp : Lkp) * 2;
@@ -568,18 +594,7 @@ __global__ void __launch_bounds__(512, 1) attn_bwd_mfma_kernel(const AttnParams 
           dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Kn, kt * 32 + s2 * 16, ct, lane), dsf, dq[ct], 0, 0, 0);
       }
     }
-    if (valid_q) {
-      bf16_t* dst = (bf16_t*)p.dq + (int64_t)(q0 + ql) * p.lddq + h * 64;
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          uint2 o;
-          o.x = pack_bf16(dq[ct][4 * g4 + 0], dq[ct][4 * g4 + 1]);
-          o.y = pack_bf16(dq[ct][4 * g4 + 2], dq[ct][4 * g4 + 3]);
-          *reinterpret_cast<uint2*>(dst + ct * 32 + 8 * g4 + 4 * hh) = o;
-        }
-    }
+    store_tile_rows(patch, dq, (bf16_t*)p.dq + (int64_t)(q0 + qt * 32) * p.lddq + h * 64, p.lddq, lq - qt * 32, lane);
   }
 
   // ---------------- phase B: dK, dV ----------------
@@ -642,28 +657,15 @@ __global__ void __launch_bounds__(512, 1) attn_bwd_mfma_kernel(const AttnParams 
         }
       }
     }
-    if (valid_k) {
-      bf16_t* dkd = (bf16_t*)p.dk + (int64_t)(k0 + kl) * p.lddk + h * 64;
-      bf16_t* dvd = (bf16_t*)p.dv + (int64_t)(k0 + kl) * p.lddv + h * 64;
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          uint2 o;
-          o.x = pack_bf16(dk[ct][4 * g4 + 0], dk[ct][4 * g4 + 1]);
-          o.y = pack_bf16(dk[ct][4 * g4 + 2], dk[ct][4 * g4 + 3]);
-          *reinterpret_cast<uint2*>(dkd + ct * 32 + 8 * g4 + 4 * hh) = o;
-          o.x = pack_bf16(dv[ct][4 * g4 + 0], dv[ct][4 * g4 + 1]);
-          o.y = pack_bf16(dv[ct][4 * g4 + 2], dv[ct][4 * g4 + 3]);
-          *reinterpret_cast<uint2*>(dvd + ct * 32 + 8 * g4 + 4 * hh) = o;
-        }
-    }
+    store_tile_rows(patch, dk, (bf16_t*)p.dk + (int64_t)(k0 + kt * 32) * p.lddk + h * 64, p.lddk, lk - kt * 32, lane);
+    store_tile_rows(patch, dv, (bf16_t*)p.dv + (int64_t)(k0 + kt * 32) * p.lddv + h * 64, p.lddv, lk - kt * 32, lane);
   }
 }
 
-inline size_t mfma_bwd_lds(int max_lq, int max_lk) {
+inline size_t mfma_bwd_lds(int max_lq, int max_lk, int waves) {
   const size_t Lq = ((max_lq + 31) / 32) * 32, Lk = ((max_lk + 31) / 32) * 32;
-  return 2 * Lq * sizeof(float) + 2 * Lq * 128 + 2 * Lk * 128;   // D and lse tables; Q, dO, K, V tiles
+  // D and lse tables; Q, dO, K, V tiles; one store patch per wavefront
+  return 2 * Lq * sizeof(float) + 2 * Lq * 128 + 2 * Lk * 128 + (size_t)waves * STORE_PATCH_BYTES;
 }
 
 template <typename T>
@@ -684,14 +686,14 @@ size_t attn_lds_bytes(Dtype dt, int dh, int max_lq, int max_lk, bool backward) {
 
 static bool mfma_ok(Dtype dt, const AttnParams& p) {
   return dt == BF16 && p.dh == 64 && p.max_lk <= 256 && p.max_lq <= 256 && p.ldq % 8 == 0 && p.ldk % 8 == 0 &&
-         p.ldv % 8 == 0 && p.ldo % 4 == 0;
+         p.ldv % 8 == 0 && p.ldo % 8 == 0;
 }
 
 void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p, const LaunchEvents& ev) {
   if (mfma_ok(dt, p)) {
-    const size_t lds = mfma_fwd_lds(p.max_lq, p.max_lk);
     // one wavefront per 32 queries, up to eight: short sentences get small workgroups, so more of them share a CU
     const int threads = 64 * std::min(8, (p.max_lq + 31) / 32);
+    const size_t lds = mfma_fwd_lds(p.max_lq, p.max_lk, threads / 64);
     if (p.max_lk <= 128) {
       hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       hipExtLaunchKernelGGL(attn_fwd_mfma_kernel<4>, dim3(p.B * p.H), dim3(threads), lds, st, ev.start, ev.stop, 0, p);
@@ -712,10 +714,11 @@ void launch_attn_fwd(hipStream_t st, Dtype dt, const AttnParams& p, const Launch
 }
 
 void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p, const LaunchEvents& ev) {
-  if (mfma_ok(dt, p) && p.lddo % 8 == 0 && p.lddq % 4 == 0 && p.lddk % 4 == 0 && p.lddv % 4 == 0) {
-    const size_t lds = mfma_bwd_lds(p.max_lq, p.max_lk);
+  if (mfma_ok(dt, p) && p.lddo % 8 == 0 && p.lddq % 8 == 0 && p.lddk % 8 == 0 && p.lddv % 8 == 0) {
+    int threads = 64 * std::min(8, (std::max(p.max_lq, p.max_lk) + 31) / 32);
+    if (mfma_bwd_lds(p.max_lq, p.max_lk, threads / 64) > 160 * 1024) threads = 256;   // the longest sentences: four store patches
+    const size_t lds = mfma_bwd_lds(p.max_lq, p.max_lk, threads / 64);
     hipFuncSetAttribute((const void*)attn_bwd_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    const int threads = 64 * std::min(8, (std::max(p.max_lq, p.max_lk) + 31) / 32);
     hipExtLaunchKernelGGL(attn_bwd_mfma_kernel, dim3(p.B * p.H), dim3(threads), lds, st, ev.start, ev.stop, 0, p);
     return;
   }
