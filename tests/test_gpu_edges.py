@@ -94,3 +94,13 @@ def test_update_of_listed_modules_only():
         assert np.abs(ctx.mm_get_params(j) - orc.modules[j].theta).max() <= 2.5e-3
     for j in rest:
         assert ctx.mm_get_adam(j)[2] == 0 and np.array_equal(ctx.mm_get_grads(j), keep[j])
+
+
+def test_nine_decoder_layers():
+    """More decoder layers than one multi-product launch takes (eight): the key/value projections
+    of the encoder output and their input-gradient products go out in two groups, and the
+    encoder's closing LayerNorm backward adds nine parts."""
+    setup = tiny_setup(d=128, H=2, F_=64, V=56, adapter_dim=16, dtype="bf16", max_len=24, dec_layers=9)
+    batch = tiny_batch(setup, lengths=((5, 4), (3, 7), (8, 2), (1, 5), (24, 25), (2, 2), (17, 9)))
+    say("[case] nine decoder layers")
+    _run(setup, batch, "bf16", label="9 decoder layers")
