@@ -141,6 +141,13 @@ def main():
     ap.add_argument("--task-temperature", type=float, default=None,
                     help="draw each pass's task with probability proportional to (corpus size)^(1/T), "
                          "corpus sizes falling off as 1/rank, instead of uniformly")
+    ap.add_argument("--sharing", default=None, metavar="ENC/DEC",
+                    help="replace the set-up's modules and tasks by a layerwise sharing definition, one "
+                         "PATTERN:LAYERS per module position, e.g. 'LANGUAGE:4,FULL:4/LANGUAGE:4' "
+                         "(patterns: FULL, SRC_GROUP, TGT_GROUP, GROUP, SRC_LANGUAGE, TGT_LANGUAGE, LANGUAGE); "
+                         "model shape, data and seeds stay those of --config")
+    ap.add_argument("--languages", type=int, default=4, help="with --sharing: number of languages (all ordered pairs are tasks)")
+    ap.add_argument("--groups", type=int, default=2, help="with --sharing: language l belongs to cluster l %% GROUPS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--translate", type=int, default=0, metavar="MAX_NEW",
                     help="time routed greedy translation instead of training: every sentence of one batch "
@@ -163,6 +170,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     setup = mm_synth.build_setup(args.config)
+    if args.sharing:
+        enc_text, _, dec_text = args.sharing.partition("/")
+        setup = mm_synth.pattern_setup(setup, args.languages, mm_synth.parse_stack(enc_text), mm_synth.parse_stack(dec_text),
+                                       {l: l % max(1, args.groups) for l in range(args.languages)})
     sh = setup.shape
     A = max(1, args.accumulate)
     n_steps = (args.warmup + args.steps) * A      # routed passes; A of them per update
@@ -231,7 +242,7 @@ def main():
                 "avg_launch_us": 1e3 * g["ms"] / max(1, g["launches"]), "launches_per_step": g["launches"] / args.steps}
     # HBM bytes per GEMM launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (same workload)
     tpath = os.path.join(ROOT, "profiles", f"bench_config{args.config}_gemm_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not args.sharing:
         t = json.load(open(tpath))
         roofline["traffic"] = t["read_bytes_per_launch"] + t["written_bytes_per_launch"]
         roofline["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel)"
@@ -251,7 +262,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps,
         "ms_per_step_gpu": {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90)}, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
-        "config": {"workload": f"configs[{args.config - 1}]: {setup.title}; d={sh.d_model} heads={sh.n_heads} "
+        "config": {"workload": f"configs[{args.config - 1}]{' shape and data with' if args.sharing else ':'} {setup.title}; d={sh.d_model} heads={sh.n_heads} "
                                f"ffn={sh.d_ff} vocab={sh.vocab}, {len(setup.modules)} modules resident, "
                                f"{len(setup.tasks)} task(s), ~{sh.batch_tokens}-token length-bucketed batches"
                                + (f", {A} routed passes per update" if A > 1 else "")

@@ -18,3 +18,11 @@ from .data import (  # noqa: F401
     zipf_cdf,
 )
 from .init import fill_params  # noqa: F401
+from .sharing import (  # noqa: F401
+    PATTERNS,
+    layerwise_tasks,
+    parse_stack,
+    pattern_setup,
+    route_signature,
+    sharing_name,
+)

@@ -274,3 +274,44 @@ def test_steps_and_updates_interleaved(dtype):
     step("2-1", 5); step("2-1", 6); update(None)
     step("1-2", 7)
     ctx.close()
+
+
+def test_step_on_a_sharing_pattern_setup():
+    """Modules and tasks generated from layerwise sharing patterns (appendix B), including a
+    target-language-dependent encoder position and a decoder split into a shared and a
+    language-specific position: three directions that share modules in different ways, then one
+    update of everything touched."""
+    base = tiny_setup(d=32, H=2, F_=64, V=56, adapters=False, dtype="f32", max_len=24)
+    setup = mm_synth.pattern_setup(base, 3, [("GROUP", 1), ("TGT_LANGUAGE", 1)], [("FULL", 1), ("LANGUAGE", 1)],
+                                   {0: 0, 1: 0, 2: 1})
+    say(f"[case] sharing-pattern set-up: {setup.title}, {len(setup.modules)} modules, {len(setup.tasks)} tasks")
+    ctx, orc = make_pair(setup)
+    batch = tiny_batch(setup, lengths=RAGGED)
+    names = [n for n, _ in setup.tasks]
+    used = set()
+    for task in (names.index("0-2"), names.index("1-2"), names.index("2-0")):
+        loss = ctx.mm_train_step(task, batch.src_ids, batch.tgt_ids, batch.lengths)
+        ref = orc.train_step(task, batch.src_ids, batch.tgt_ids, batch.lengths)
+        say(f"  task {names[task]}: loss {loss:.6f} oracle {ref:.6f}")
+        assert abs(loss - ref) <= 1e-4 * abs(ref)
+        assert ctx.mm_get_route(task) == list(orc.routes[task])
+        check_touched(ctx, orc)
+        used |= set(orc.routes[task])
+    # 0-2 and 1-2 share the first encoder position (group 0), the second (target language 2), both
+    # decoder positions, the target table and the generator: those have been used twice, 2-0's once
+    counts = ctx.mm_get_touched()
+    r02, r12, r20 = (orc.routes[names.index(n)] for n in ("0-2", "1-2", "2-0"))
+    assert all(counts[j] == 2 for j in set(r02) & set(r12) - set(r20))
+    assert all(counts[j] == 3 for j in set(r02) & set(r12) & set(r20))   # the fully shared decoder position
+    worst = check_grads(ctx, orc, sorted(used), label="pattern", **F32_TOL)
+    say(f"  worst tensor rel L2 {worst}")
+    check_untouched_zero(ctx, orc, used)
+    ctx.mm_apply_update(None, setup.shape.lr)
+    orc.apply_update(None, setup.shape.lr)
+    for j in range(len(setup.modules)):
+        d = np.abs(ctx.mm_get_params(j) - orc.modules[j].theta)
+        if j in used:   # first Adam step: |delta| <= lr each, so a near-zero gradient's sign may differ
+            assert d.max() <= 2.5 * setup.shape.lr, f"module {j}"
+            assert ctx.mm_get_adam(j)[2] == orc.modules[j].t == 1
+        else:
+            assert d.max() == 0 and ctx.mm_get_adam(j)[2] == 0, f"module {j} was not on any route"

@@ -178,3 +178,87 @@ def test_paper_shape_setups_carry_section4_numbers():
             assert len(shared) == 1 and shared[0].n_layers == gold["scheme2_enc_shared"] and shared[0].position == 1
         if scheme == 3:      # one encoder for all languages
             assert names == {"full"}
+
+
+# ---- layerwise sharing patterns (appendix B) and the task constraints of section 3.2 ----------
+
+def _all_pairs(n):
+    return [(s, t) for s in range(n) for t in range(n) if s != t]
+
+
+# (set-up, encoder positions, decoder positions, language groups): the sharing definition each
+# benchmark set-up is meant to be an instance of
+_SHARING = {
+    3: ([("LANGUAGE", 6)], [("LANGUAGE", 6)], None),
+    4: ([("GROUP", 3), ("FULL", 3)], [("LANGUAGE", 6)], {0: 0, 1: 0, 2: 1, 3: 1}),
+    5: ([("SRC_LANGUAGE", 6)], [("TGT_LANGUAGE", 6)], None),
+    6: ([("LANGUAGE", 6)], [("LANGUAGE", 6)], None),
+    7: ([("LANGUAGE", 4), ("FULL", 4)], [("LANGUAGE", 4)], None),
+    8: ([("FULL", 9)], [("LANGUAGE", 4)], None),
+}
+
+
+@pytest.mark.parametrize("index", sorted(_SHARING))
+def test_benchmark_routes_are_instances_of_the_sharing_patterns(index):
+    setup = mm_synth.build_setup(index)
+    enc, dec, groups = _SHARING[index]
+    pairs = [tuple(int(x) for x in name.split("-")) for name, _ in setup.tasks]
+    modules, tasks = mm_synth.layerwise_tasks(pairs, enc, dec, groups)
+    n_route = len(enc) + len(dec) + 3
+    for (name, route), (name2, route2) in zip(setup.tasks, tasks):
+        assert name == name2
+        # adapters (set-up 4) follow the pattern-defined part of a route
+        assert mm_synth.route_signature(setup.modules, route[:n_route]) == mm_synth.route_signature(modules, route2)
+        assert all(setup.modules[j].kind == "adapter" for j in route[n_route:])
+    # the same modules exist, whatever their numbering (a set-up may hold modules no task uses yet)
+    have = {mm_synth.route_signature(setup.modules, [j])[0] for j, m in enumerate(setup.modules) if m.kind != "adapter"}
+    used = {mm_synth.route_signature(modules, [j])[0] for j in range(len(modules))}
+    assert used <= have
+    if index != 4:   # set-up 4 keeps all four languages resident but trains 8 of the 12 directions
+        assert used == have
+
+
+def test_sharing_pattern_names():
+    g = {0: 0, 1: 0, 2: 1}
+    name = mm_synth.sharing_name
+    assert name("FULL", "enc", 0, 2, g) == name("FULL", "dec", 1, 0, g) == "full"
+    assert name("SRC_GROUP", "enc", 1, 2, g) == "group0" and name("TGT_GROUP", "enc", 1, 2, g) == "group1"
+    assert name("GROUP", "enc", 1, 2, g) == "group0" and name("GROUP", "dec", 1, 2, g) == "group1"
+    assert name("SRC_LANGUAGE", "dec", 1, 2, g) == "lang1" and name("TGT_LANGUAGE", "enc", 1, 2, g) == "lang2"
+    assert name("LANGUAGE", "enc", 1, 2, g) == "lang1" and name("LANGUAGE", "dec", 1, 2, g) == "lang2"
+    with pytest.raises(ValueError):
+        name("HALF", "enc", 0, 1, g)
+    with pytest.raises(ValueError):
+        name("SRC_GROUP", "enc", 5, 1, g)   # a language outside every cluster
+
+
+def test_modules_are_position_specific_and_counts_are_equal():
+    # two positions with the same pattern: the names coincide, the modules do not (section 3.2:
+    # the groups [x, y] and [y, x] are four modules)
+    modules, tasks = mm_synth.layerwise_tasks([(0, 1), (1, 0)], [("SRC_LANGUAGE", 2), ("TGT_LANGUAGE", 2)],
+                                              [("FULL", 1)], None)
+    enc = [m for m in modules if m.kind == "enc"]
+    assert sorted((m.position, m.name) for m in enc) == [(0, "lang0"), (0, "lang1"), (1, "lang0"), (1, "lang1")]
+    assert len({len(r) for _, r in tasks}) == 1                       # constraint (i)
+    assert [m.owns_final_norm for m in enc] == [m.position == 1 for m in enc]
+    assert sum(m.kind == "dec" for m in modules) == 1                 # one fully shared decoder
+    # a target-language-dependent encoder position: tasks into the same language share it
+    modules, tasks = mm_synth.layerwise_tasks(_all_pairs(3), [("LANGUAGE", 1), ("TGT_LANGUAGE", 1)], [("FULL", 1)])
+    by_name = dict(tasks)
+    assert by_name["0-2"][2] == by_name["1-2"][2] != by_name["0-1"][2]
+    assert by_name["0-2"][1] == by_name["0-1"][1] != by_name["1-2"][1]
+
+
+def test_pattern_generated_tasks_register_and_route():
+    # what the helper emits passes the library's own route rules (same count for every task, kinds
+    # in order, positions consistent, stacks closed) -- host bookkeeping only, no compute
+    modules, tasks = mm_synth.layerwise_tasks(_all_pairs(3), [("GROUP", 1), ("FULL", 1)], [("LANGUAGE", 2)],
+                                              {0: 0, 1: 0, 2: 1})
+    ctx = _ctx()
+    orc = Oracle(32, 2, 64, 56, 24)
+    for m in modules:
+        a = ctx.mm_register_module(m.kind, m.name, m.position, m.n_layers, m.owns_final_norm)
+        assert a == orc.register_module(m.kind, m.name, m.position, m.n_layers, m.owns_final_norm)
+    for k, (_, route) in enumerate(tasks):
+        assert ctx.mm_route_task(route) == orc.route_task(route) == k
+        assert ctx.mm_get_route(k) == list(route)
