@@ -258,3 +258,36 @@ def test_only_the_tasks_modules_are_read(dtype):
     for j in route:
         assert np.array_equal(ctx.mm_get_grads(j), grads0[j])
     ctx.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_a_context_holding_only_the_tasks_modules_translates_the_same(dtype):
+    """Section 3.2 (inference): only the components a task needs have to be loaded.  A second
+    context registers just the modules on one task's route, with the trained context's values,
+    and must write the same tokens bit for bit; its memory is a fraction of the full model's."""
+    from paper_2403_07544_amd import Context
+    d = 32 if dtype == "f32" else 128
+    setup = tiny_setup(d=d, H=2, F_=64, V=56, n_lang=3, adapter_dim=16, dtype=dtype, max_len=24)
+    ctx, orc = sharpened_pair(setup, 6.0, 1.0)
+    batch = tiny_batch(setup, lengths=LENGTHS)
+    src, s_len = batch.src_ids, batch.lengths[:, 0].copy()
+    task = 3
+    route = ctx.mm_get_route(task)
+    full = ctx.mm_translate_greedy(task, src, s_len, 8)
+    sh = setup.shape
+    small = Context(sh.d_model, sh.n_heads, sh.d_ff, sh.vocab, sh.dtype, sh.max_len, 256, sh.label_smoothing,
+                    sh.adam_beta1, sh.adam_beta2, sh.adam_eps, sh.ln_eps)
+    new_ids = []
+    for j in route:
+        ms = setup.modules[j]
+        k = small.mm_register_module(ms.kind, ms.name, ms.position, ms.n_layers, ms.owns_final_norm,
+                                     ms.adapter_dim, ms.stack)
+        small.mm_set_params(k, ctx.mm_get_params(j))
+        new_ids.append(k)
+    t = small.mm_route_task(new_ids)
+    assert small.mm_num_modules() == len(route) < ctx.mm_num_modules()
+    part = small.mm_translate_greedy(t, src, s_len, 8)
+    say(f"  {len(route)} of {ctx.mm_num_modules()} modules loaded; lengths {part[1].tolist()}")
+    assert np.array_equal(full[0], part[0]) and np.array_equal(full[1], part[1])
+    small.close()
+    ctx.close()
