@@ -96,6 +96,7 @@ def test_batch_validation_and_state_errors():
 
     assert status() == MM_ESTATE                       # valid batch, but the context cannot compute
     assert status(task=7) == MM_EINVAL
+    assert status(src=batch.src_ids[:0], tgt=batch.tgt_ids[:0], lengths=batch.lengths[:0]) == MM_EINVAL   # empty batch
     src = batch.src_ids.copy(); src[0, 0] = 56
     assert status(src=src) == MM_ERANGE                # id >= vocab
     tgt = batch.tgt_ids.copy(); tgt[0, -1] = 5
