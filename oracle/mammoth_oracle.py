@@ -23,7 +23,10 @@ moments, single-key attention); structural identities (split stack == whole stac
 zero adapter == no adapter, padding width, unused modules untouched).  Routed inference
 (`forward_logits`, `greedy_decode`): the library transcription sentence by sentence, a greedy
 loop written over it, the training step's own logits, prefix and batch-independence
-properties, forced and forbidden EOS, equal top logits.
+properties, forced and forbidden EOS, equal top logits.  Beam search (`beam_decode`): beam 1
+against the greedy search, a beam that holds every prefix against brute force over all sequences
+scored with the library transcription, scores recomputed from it, carried finished hypotheses,
+tie order.
 """
 from __future__ import annotations
 
@@ -634,6 +637,59 @@ class Oracle:
                     if tok == EOS:
                         alive[b] = False
         return out, n_out
+
+    def beam_decode(self, task: int, src_ids, src_len, max_new: int, beam: int):
+        """Beam search, the slow way (the paper fixes no search procedure; reading: the textbook
+        length-synchronous beam with summed log-probabilities and no length normalisation).
+        Per sentence a beam of at most `beam` hypotheses, best first, starting from the empty
+        one with score 0.  Each step every unfinished hypothesis i is extended by every token v
+        at score_i + log softmax(z_i)[v], where z_i is the generator's logit row after BOS and
+        the hypothesis' tokens (the whole model is run again from the source); a finished
+        hypothesis (one that ends in EOS) is carried over unchanged.  The `beam` best candidates
+        form the next beam; ties go to the lower hypothesis index, then the lower token id.  The
+        search ends when every hypothesis in the beam is finished or after max_new tokens; the
+        first hypothesis is the result.  beam = 1 is `greedy_decode`.
+        Returns (ids [B, max_new] padded with PAD, produced counts [B], scores [B])."""
+        src_ids, s_len = np.asarray(src_ids), np.asarray(src_len)
+        B = src_ids.shape[0]
+        assert 1 <= max_new <= self.max_len and beam >= 1
+        out = np.full((B, max_new), PAD, dtype=np.int32)
+        n_out = np.zeros(B, dtype=np.int32)
+        best = np.zeros(B, dtype=np.float64)
+        for b in range(B):
+            hyps = [([], 0.0, False)]                      # (tokens, score, finished)
+            for t in range(max_new):
+                live = [i for i, h in enumerate(hyps) if not h[2]]
+                if not live:
+                    break
+                dec_in = np.full((len(live), t + 1), PAD, dtype=np.int32)
+                dec_in[:, 0] = BOS
+                for r, i in enumerate(live):
+                    dec_in[r, 1:] = hyps[i][0]             # an unfinished hypothesis has exactly t tokens
+                z = self.forward_logits(task, np.repeat(src_ids[b:b + 1], len(live), axis=0),
+                                        np.repeat(s_len[b:b + 1], len(live)), dec_in,
+                                        np.full(len(live), t + 1, dtype=np.int32))
+                cand = []                                   # (-score, hypothesis index, token or -1)
+                for i, h in enumerate(hyps):
+                    if h[2]:
+                        cand.append((-h[1], i, -1))
+                for r, i in enumerate(live):
+                    row = z[r, t].astype(np.float64)
+                    mx = row.max()
+                    logp = row - (mx + np.log(np.exp(row - mx).sum()))
+                    for v in range(self.V):
+                        cand.append((-(hyps[i][1] + logp[v]), i, v))
+                cand.sort()
+                nxt = []
+                for neg, i, v in cand[:beam]:
+                    toks, _, fin = hyps[i]
+                    nxt.append((toks, -neg, True) if v < 0 else (toks + [v], -neg, v == EOS))
+                hyps = nxt
+            toks, score, _ = hyps[0]
+            out[b, :len(toks)] = toks
+            n_out[b] = len(toks)
+            best[b] = score
+        return out, n_out, best
 
     # ---- renormalise and update (Algorithm 1 last line + Adam) ---------------------------
     def apply_update(self, module_ids: Optional[Sequence[int]], lr: float):
