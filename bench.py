@@ -76,16 +76,23 @@ def bench_translate(args, setup, ctx, batches):
     src = torch.tensor(src_host, dtype=torch.int32, device="cuda")
     B = len(s_len)
     directions = [tasks[k % len(tasks)] for k in range(args.warmup + args.steps)]
+    beam = max(0, args.beam)
+
+    def translate(task):
+        if beam:
+            return ctx.mm_translate_beam(task, src, s_len, max_new, beam)[:2]
+        return ctx.mm_translate_greedy(task, src, s_len, max_new)
+
     for k in range(args.warmup):
-        ctx.mm_translate_greedy(directions[k], src, s_len, max_new)
+        translate(directions[k])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.warmup, args.warmup + args.steps):
-        ids, n = ctx.mm_translate_greedy(directions[k], src, s_len, max_new)
+        ids, n = translate(directions[k])
     elapsed = time.perf_counter() - t0
     assert (n == max_new).all()
     ctx.mm_profile(True)
-    ctx.mm_translate_greedy(directions[0], src, s_len, max_new)
+    translate(directions[0])
     prof = ctx.mm_profile_read()
     ctx.mm_profile(False)
     classes = {name: {"ms_per_call": r["ms"], "launches_per_call": r["launches"]}
@@ -113,19 +120,25 @@ def bench_translate(args, setup, ctx, batches):
         orc.modules[gen].p("bg")[2] = -1e3
         nb, steps_cpu = min(32, B), min(20, max_new)   # about 10 s
         t1 = time.perf_counter()
-        _, n_cpu = orc.greedy_decode(tasks[0], src_host[:nb], s_len[:nb], steps_cpu)
+        if beam:
+            nb, steps_cpu = min(4, B), min(8, max_new)
+            _, n_cpu, _ = orc.beam_decode(tasks[0], src_host[:nb], s_len[:nb], steps_cpu, beam)
+        else:
+            _, n_cpu = orc.greedy_decode(tasks[0], src_host[:nb], s_len[:nb], steps_cpu)
         dt = time.perf_counter() - t1
         from threadpoolctl import threadpool_info
         threads = max([q.get("num_threads", 1) for q in threadpool_info()] or [1])
         cpu = {"value": float(n_cpu.sum()) / dt, "unit": "generated tokens/s", "cores": int(threads), "kind": "oracle",
                "sample": f"{nb} sentences x {steps_cpu} tokens of the same batch, {dt:.1f} s"}
     print(json.dumps({
-        "metric": "greedy translation tokens/s per MI355X (routed inference)", "value": B * max_new * args.steps / elapsed,
+        "metric": (f"beam-{beam} translation" if beam else "greedy translation") + " tokens/s per MI355X (routed inference)",
+        "value": B * max_new * args.steps / elapsed,
         "unit": "generated tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * elapsed / args.steps, "ms_per_decoding_step": 1e3 * elapsed / args.steps / max_new,
         "higher_is_better": True, "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}]: {setup.title}; {B} sentences, {int(s_len.sum())} source "
-                               f"tokens, {max_new} tokens written per sentence"},
+                               f"tokens, {max_new} tokens written per sentence"
+                               + (f", {beam} hypotheses per sentence ({B * beam} decoder rows)" if beam else "")},
         "roofline": roofline, "cpu_baseline": cpu, "kernel_classes": classes}))
 
 
@@ -152,6 +165,8 @@ def main():
     ap.add_argument("--translate", type=int, default=0, metavar="MAX_NEW",
                     help="time routed greedy translation instead of training: every sentence of one batch "
                          "writes MAX_NEW tokens (EOS is suppressed so the work is fixed)")
+    ap.add_argument("--beam", type=int, default=0, metavar="K",
+                    help="with --translate: beam search with K hypotheses per sentence instead of greedy search")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a kernel of known traffic, used to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")

@@ -142,6 +142,22 @@ mm_status mm_translate_greedy(mm_ctx* ctx, int32_t task, const int32_t* src_ids,
                               int32_t B, int32_t S_max, int32_t max_new, int32_t ids_mem,
                               int32_t* out_ids, int32_t* out_lengths);
 
+/* Beam search with the task's own modules (same property as mm_translate_greedy: only the task's
+ * modules are read, no training state is written).  The paper names no search procedure; this is
+ * the textbook one: per sentence `beam` hypotheses, best first, starting from the empty one at
+ * score 0; each step an unfinished hypothesis extended by token v scores its own score plus
+ * log softmax(logits)[v] (fp32), a hypothesis that ended in EOS (id 2) is carried at its score; the
+ * `beam` best candidates form the next beam, equal scores going to the lower hypothesis, then
+ * the lower token id; no length normalisation.  The search ends when every hypothesis of every
+ * sentence is finished or after max_new tokens; the first hypothesis of each beam is returned.
+ * beam = 1 produces what mm_translate_greedy produces.
+ *   1 <= beam <= 8; B * beam <= max_batch_tokens; other arguments as for mm_translate_greedy.
+ *   out_scores [B] float (host, may be NULL): summed log-probability of the returned hypothesis.
+ * Synchronous; errors and the note on mm_debug_dump as for mm_translate_greedy. */
+mm_status mm_translate_beam(mm_ctx* ctx, int32_t task, const int32_t* src_ids, const int32_t* src_lengths,
+                            int32_t B, int32_t S_max, int32_t max_new, int32_t beam, int32_t ids_mem,
+                            int32_t* out_ids, int32_t* out_lengths, float* out_scores);
+
 /* Waits for the most recent mm_train_step and returns its loss and status. */
 mm_status mm_last_loss(mm_ctx* ctx, float* out_loss);
 

@@ -28,7 +28,7 @@ DUMP = {"cu_src": 0, "cu_dec": 1, "src_tok": 2, "src_pos": 3, "dec_tok": 4, "dec
 KERNEL_CLASSES = ("gemm", "attn_fwd", "attn_bwd", "layernorm_fwd", "layernorm_bwd", "embed",
                   "embed_grad", "ce", "colsum", "adam", "other")
 
-EXPORTS = ("mm_create", "mm_destroy", "mm_register_module", "mm_route_task", "mm_train_step", "mm_translate_greedy",
+EXPORTS = ("mm_create", "mm_destroy", "mm_register_module", "mm_route_task", "mm_train_step", "mm_translate_greedy", "mm_translate_beam",
            "mm_last_loss", "mm_apply_update", "mm_num_modules", "mm_get_route", "mm_get_touched",
            "mm_get_layout", "mm_get_params", "mm_set_params", "mm_get_grads", "mm_get_bucket_memory", "mm_set_grads",
            "mm_get_adam", "mm_get_working", "mm_debug_dump", "mm_profile", "mm_profile_read",
@@ -75,6 +75,7 @@ def load_library() -> C.CDLL:
         "mm_route_task": [vp, vp, i32, pi32],
         "mm_train_step": [vp, i32, vp, vp, vp, i32, i32, i32, i32, pf32],
         "mm_translate_greedy": [vp, i32, vp, vp, i32, i32, i32, i32, vp, vp],
+        "mm_translate_beam": [vp, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp],
         "mm_last_loss": [vp, pf32],
         "mm_apply_update": [vp, vp, i32, f32],
         "mm_num_modules": [vp, pi32],
@@ -201,6 +202,27 @@ class Context:
                                           mem, _ptr(out_ids), _ptr(out_len))
         self._check(st)
         return out_ids, out_len
+
+    def mm_translate_beam(self, task: int, src_ids, src_lengths, max_new: int, beam: int):
+        """As mm_translate_greedy, with a beam of `beam` hypotheses per sentence.  Returns (ids
+        [B, max_new], produced counts [B], summed log-probabilities [B] float32)."""
+        src_lengths = np.ascontiguousarray(src_lengths, dtype=np.int32)
+        B = src_lengths.shape[0]
+        if isinstance(src_ids, np.ndarray):
+            src = np.ascontiguousarray(src_ids, dtype=np.int32)
+            sp, mem = _ptr(src), MM_HOST
+        else:
+            assert src_ids.is_cuda and src_ids.is_contiguous() and str(src_ids.dtype) == "torch.int32"
+            src = src_ids
+            sp, mem = C.c_void_p(src.data_ptr()), MM_DEVICE
+        assert src.shape[0] == B
+        out_ids = np.zeros((B, max(int(max_new), 0)), dtype=np.int32)
+        out_len = np.zeros(B, dtype=np.int32)
+        out_score = np.zeros(B, dtype=np.float32)
+        st = self.lib.mm_translate_beam(self.handle, task, sp, _ptr(src_lengths), B, src.shape[1], int(max_new),
+                                        int(beam), mem, _ptr(out_ids), _ptr(out_len), _ptr(out_score))
+        self._check(st)
+        return out_ids, out_len, out_score
 
     def mm_last_loss(self) -> float:
         loss = C.c_float(0.0)

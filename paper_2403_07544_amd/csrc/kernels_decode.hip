@@ -50,7 +50,7 @@ template <typename T, int LPK>
 __global__ void __launch_bounds__(256)
 attn_decode_vec_kernel(const T* __restrict__ q, int64_t q_stride, const T* __restrict__ k, const T* __restrict__ v,
                        int64_t ldkv, const int32_t* __restrict__ cu, int64_t seq_rows, int len_uniform,
-                       T* __restrict__ o, int64_t o_stride, float scale) {
+                       T* __restrict__ o, int64_t o_stride, float scale, int rows_per_seq) {
   constexpr int N = Vec16<T>::N, KPP = 64 / LPK, dh = LPK * N, WAVES = 4, UNR = 2, CH = KPP * WAVES * UNR;
   extern __shared__ float smem[];
   float* red = smem;               // [2][WAVES] maxima, sums
@@ -58,8 +58,11 @@ attn_decode_vec_kernel(const T* __restrict__ q, int64_t q_stride, const T* __res
   float* p = accs + WAVES * dh;    // [len] scaled scores
   const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane % LPK, g = lane / LPK;
-  const int64_t row0 = cu ? (int64_t)cu[b] : (int64_t)b * seq_rows;
-  const int len = cu ? cu[b + 1] - cu[b] : len_uniform;
+  // packed keys (cu given): rows_per_seq consecutive query rows (the hypotheses of one sentence)
+  // attend to the same sentence's keys
+  const int sb = b / rows_per_seq;
+  const int64_t row0 = cu ? (int64_t)cu[sb] : (int64_t)b * seq_rows;
+  const int len = cu ? cu[sb + 1] - cu[sb] : len_uniform;
   const int64_t col = (int64_t)h * dh + c * N;
   float qv[N], vv0[UNR][N];
   Vec16<T>::ld(q + (int64_t)b * q_stride + col, qv);
@@ -201,11 +204,124 @@ greedy_pick_kernel(const T* __restrict__ z, int V, int t, int max_new, int eos, 
   }
 }
 
+
+// ---- beam search -----------------------------------------------------------------------------
+// One workgroup per sentence.  The sentence's `beam` hypotheses are rows r0 .. r0 + beam - 1 of z,
+// best first.  Candidates: an unfinished hypothesis i extended by token v scores
+// score[i] + (z[i, v] - logsumexp(z[i, :])); a finished one is carried at its score.  The `beam`
+// best candidates, by (score descending, then hypothesis index, then token id), become the next
+// beam: selection round j takes the best candidate that comes strictly after round j-1's in that
+// order, so every round is a plain block-wide arg-max over all candidates and nothing needs to
+// be marked.  All arithmetic is fp32; both passes over a row evaluate the same expression, so a
+// candidate has the same score in every round.
+constexpr int BEAM_MAX = 8;
+template <typename T>
+__global__ void __launch_bounds__(256)
+beam_select_kernel(const T* __restrict__ z, int V, int beam, int t, int eos, const float* __restrict__ score_in,
+                   const int32_t* __restrict__ done_in, float* __restrict__ score_out, int32_t* __restrict__ done_out,
+                   int32_t* __restrict__ next_tok, int32_t* __restrict__ parent_out, int32_t* __restrict__ hist_tok,
+                   int32_t* __restrict__ hist_parent, int32_t* __restrict__ n_finished, int R) {
+  __shared__ float s_val[256];
+  __shared__ int s_idx[256];
+  __shared__ float s_lse[BEAM_MAX], s_score[BEAM_MAX];
+  __shared__ int s_done[BEAM_MAX];
+  __shared__ float s_prev_val;
+  __shared__ int s_prev_idx;
+  const int b = blockIdx.x, tid = threadIdx.x, r0 = b * beam;
+  if (tid < beam) { s_score[tid] = score_in[r0 + tid]; s_done[tid] = done_in[r0 + tid]; }
+  __syncthreads();
+  for (int i = 0; i < beam; ++i) {        // log of the softmax denominator of every unfinished row
+    if (s_done[i]) continue;              // (uniform over the workgroup)
+    const T* row = z + (int64_t)(r0 + i) * V;
+    float mx = -INFINITY;
+    for (int v = tid; v < V; v += 256) mx = fmaxf(mx, ldf(row + v));
+    s_val[tid] = mx;
+    __syncthreads();
+    for (int w = 128; w; w >>= 1) { if (tid < w) s_val[tid] = fmaxf(s_val[tid], s_val[tid + w]); __syncthreads(); }
+    mx = s_val[0];
+    __syncthreads();
+    float sum = 0.f;
+    for (int v = tid; v < V; v += 256) sum += __expf(ldf(row + v) - mx);
+    s_val[tid] = sum;
+    __syncthreads();
+    for (int w = 128; w; w >>= 1) { if (tid < w) s_val[tid] += s_val[tid + w]; __syncthreads(); }
+    if (tid == 0) s_lse[i] = mx + __logf(s_val[0]);
+    __syncthreads();
+  }
+  int all_done = 1;
+  for (int j = 0; j < beam; ++j) {
+    const float pv = j ? s_prev_val : INFINITY;
+    const int pi = j ? s_prev_idx : -1;
+    float best = -INFINITY;
+    int best_i = 0x7fffffff;
+    auto offer = [&](float sc, int flat) {
+      if (sc != sc) return;                                              // NaN never competes
+      const bool after_prev = j == 0 || sc < pv || (sc == pv && flat > pi);
+      if (after_prev && (sc > best || (sc == best && flat < best_i))) { best = sc; best_i = flat; }
+    };
+    for (int i = 0; i < beam; ++i) {
+      if (s_done[i]) { if (tid == 0) offer(s_score[i], i * V); continue; }
+      const T* row = z + (int64_t)(r0 + i) * V;
+      const float base = s_score[i], lse = s_lse[i];
+      for (int v = tid; v < V; v += 256) offer(base + (ldf(row + v) - lse), i * V + v);
+    }
+    s_val[tid] = best; s_idx[tid] = best_i;
+    __syncthreads();
+    for (int w = 128; w; w >>= 1) {
+      if (tid < w) {
+        const float x = s_val[tid + w];
+        const int i = s_idx[tid + w];
+        if (x > s_val[tid] || (x == s_val[tid] && i < s_idx[tid])) { s_val[tid] = x; s_idx[tid] = i; }
+      }
+      __syncthreads();
+    }
+    const float win = s_val[0];
+    const int flat = s_idx[0];
+    __syncthreads();
+    int fin = 1;
+    if (tid == 0) {
+      s_prev_val = win; s_prev_idx = flat;
+      int i = 0, v = 0;
+      if (flat != 0x7fffffff) { i = flat / V; v = flat - i * V; }        // (no candidate left: repeat row 0, finished)
+      const int carried = flat == 0x7fffffff || s_done[i];
+      fin = carried || v == eos;
+      const int r = r0 + j;
+      score_out[r] = flat == 0x7fffffff ? -INFINITY : win;
+      done_out[r] = fin;
+      next_tok[r] = carried ? 0 : v;
+      parent_out[r] = r0 + i;
+      hist_tok[(int64_t)t * R + r] = carried ? 0 : v;
+      hist_parent[(int64_t)t * R + r] = r0 + i;
+      all_done &= fin;
+    }
+    __syncthreads();
+  }
+  if (tid == 0 && all_done) atomicAdd(&n_finished[t], 1);
+}
+
+// score[r] = 0 for the first row of every sentence's beam, -inf for the others (at the first step
+// all rows of a beam hold the same hypothesis; only one of them may compete).
+__global__ void beam_init_kernel(float* __restrict__ score, int R, int beam) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r < R) score[r] = (r % beam) == 0 ? 0.f : -INFINITY;
+}
+
+// Token caches follow their hypotheses: dst[l][r] = src[l][parent[r]] for the first `bytes` bytes of
+// a row's cache (a multiple of 16), all decoder layers in one launch (grid: rows x layers).
+struct CachePairs { const char* src[BEAM_LAYERS_MAX]; char* dst[BEAM_LAYERS_MAX]; };
+__global__ void __launch_bounds__(256)
+cache_gather_kernel(const CachePairs cp, const int32_t* __restrict__ parent, int64_t row_stride, int64_t bytes) {
+  const int r = blockIdx.x, l = blockIdx.y;
+  const uint4* s = reinterpret_cast<const uint4*>(cp.src[l] + (int64_t)parent[r] * row_stride);
+  uint4* d = reinterpret_cast<uint4*>(cp.dst[l] + (int64_t)r * row_stride);
+  for (int64_t i = threadIdx.x; i < bytes / 16; i += 256) d[i] = s[i];
+}
 }  // namespace
 
 bool launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_stride, const void* k, const void* v,
                         int64_t ldkv, const int32_t* cu, int64_t seq_rows, int len_uniform, int max_len,
-                        void* o, int64_t o_stride, int B, int H, int dh) {
+                        void* o, int64_t o_stride, int B, int H, int dh, int rows_per_seq) {
+  if (rows_per_seq < 1) return false;
   const float scale = 1.0f / sqrtf((float)dh);
   const dim3 grid(H, B);
   const int n = dt == BF16 ? 8 : 4;                       // elements per 16 bytes
@@ -217,7 +333,7 @@ bool launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_strid
 #define MM_AD(T, L)                                                                                              \
   case L:                                                                                                        \
     attn_decode_vec_kernel<T, L><<<grid, 256, lds, st>>>((const T*)q, q_stride, (const T*)k, (const T*)v, ldkv, cu, \
-                                                         seq_rows, len_uniform, (T*)o, o_stride, scale);         \
+                                                         seq_rows, len_uniform, (T*)o, o_stride, scale, rows_per_seq); \
     break;
   if (dt == BF16) {
     switch (lpk) { MM_AD(bf16_t, 2) MM_AD(bf16_t, 4) MM_AD(bf16_t, 8) }
@@ -236,6 +352,35 @@ void launch_greedy_pick(hipStream_t st, Dtype dt, const void* z, int B, int V, i
   else
     greedy_pick_kernel<float><<<B, 256, 0, st>>>((const float*)z, V, t, max_new, eos, cur_tok, done, out_ids,
                                                  out_len, n_done);
+}
+
+bool launch_beam_select(hipStream_t st, Dtype dt, const void* z, int B, int V, int beam, int t, int eos,
+                        const float* score_in, const int32_t* done_in, float* score_out, int32_t* done_out,
+                        int32_t* next_tok, int32_t* parent_out, int32_t* hist_tok, int32_t* hist_parent,
+                        int32_t* n_finished) {
+  if (beam < 1 || beam > BEAM_MAX || (int64_t)beam * V > 0x7ffffffe) return false;
+  const int R = B * beam;
+  if (dt == BF16)
+    beam_select_kernel<bf16_t><<<B, 256, 0, st>>>((const bf16_t*)z, V, beam, t, eos, score_in, done_in, score_out, done_out,
+                                                  next_tok, parent_out, hist_tok, hist_parent, n_finished, R);
+  else
+    beam_select_kernel<float><<<B, 256, 0, st>>>((const float*)z, V, beam, t, eos, score_in, done_in, score_out, done_out,
+                                                 next_tok, parent_out, hist_tok, hist_parent, n_finished, R);
+  return true;
+}
+
+void launch_beam_init(hipStream_t st, float* score, int R, int beam) {
+  beam_init_kernel<<<(R + 255) / 256, 256, 0, st>>>(score, R, beam);
+}
+
+bool launch_cache_gather(hipStream_t st, const char* const* src, char* const* dst, int n_layers, const int32_t* parent,
+                         int R, int64_t row_stride_bytes, int64_t bytes) {
+  if (n_layers < 1 || n_layers > BEAM_LAYERS_MAX || bytes % 16 || row_stride_bytes % 16) return false;
+  CachePairs cp;
+  for (int l = 0; l < n_layers; ++l) { cp.src[l] = src[l]; cp.dst[l] = dst[l]; }
+  for (int l = n_layers; l < BEAM_LAYERS_MAX; ++l) { cp.src[l] = nullptr; cp.dst[l] = nullptr; }
+  cache_gather_kernel<<<dim3(R, n_layers), 256, 0, st>>>(cp, parent, row_stride_bytes, bytes);
+  return true;
 }
 
 }  // namespace mm

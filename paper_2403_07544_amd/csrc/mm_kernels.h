@@ -210,12 +210,31 @@ void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int to
 // Head sizes 16, 32, 64 with 16-byte aligned operands; anything else returns false and launches nothing.
 bool launch_attn_decode(hipStream_t st, Dtype dt, const void* q, int64_t q_stride, const void* k, const void* v,
                         int64_t ldkv, const int32_t* cu, int64_t seq_rows, int len_uniform, int max_len,
-                        void* o, int64_t o_stride, int B, int H, int dh);
+                        void* o, int64_t o_stride, int B, int H, int dh, int rows_per_seq = 1);
+// (rows_per_seq, packed keys only: that many consecutive query rows -- the hypotheses of one
+// sentence's beam -- share the keys of sentence row / rows_per_seq.)
 // Row-wise arg-max of z [B, V] (lowest index among equal entries) for the sentences with
 // done[b] == 0: out_ids[b, t] = cur_tok[b] = token, out_len[b] = t+1; EOS sets done[b] and
 // adds one to n_done[0].
 void launch_greedy_pick(hipStream_t st, Dtype dt, const void* z, int B, int V, int t, int max_new, int eos,
                         int32_t* cur_tok, int32_t* done, int32_t* out_ids, int32_t* out_len, int32_t* n_done);
+
+// Beam search over summed log-probabilities.  Rows r0 = b*beam .. r0+beam-1 of z [B*beam, V] are
+// sentence b's hypotheses, best first.  Writes the next beam: score_out, done_out, next_tok (the
+// token a row feeds back; 0 for a carried finished hypothesis), parent_out (row of z the new row
+// continues), the same two into hist_tok / hist_parent [t][B*beam], and adds one to n_finished[t]
+// for every sentence whose new beam is finished throughout.  In and out arrays must differ.
+// Order among equal scores: lower hypothesis row, then lower token id.  beam <= BEAM_MAX (8).
+bool launch_beam_select(hipStream_t st, Dtype dt, const void* z, int B, int V, int beam, int t, int eos,
+                        const float* score_in, const int32_t* done_in, float* score_out, int32_t* done_out,
+                        int32_t* next_tok, int32_t* parent_out, int32_t* hist_tok, int32_t* hist_parent,
+                        int32_t* n_finished);
+// score[r] = 0 where r % beam == 0, -infinity elsewhere
+void launch_beam_init(hipStream_t st, float* score, int R, int beam);
+// dst[l] row r <- src[l] row parent[r], first `bytes` bytes of each row, for n_layers <= 32 buffers
+constexpr int BEAM_LAYERS_MAX = 32;
+bool launch_cache_gather(hipStream_t st, const char* const* src, char* const* dst, int n_layers, const int32_t* parent,
+                         int R, int64_t row_stride_bytes, int64_t bytes);
 
 // fp32 -> bf16 copy (working weights) and fill
 void launch_to_bf16(hipStream_t st, const float* src, bf16_t* dst, int64_t n);

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/mammoth_hip.h"
@@ -819,10 +820,17 @@ bool valid_module(mm_ctx* c, int id) { return id >= 0 && id < (int)c->mods.size(
 // so far ([B][max_new][3d]) and the key/value projection of the encoder output, so a step
 // works on one new row per sentence.  Runs twice like the training step: measuring, then real.
 // ---------------------------------------------------------------------------------------------
-struct TranslateOut { int32_t* ids; int32_t* len; };
+struct TranslateOut {
+  int32_t* ids; int32_t* len;                       // greedy search: produced ids [B][max_new], counts [B]
+  // beam search: per step and row the token and the row of the step before it continues; the final
+  // scores (best hypothesis of sentence b in row b * beam); number of steps taken
+  int32_t* hist_tok; int32_t* hist_parent; float* score; int steps;
+};
 
+// beam == 0: greedy search (arg-max of the logits).  beam >= 1: beam search over summed
+// log-probabilities with beam rows per sentence.
 mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src_lens, int max_new,
-                        TranslateOut& out) {
+                        TranslateOut& out, int beam) {
   Step s;
   s.c = c; s.run = Run{c, dry}; s.rt = &rt;
   s.d = c->cfg.d_model; s.H = c->cfg.n_heads; s.F = c->cfg.d_ff; s.V = c->cfg.vocab; s.dh = s.d / s.H;
@@ -833,7 +841,10 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
     s.sum_ss += sl * sl; s.sum_us += sl; s.sum_uu += 1;
     if (sl > s.max_s) s.max_s = (int)sl;
   }
-  const int d = s.d, S = s.S, B = s.B, V = s.V, H = s.H, dh = s.dh;
+  const int d = s.d, S = s.S, V = s.V, H = s.H, dh = s.dh;
+  const int n_sent = s.B;                     // sentences
+  const int kb = beam > 0 ? beam : 1;         // decoder rows per sentence
+  const int B = n_sent * kb;                  // decoder rows (the name the decoding code below uses)
   const size_t esz = s.esz;
   Run& run = s.run;
   if (!dry) run.mark();
@@ -863,7 +874,7 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
   run.ln_fwd(x, pv_encf.V(0), pv_encf.V(1), mem, s.f32(S), s.f32(S), S);
 
   // ---------------- per decoder layer: key/value projection of the encoder output, token cache ----
-  struct DecLayer { PV pv; bool has_adapter; PV apv; char* kv_mem; char* cache; };
+  struct DecLayer { PV pv; bool has_adapter; PV apv; char* kv_mem; char* cache; char* cache_alt; };
   std::vector<DecLayer> layers;
   std::vector<GemmParams> kv_jobs;
   li = 0;
@@ -876,6 +887,7 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
       if (L.has_adapter) L.apv = PV{c, &c->mods[rt.ad_dec], li * ADP_T};
       L.kv_mem = (char*)s.act((size_t)S * 2 * d);
       L.cache = (char*)s.act((size_t)B * max_new * 3 * d);
+      L.cache_alt = beam > 0 ? (char*)s.act((size_t)B * max_new * 3 * d) : nullptr;   // hypotheses move between rows
       kv_jobs.push_back(s.gp_cross_kv(L.pv, 10, mem, L.kv_mem));
       layers.push_back(L);
     }
@@ -895,6 +907,25 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
   if (!dry) {
     launch_fill_i32(c->st, cur_tok, B, 1 /* BOS */);
     launch_fill_i32(c->st, done, 2 * (size_t)B + 1 + (size_t)B * max_new, 0);   // done, len, n_done, ids
+  }
+  // beam search state: scores and finished flags in two copies (a step reads one and writes the
+  // other), the row each new row continues, and the per-step history the host walks back at the end
+  float* score[2] = {nullptr, nullptr};
+  int32_t* bdone[2] = {nullptr, nullptr};
+  int32_t* parent = nullptr; int32_t* n_fin = nullptr;
+  if (beam > 0) {
+    if ((int)layers.size() > BEAM_LAYERS_MAX) return fail(c, MM_EINVAL, "beam search supports at most %d decoder layers", BEAM_LAYERS_MAX);
+    char* bs = (char*)c->ws.take(((size_t)5 * B + max_new + 2 * (size_t)B * max_new) * 4);
+    score[0] = (float*)bs; score[1] = score[0] + B;
+    bdone[0] = (int32_t*)(score[1] + B); bdone[1] = bdone[0] + B;
+    parent = bdone[1] + B;
+    n_fin = parent + B;
+    out.hist_tok = n_fin + max_new;
+    out.hist_parent = out.hist_tok + (size_t)B * max_new;
+    if (!dry) {
+      launch_beam_init(c->st, score[0], B, kb);
+      launch_fill_i32(c->st, bdone[0], (size_t)3 * B + max_new + 2 * (size_t)B * max_new, 0);
+    }
   }
   int32_t* n_done_host = (int32_t*)c->result_host + 8;
   const int64_t row3 = (int64_t)3 * d;                 // one cached row: q | k | v
@@ -968,7 +999,7 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
       run.gemm(p);
       o = s.act((size_t)B * d);
       if (!dry && !launch_attn_decode(c->st, c->dt, q, d, L.kv_mem, L.kv_mem + (size_t)d * esz, 2 * d, c->cu_s, 0, 0,
-                                      s.max_s, o, d, B, H, dh))
+                                      s.max_s, o, d, B, H, dh, kb))
         return fail(c, MM_EINVAL, "decoding attention does not support head size %d", dh);
       y = proj_out(o, d, pv.W(18), pv.V(19), x_full);
       y = ffn_block(pv, 20, y, s.F);
@@ -981,6 +1012,28 @@ mm_status run_translate(mm_ctx* c, const Route& rt, bool dry, const int32_t* src
     p.bias = pv_gen.V(1);
     run.gemm(p);
     if (dry) break;                                    // one step measures them all
+    if (beam > 0) {
+      const int cur = t & 1, nxt = cur ^ 1;
+      if (!launch_beam_select(c->st, c->dt, z, n_sent, V, kb, t, 2 /* EOS */, score[cur], bdone[cur], score[nxt], bdone[nxt],
+                              cur_tok, parent, out.hist_tok, out.hist_parent, n_fin))
+        return fail(c, MM_EINVAL, "beam width %d is not supported", kb);
+      out.score = score[nxt];
+      out.steps = t + 1;
+      if (t + 1 < max_new) {                           // the caches follow their hypotheses
+        const char* src[BEAM_LAYERS_MAX]; char* dst[BEAM_LAYERS_MAX];
+        for (size_t l = 0; l < layers.size(); ++l) { src[l] = layers[l].cache; dst[l] = layers[l].cache_alt; }
+        if (!launch_cache_gather(c->st, src, dst, (int)layers.size(), parent, B, seq3 * (int64_t)esz,
+                                 (int64_t)(t + 1) * row3 * (int64_t)esz))
+          return fail(c, MM_EINVAL, "token cache rows are not multiples of 16 bytes");
+        for (DecLayer& L : layers) std::swap(L.cache, L.cache_alt);
+      }
+      if ((t & 7) == 7 && t + 1 < max_new) {           // now and then: is every beam finished?
+        HIP_TRY(c, hipMemcpyAsync(n_done_host, n_fin + t, 4, hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(c, hipStreamSynchronize(c->st));
+        if (*n_done_host >= n_sent) break;
+      }
+      continue;
+    }
     launch_greedy_pick(c->st, c->dt, z, B, V, t, max_new, 2 /* EOS */, cur_tok, done, out.ids, out.len, n_done);
     if ((t & 7) == 7 && t + 1 < max_new) {             // now and then: has every sentence finished?
       HIP_TRY(c, hipMemcpyAsync(n_done_host, n_done, 4, hipMemcpyDeviceToHost, c->st));
@@ -1298,10 +1351,16 @@ mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const i
   return MM_OK;
 }
 
-mm_status mm_translate_greedy(mm_ctx* c, int32_t task, const int32_t* src_ids, const int32_t* src_lengths, int32_t B,
-                              int32_t S_max, int32_t max_new, int32_t ids_mem, int32_t* out_ids, int32_t* out_lengths) {
+}  // extern "C"
+
+namespace {
+// Both searches: beam == 0 greedy, beam >= 1 beam search (out_scores may be NULL).
+mm_status translate_impl(mm_ctx* c, int32_t task, const int32_t* src_ids, const int32_t* src_lengths, int32_t B,
+                         int32_t S_max, int32_t max_new, int32_t ids_mem, int beam, int32_t* out_ids,
+                         int32_t* out_lengths, float* out_scores) {
   if (!c) return MM_EINVAL;
   if (!src_ids || !src_lengths || !out_ids || !out_lengths) return fail(c, MM_EINVAL, "null pointer");
+  if (beam < 0 || beam > 8) return fail(c, MM_EINVAL, "beam width %d outside [1, 8]", beam);
   if (task < 0 || task >= (int)c->routes.size()) return fail(c, MM_EINVAL, "unknown task %d", task);
   if (ids_mem != MM_HOST && ids_mem != MM_DEVICE) return fail(c, MM_EINVAL, "ids_mem must be MM_HOST or MM_DEVICE");
   if (B < 1 || S_max < 1 || max_new < 1) return fail(c, MM_EINVAL, "empty batch");
@@ -1313,8 +1372,9 @@ mm_status mm_translate_greedy(mm_ctx* c, int32_t task, const int32_t* src_ids, c
     if (sl < 1 || sl > S_max) return fail(c, MM_ERANGE, "sentence %d has length %d outside [1,%d]", b, sl, S_max);
     S += sl;
   }
-  if (S > c->cfg.max_batch_tokens || B > c->cfg.max_batch_tokens)
-    return fail(c, MM_ERANGE, "batch holds %lld source tokens, limit %d", (long long)S, c->cfg.max_batch_tokens);
+  if (S > c->cfg.max_batch_tokens || (int64_t)B * (beam > 0 ? beam : 1) > c->cfg.max_batch_tokens)
+    return fail(c, MM_ERANGE, "batch holds %lld source tokens and %lld decoder rows, limit %d", (long long)S,
+                (long long)B * (beam > 0 ? beam : 1), c->cfg.max_batch_tokens);
   if (ids_mem == MM_HOST) {
     const int V = c->cfg.vocab;
     for (int b = 0; b < B; ++b)
@@ -1354,8 +1414,8 @@ mm_status mm_translate_greedy(mm_ctx* c, int32_t task, const int32_t* src_ids, c
   const int32_t* tgt_dev = c->ids_dev + n_src;
   c->B = B; c->S_max = S_max; c->T_max = 2; c->S = (int)S; c->U = B;
   const Route& rt = c->routes[task];
-  TranslateOut out{nullptr, nullptr};
-  run_translate(c, rt, true, src_lengths, max_new, out);
+  TranslateOut out{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+  run_translate(c, rt, true, src_lengths, max_new, out, beam);
   s = ensure_ws(c, c->ws.high);
   if (s != MM_OK) return s;
   // lengths and both prefix sums lie back to back in the staging block and travel in one copy
@@ -1365,19 +1425,60 @@ mm_status mm_translate_greedy(mm_ctx* c, int32_t task, const int32_t* src_ids, c
   launch_fill_i32(c->st, c->flag, 1, 0);
   launch_pack_ids(c->st, src_dev, tgt_dev, c->lens, c->cu_s, c->cu_u, B, S_max, 2, c->cfg.vocab, c->src_tok,
                   c->src_pos, c->dec_tok, c->dec_pos, c->label, c->flag);
-  s = run_translate(c, rt, false, src_lengths, max_new, out);
+  s = run_translate(c, rt, false, src_lengths, max_new, out, beam);
   if (s != MM_OK) return s;
   HIP_TRY(c, hipGetLastError());
   int32_t* flag_host = (int32_t*)c->result_host + 9;
   HIP_TRY(c, hipMemcpyAsync(flag_host, c->flag, 4, hipMemcpyDeviceToHost, c->st));
-  HIP_TRY(c, hipMemcpyAsync(out_ids, out.ids, (size_t)B * max_new * 4, hipMemcpyDeviceToHost, c->st));
-  HIP_TRY(c, hipMemcpyAsync(out_lengths, out.len, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
-  HIP_TRY(c, hipStreamSynchronize(c->st));
+  if (beam == 0) {
+    HIP_TRY(c, hipMemcpyAsync(out_ids, out.ids, (size_t)B * max_new * 4, hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipMemcpyAsync(out_lengths, out.len, (size_t)B * 4, hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+  } else {
+    // Walk the best hypothesis of every sentence (row b * beam of the last beam) back through the
+    // steps: each step stored, per row, its token and the row of the step before that it continues.
+    const size_t R = (size_t)B * beam, n_hist = R * (size_t)out.steps;
+    std::vector<int32_t> tok(n_hist), par(n_hist);
+    std::vector<float> sc(R);
+    HIP_TRY(c, hipMemcpyAsync(tok.data(), out.hist_tok, n_hist * 4, hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipMemcpyAsync(par.data(), out.hist_parent, n_hist * 4, hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipMemcpyAsync(sc.data(), out.score, R * 4, hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    std::vector<int32_t> seq(out.steps);
+    for (int b = 0; b < B; ++b) {
+      int r = b * beam;
+      for (int t = out.steps - 1; t >= 0; --t) {
+        if (r < b * beam || r >= (b + 1) * beam) return fail(c, MM_EHIP, "beam history leaves its sentence");
+        seq[t] = tok[(size_t)t * R + r];
+        r = par[(size_t)t * R + r];
+      }
+      int n = 0;
+      while (n < out.steps) { ++n; if (seq[n - 1] == 2 /* EOS */) break; }   // carried steps follow the EOS
+      for (int t = 0; t < max_new; ++t) out_ids[(size_t)b * max_new + t] = t < n ? seq[t] : 0;
+      out_lengths[b] = n;
+      if (out_scores) out_scores[b] = sc[(size_t)b * beam];
+    }
+  }
   if (c->prof && c->prof_recs.size() > 8192) collect_profile(c);
   if (*flag_host != 0)
     return fail(c, MM_ERANGE, *flag_host & 1 ? "token id outside [0, vocab) (found on the device); output is meaningless"
                                              : "non-pad id after the end of a sentence (found on the device); output is meaningless");
   return MM_OK;
+}
+}  // namespace
+
+extern "C" {
+
+mm_status mm_translate_greedy(mm_ctx* c, int32_t task, const int32_t* src_ids, const int32_t* src_lengths, int32_t B,
+                              int32_t S_max, int32_t max_new, int32_t ids_mem, int32_t* out_ids, int32_t* out_lengths) {
+  return translate_impl(c, task, src_ids, src_lengths, B, S_max, max_new, ids_mem, 0, out_ids, out_lengths, nullptr);
+}
+
+mm_status mm_translate_beam(mm_ctx* c, int32_t task, const int32_t* src_ids, const int32_t* src_lengths, int32_t B,
+                            int32_t S_max, int32_t max_new, int32_t beam, int32_t ids_mem, int32_t* out_ids,
+                            int32_t* out_lengths, float* out_scores) {
+  if (c && beam < 1) return fail(c, MM_EINVAL, "beam width %d outside [1, 8]", beam);
+  return translate_impl(c, task, src_ids, src_lengths, B, S_max, max_new, ids_mem, beam, out_ids, out_lengths, out_scores);
 }
 
 mm_status mm_last_loss(mm_ctx* c, float* out_loss) {
