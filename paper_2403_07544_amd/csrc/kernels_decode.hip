@@ -210,81 +210,134 @@ greedy_pick_kernel(const T* __restrict__ z, int V, int t, int max_new, int eos, 
 // best first.  Candidates: an unfinished hypothesis i extended by token v scores
 // score[i] + (z[i, v] - logsumexp(z[i, :])); a finished one is carried at its score.  The `beam`
 // best candidates, by (score descending, then hypothesis index, then token id), become the next
-// beam: selection round j takes the best candidate that comes strictly after round j-1's in that
-// order, so every round is a plain block-wide arg-max over all candidates and nothing needs to
-// be marked.  All arithmetic is fp32; both passes over a row evaluate the same expression, so a
-// candidate has the same score in every round.
+// beam.  Two sweeps over the rows: the softmax denominators, then the selection (each thread keeps
+// its own best `beam` candidates, the workgroup merges the lists).  All arithmetic is fp32.
 constexpr int BEAM_MAX = 8;
+constexpr int BEAM_THREADS = 1024;   // per sentence: the sweeps over beam x V logits are the kernel's time
+// (score, flat index) order of the candidates: higher score first, then the lower flat index
+__device__ __forceinline__ bool cand_before(float sa, int fa, float sb, int fb) {
+  return sa > sb || (sa == sb && fa < fb);
+}
 template <typename T>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(BEAM_THREADS)
 beam_select_kernel(const T* __restrict__ z, int V, int beam, int t, int eos, const float* __restrict__ score_in,
                    const int32_t* __restrict__ done_in, float* __restrict__ score_out, int32_t* __restrict__ done_out,
                    int32_t* __restrict__ next_tok, int32_t* __restrict__ parent_out, int32_t* __restrict__ hist_tok,
                    int32_t* __restrict__ hist_parent, int32_t* __restrict__ n_finished, int R) {
-  __shared__ float s_val[256];
-  __shared__ int s_idx[256];
+  __shared__ float s_val[BEAM_THREADS];
+  __shared__ float s_aux[BEAM_THREADS];
+  __shared__ int s_idx[BEAM_THREADS];
+  __shared__ int s_who[BEAM_THREADS];
   __shared__ float s_lse[BEAM_MAX], s_score[BEAM_MAX];
   __shared__ int s_done[BEAM_MAX];
-  __shared__ float s_prev_val;
-  __shared__ int s_prev_idx;
+  constexpr int N = Vec16<T>::N;
   const int b = blockIdx.x, tid = threadIdx.x, r0 = b * beam;
+  const bool vec = V % N == 0 && (reinterpret_cast<uintptr_t>(z) & 15) == 0;   // rows start on 16-byte boundaries
   if (tid < beam) { s_score[tid] = score_in[r0 + tid]; s_done[tid] = done_in[r0 + tid]; }
   __syncthreads();
-  for (int i = 0; i < beam; ++i) {        // log of the softmax denominator of every unfinished row
+  // Pass 1, per unfinished row: log of the softmax denominator, running maximum and rescaled sum
+  // in one sweep; the threads' (max, sum) pairs are combined the same way.
+  for (int i = 0; i < beam; ++i) {
     if (s_done[i]) continue;              // (uniform over the workgroup)
     const T* row = z + (int64_t)(r0 + i) * V;
-    float mx = -INFINITY;
-    for (int v = tid; v < V; v += 256) mx = fmaxf(mx, ldf(row + v));
-    s_val[tid] = mx;
+    float mx = -INFINITY, sum = 0.f;
+    auto take = [&](float x) {
+      if (x > mx) { sum = sum * __expf(mx - x) + 1.f; mx = x; }
+      else if (x == x && mx > -INFINITY) sum += __expf(x - mx);   // (NaN and a leading -inf contribute nothing)
+    };
+    if (vec) {
+      for (int v0 = tid * N; v0 < V; v0 += BEAM_THREADS * N) {
+        float x[N];
+        Vec16<T>::ld(row + v0, x);
+#pragma unroll
+        for (int e = 0; e < N; ++e) take(x[e]);
+      }
+    } else {
+      for (int v = tid; v < V; v += BEAM_THREADS) take(ldf(row + v));
+    }
+    s_val[tid] = mx; s_aux[tid] = sum;
     __syncthreads();
-    for (int w = 128; w; w >>= 1) { if (tid < w) s_val[tid] = fmaxf(s_val[tid], s_val[tid + w]); __syncthreads(); }
-    mx = s_val[0];
+    for (int w = BEAM_THREADS / 2; w; w >>= 1) {
+      if (tid < w) {
+        const float ma = s_val[tid], mb = s_val[tid + w];
+        const float m = fmaxf(ma, mb);
+        float acc = 0.f;
+        if (ma > -INFINITY) acc += s_aux[tid] * __expf(ma - m);
+        if (mb > -INFINITY) acc += s_aux[tid + w] * __expf(mb - m);
+        s_val[tid] = m; s_aux[tid] = acc;
+      }
+      __syncthreads();
+    }
+    if (tid == 0) s_lse[i] = s_val[0] + __logf(s_aux[0]);
     __syncthreads();
-    float sum = 0.f;
-    for (int v = tid; v < V; v += 256) sum += __expf(ldf(row + v) - mx);
-    s_val[tid] = sum;
-    __syncthreads();
-    for (int w = 128; w; w >>= 1) { if (tid < w) s_val[tid] += s_val[tid + w]; __syncthreads(); }
-    if (tid == 0) s_lse[i] = mx + __logf(s_val[0]);
-    __syncthreads();
+  }
+  // Pass 2: every thread keeps the best `beam` of the candidates it sees (all rows), sorted, in
+  // registers (slots past `beam` stay empty); then `beam` rounds of a block-wide arg-max over the
+  // threads' first entries, the winner's list moving up by one.
+  float cs[BEAM_MAX];
+  int cf[BEAM_MAX];
+#pragma unroll
+  for (int q = 0; q < BEAM_MAX; ++q) { cs[q] = -INFINITY; cf[q] = 0x7fffffff; }
+  int filled = 0;                                          // entries held, at most beam
+  auto offer = [&](float sc, int flat) {
+    if (sc != sc) return;                                  // NaN never competes
+    // position of the last slot in use once this candidate is in: compare with the current last
+    bool in = filled < beam;
+#pragma unroll
+    for (int q = 0; q < BEAM_MAX; ++q)
+      if (q == beam - 1 && !in) in = cand_before(sc, flat, cs[q], cf[q]);
+    if (!in) return;
+    if (filled < beam) ++filled;
+    // put it into the last used slot, then let it rise
+#pragma unroll
+    for (int q = 0; q < BEAM_MAX; ++q)
+      if (q == filled - 1) { cs[q] = sc; cf[q] = flat; }
+#pragma unroll
+    for (int q = BEAM_MAX - 1; q > 0; --q) {
+      if (q < filled && cand_before(cs[q], cf[q], cs[q - 1], cf[q - 1])) {
+        const float ts = cs[q]; cs[q] = cs[q - 1]; cs[q - 1] = ts;
+        const int tf = cf[q]; cf[q] = cf[q - 1]; cf[q - 1] = tf;
+      }
+    }
+  };
+  for (int i = 0; i < beam; ++i) {
+    if (s_done[i]) { if (tid == 0) offer(s_score[i], i * V); continue; }   // carried at its score
+    const T* row = z + (int64_t)(r0 + i) * V;
+    const float base = s_score[i], lse = s_lse[i];
+    if (vec) {
+      for (int v0 = tid * N; v0 < V; v0 += BEAM_THREADS * N) {
+        float x[N];
+        Vec16<T>::ld(row + v0, x);
+#pragma unroll
+        for (int e = 0; e < N; ++e) offer(base + (x[e] - lse), i * V + v0 + e);
+      }
+    } else {
+      for (int v = tid; v < V; v += BEAM_THREADS) offer(base + (ldf(row + v) - lse), i * V + v);
+    }
   }
   int all_done = 1;
   for (int j = 0; j < beam; ++j) {
-    const float pv = j ? s_prev_val : INFINITY;
-    const int pi = j ? s_prev_idx : -1;
-    float best = -INFINITY;
-    int best_i = 0x7fffffff;
-    auto offer = [&](float sc, int flat) {
-      if (sc != sc) return;                                              // NaN never competes
-      const bool after_prev = j == 0 || sc < pv || (sc == pv && flat > pi);
-      if (after_prev && (sc > best || (sc == best && flat < best_i))) { best = sc; best_i = flat; }
-    };
-    for (int i = 0; i < beam; ++i) {
-      if (s_done[i]) { if (tid == 0) offer(s_score[i], i * V); continue; }
-      const T* row = z + (int64_t)(r0 + i) * V;
-      const float base = s_score[i], lse = s_lse[i];
-      for (int v = tid; v < V; v += 256) offer(base + (ldf(row + v) - lse), i * V + v);
-    }
-    s_val[tid] = best; s_idx[tid] = best_i;
+    s_val[tid] = cs[0]; s_idx[tid] = cf[0]; s_who[tid] = tid;
     __syncthreads();
-    for (int w = 128; w; w >>= 1) {
-      if (tid < w) {
-        const float x = s_val[tid + w];
-        const int i = s_idx[tid + w];
-        if (x > s_val[tid] || (x == s_val[tid] && i < s_idx[tid])) { s_val[tid] = x; s_idx[tid] = i; }
+    for (int w = BEAM_THREADS / 2; w; w >>= 1) {
+      if (tid < w && cand_before(s_val[tid + w], s_idx[tid + w], s_val[tid], s_idx[tid])) {
+        s_val[tid] = s_val[tid + w]; s_idx[tid] = s_idx[tid + w]; s_who[tid] = s_who[tid + w];
       }
       __syncthreads();
     }
     const float win = s_val[0];
-    const int flat = s_idx[0];
+    const int flat = s_idx[0], who = s_who[0];
     __syncthreads();
-    int fin = 1;
+    if (tid == who && flat != 0x7fffffff) {                // the winner's list moves up
+#pragma unroll
+      for (int q = 0; q + 1 < BEAM_MAX; ++q) { cs[q] = cs[q + 1]; cf[q] = cf[q + 1]; }
+      cs[BEAM_MAX - 1] = -INFINITY; cf[BEAM_MAX - 1] = 0x7fffffff;
+    }
     if (tid == 0) {
-      s_prev_val = win; s_prev_idx = flat;
       int i = 0, v = 0;
       if (flat != 0x7fffffff) { i = flat / V; v = flat - i * V; }        // (no candidate left: repeat row 0, finished)
       const int carried = flat == 0x7fffffff || s_done[i];
-      fin = carried || v == eos;
+      const int fin = carried || v == eos;
       const int r = r0 + j;
       score_out[r] = flat == 0x7fffffff ? -INFINITY : win;
       done_out[r] = fin;
@@ -294,7 +347,6 @@ beam_select_kernel(const T* __restrict__ z, int V, int beam, int t, int eos, con
       hist_parent[(int64_t)t * R + r] = r0 + i;
       all_done &= fin;
     }
-    __syncthreads();
   }
   if (tid == 0 && all_done) atomicAdd(&n_finished[t], 1);
 }
@@ -361,10 +413,10 @@ bool launch_beam_select(hipStream_t st, Dtype dt, const void* z, int B, int V, i
   if (beam < 1 || beam > BEAM_MAX || (int64_t)beam * V > 0x7ffffffe) return false;
   const int R = B * beam;
   if (dt == BF16)
-    beam_select_kernel<bf16_t><<<B, 256, 0, st>>>((const bf16_t*)z, V, beam, t, eos, score_in, done_in, score_out, done_out,
+    beam_select_kernel<bf16_t><<<B, BEAM_THREADS, 0, st>>>((const bf16_t*)z, V, beam, t, eos, score_in, done_in, score_out, done_out,
                                                   next_tok, parent_out, hist_tok, hist_parent, n_finished, R);
   else
-    beam_select_kernel<float><<<B, 256, 0, st>>>((const float*)z, V, beam, t, eos, score_in, done_in, score_out, done_out,
+    beam_select_kernel<float><<<B, BEAM_THREADS, 0, st>>>((const float*)z, V, beam, t, eos, score_in, done_in, score_out, done_out,
                                                  next_tok, parent_out, hist_tok, hist_parent, n_finished, R);
   return true;
 }
