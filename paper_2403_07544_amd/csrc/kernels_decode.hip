@@ -1,6 +1,7 @@
-// Kernels of routed greedy translation (paper section 3.2: a task is translated with its own
-// modules): attention of one new query per sentence over cached keys and values, and the
-// pick of the next token.  Everything else of a decoding step reuses the training kernels.
+// Kernels of routed translation (paper section 3.2: a task is translated with its own modules):
+// attention of one new query per row over cached keys and values, the greedy pick of the next
+// token, and for beam search the selection of the next beam and the move of the token caches to
+// their new hypotheses.  Everything else of a decoding step reuses the training kernels.
 #include <hip/hip_runtime.h>
 
 #include "mm_kernels.h"
