@@ -219,7 +219,8 @@ constexpr int BEAM_THREADS = 1024;   // per sentence: the sweeps over beam x V l
 __device__ __forceinline__ bool cand_before(float sa, int fa, float sb, int fb) {
   return sa > sb || (sa == sb && fa < fb);
 }
-template <typename T>
+// K: entries of a thread's candidate list, a compile-time size >= beam (1, 2, 4 or 8).
+template <typename T, int K>
 __global__ void __launch_bounds__(BEAM_THREADS)
 beam_select_kernel(const T* __restrict__ z, int V, int beam, int t, int eos, const float* __restrict__ score_in,
                    const int32_t* __restrict__ done_in, float* __restrict__ score_out, int32_t* __restrict__ done_out,
@@ -247,11 +248,21 @@ beam_select_kernel(const T* __restrict__ z, int V, int beam, int t, int eos, con
       else if (x == x && mx > -INFINITY) sum += __expf(x - mx);   // (NaN and a leading -inf contribute nothing)
     };
     if (vec) {
-      for (int v0 = tid * N; v0 < V; v0 += BEAM_THREADS * N) {
-        float x[N];
-        Vec16<T>::ld(row + v0, x);
+      // four loads in flight per thread: a sweep is bound by load latency, not by bytes
+      for (int v0 = tid * N; v0 < V; v0 += 4 * BEAM_THREADS * N) {
+        float x[4][N];
 #pragma unroll
-        for (int e = 0; e < N; ++e) take(x[e]);
+        for (int u = 0; u < 4; ++u) {
+          const int v = v0 + u * BEAM_THREADS * N;
+          Vec16<T>::ld(row + (v < V ? v : v0), x[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (v0 + u * BEAM_THREADS * N < V) {
+#pragma unroll
+            for (int e = 0; e < N; ++e) take(x[u][e]);
+          }
+        }
       }
     } else {
       for (int v = tid; v < V; v += BEAM_THREADS) take(ldf(row + v));
@@ -272,30 +283,21 @@ beam_select_kernel(const T* __restrict__ z, int V, int beam, int t, int eos, con
     if (tid == 0) s_lse[i] = s_val[0] + __logf(s_aux[0]);
     __syncthreads();
   }
-  // Pass 2: every thread keeps the best `beam` of the candidates it sees (all rows), sorted, in
-  // registers (slots past `beam` stay empty); then `beam` rounds of a block-wide arg-max over the
-  // threads' first entries, the winner's list moving up by one.
-  float cs[BEAM_MAX];
-  int cf[BEAM_MAX];
+  // Pass 2: every thread keeps the best K >= beam of the candidates it sees (all rows), sorted, in
+  // registers; then `beam` rounds of a block-wide arg-max over the threads' first entries, the
+  // winner's list moving up by one.
+  float cs[K];
+  int cf[K];
 #pragma unroll
-  for (int q = 0; q < BEAM_MAX; ++q) { cs[q] = -INFINITY; cf[q] = 0x7fffffff; }
-  int filled = 0;                                          // entries held, at most beam
+  for (int q = 0; q < K; ++q) { cs[q] = -INFINITY; cf[q] = 0x7fffffff; }
   auto offer = [&](float sc, int flat) {
-    if (sc != sc) return;                                  // NaN never competes
-    // position of the last slot in use once this candidate is in: compare with the current last
-    bool in = filled < beam;
+    // one comparison with the list's last entry decides for nearly every candidate (an empty slot
+    // loses to everything; NaN compares false)
+    if (!cand_before(sc, flat, cs[K - 1], cf[K - 1])) return;
+    cs[K - 1] = sc; cf[K - 1] = flat;
 #pragma unroll
-    for (int q = 0; q < BEAM_MAX; ++q)
-      if (q == beam - 1 && !in) in = cand_before(sc, flat, cs[q], cf[q]);
-    if (!in) return;
-    if (filled < beam) ++filled;
-    // put it into the last used slot, then let it rise
-#pragma unroll
-    for (int q = 0; q < BEAM_MAX; ++q)
-      if (q == filled - 1) { cs[q] = sc; cf[q] = flat; }
-#pragma unroll
-    for (int q = BEAM_MAX - 1; q > 0; --q) {
-      if (q < filled && cand_before(cs[q], cf[q], cs[q - 1], cf[q - 1])) {
+    for (int q = K - 1; q > 0; --q) {                      // let it rise
+      if (cand_before(cs[q], cf[q], cs[q - 1], cf[q - 1])) {
         const float ts = cs[q]; cs[q] = cs[q - 1]; cs[q - 1] = ts;
         const int tf = cf[q]; cf[q] = cf[q - 1]; cf[q - 1] = tf;
       }
@@ -306,11 +308,21 @@ beam_select_kernel(const T* __restrict__ z, int V, int beam, int t, int eos, con
     const T* row = z + (int64_t)(r0 + i) * V;
     const float base = s_score[i], lse = s_lse[i];
     if (vec) {
-      for (int v0 = tid * N; v0 < V; v0 += BEAM_THREADS * N) {
-        float x[N];
-        Vec16<T>::ld(row + v0, x);
+      for (int v0 = tid * N; v0 < V; v0 += 4 * BEAM_THREADS * N) {
+        float x[4][N];
 #pragma unroll
-        for (int e = 0; e < N; ++e) offer(base + (x[e] - lse), i * V + v0 + e);
+        for (int u = 0; u < 4; ++u) {
+          const int v = v0 + u * BEAM_THREADS * N;
+          Vec16<T>::ld(row + (v < V ? v : v0), x[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int v = v0 + u * BEAM_THREADS * N;
+          if (v < V) {
+#pragma unroll
+            for (int e = 0; e < N; ++e) offer(base + (x[u][e] - lse), i * V + v + e);
+          }
+        }
       }
     } else {
       for (int v = tid; v < V; v += BEAM_THREADS) offer(base + (ldf(row + v) - lse), i * V + v);
@@ -331,8 +343,8 @@ beam_select_kernel(const T* __restrict__ z, int V, int beam, int t, int eos, con
     __syncthreads();
     if (tid == who && flat != 0x7fffffff) {                // the winner's list moves up
 #pragma unroll
-      for (int q = 0; q + 1 < BEAM_MAX; ++q) { cs[q] = cs[q + 1]; cf[q] = cf[q + 1]; }
-      cs[BEAM_MAX - 1] = -INFINITY; cf[BEAM_MAX - 1] = 0x7fffffff;
+      for (int q = 0; q + 1 < K; ++q) { cs[q] = cs[q + 1]; cf[q] = cf[q + 1]; }
+      cs[K - 1] = -INFINITY; cf[K - 1] = 0x7fffffff;
     }
     if (tid == 0) {
       int i = 0, v = 0;
@@ -413,12 +425,16 @@ bool launch_beam_select(hipStream_t st, Dtype dt, const void* z, int B, int V, i
                         int32_t* n_finished) {
   if (beam < 1 || beam > BEAM_MAX || (int64_t)beam * V > 0x7ffffffe) return false;
   const int R = B * beam;
-  if (dt == BF16)
-    beam_select_kernel<bf16_t><<<B, BEAM_THREADS, 0, st>>>((const bf16_t*)z, V, beam, t, eos, score_in, done_in, score_out, done_out,
-                                                  next_tok, parent_out, hist_tok, hist_parent, n_finished, R);
-  else
-    beam_select_kernel<float><<<B, BEAM_THREADS, 0, st>>>((const float*)z, V, beam, t, eos, score_in, done_in, score_out, done_out,
-                                                 next_tok, parent_out, hist_tok, hist_parent, n_finished, R);
+#define MM_BS(T, K)                                                                                               \
+  beam_select_kernel<T, K><<<B, BEAM_THREADS, 0, st>>>((const T*)z, V, beam, t, eos, score_in, done_in, score_out, \
+                                                       done_out, next_tok, parent_out, hist_tok, hist_parent,      \
+                                                       n_finished, R)
+  if (dt == BF16) {
+    if (beam == 1) MM_BS(bf16_t, 1); else if (beam == 2) MM_BS(bf16_t, 2); else if (beam <= 4) MM_BS(bf16_t, 4); else MM_BS(bf16_t, 8);
+  } else {
+    if (beam == 1) MM_BS(float, 1); else if (beam == 2) MM_BS(float, 2); else if (beam <= 4) MM_BS(float, 4); else MM_BS(float, 8);
+  }
+#undef MM_BS
   return true;
 }
 
