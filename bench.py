@@ -106,7 +106,7 @@ def bench_translate(args, setup, ctx, batches):
     w_params -= 2 * sh.d_model * sh.d_model * n_dec      # the encoder-side key/value projections ran once
     step_bytes = w_params * esz + int(s_len.sum()) * 2 * sh.d_model * esz * n_dec
     step_s = elapsed / args.steps / max_new
-    roofline = {"bound": "hbm", "kernel": "one decoding step (71 launches at set-up 2; no single kernel dominates)",
+    roofline = {"bound": "hbm", "kernel": f"one decoding step ({73 if beam else 71} launches at set-up 2; no single kernel dominates)",
                 "achieved": step_bytes / step_s / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                 "frac": step_bytes / step_s / PEAK_HBM, "traffic": None, "bytes_per_step": step_bytes}
     cpu = None
