@@ -105,6 +105,11 @@ def test_carried_hypotheses_tie_order_and_edge_shapes():
     ctx, orc = sharpened_pair(setup, 1.0, 1e3)
     ids, n, score = ctx.mm_translate_beam(0, src, s_len, 5, 4)
     assert (n == 1).all() and (ids[:, 0] == mo.EOS).all() and (np.abs(score) < 1e-3).all()
+    # a longer limit: every beam is finished after two steps, the host notices at its first look
+    # (step 8) and stops; the history it walks back is shorter than max_new
+    ids, n, score = ctx.mm_translate_beam(0, src, s_len, 20, 4)
+    assert (n == 1).all() and (ids[:, 0] == mo.EOS).all() and (ids[:, 1:] == mo.PAD).all()
+    assert (np.abs(score) < 1e-3).all()
     ctx.close()
     ctx, orc = sharpened_pair(setup, 1.0, -1e3)
     ids, n, _ = ctx.mm_translate_beam(0, src, s_len, 5, 4)
