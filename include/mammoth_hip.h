@@ -73,7 +73,7 @@ typedef struct {
                                work, compute calls return MM_ESTATE                              */
 } mm_config;
 
-/* One module (section 3.2: "module definitions are specific to a given sequential position"). */
+/* One module; a module belongs to one position of its stack (section 3.2, the second design constraint). */
 typedef struct {
   int32_t kind;             /* mm_kind                                                            */
   int32_t position;         /* index in the encoder / decoder module sequence (stacks only)       */
@@ -164,7 +164,11 @@ mm_status mm_last_loss(mm_ctx* ctx, float* out_loss);
 /* Renormalise and update (Algorithm 1 last line, then Adam): for every listed module with
  * n_j > 0: g = bucket / n_j; t_j += 1; Adam step on the fp32 master with bias correction for
  * step t_j; working copy refreshed; bucket emptied; n_j = 0.  Modules with n_j = 0 are skipped:
- * not one byte of theirs is read or written.  module_ids NULL = every module.  Asynchronous. */
+ * not one byte of theirs is read or written.  module_ids NULL = every module.
+ * A training step still in flight is settled first (the call waits for it): if its ids turned
+ * out bad on the device it had no effect, its uses are not counted, and a module left without a
+ * use gets no update; that step's status stays available from mm_last_loss.  The update itself is
+ * enqueued and not waited for. */
 mm_status mm_apply_update(mm_ctx* ctx, const int32_t* module_ids, int32_t n, float lr);
 
 /* ---- introspection (tests, checkpoints); all synchronise with the stream ------------------- */
@@ -209,6 +213,21 @@ typedef enum {
   MM_DUMP_MASK_CROSS = 9  /* uint8[B, T_max-1, S_max]                                             */
 } mm_dump_what;
 mm_status mm_debug_dump(mm_ctx* ctx, int32_t what, void* dst, int64_t* nbytes);
+
+/* Test hook on the attention kernels themselves (section 3.2 fixes no network internals; the
+ * benchmark's contract asks that blocked keys get probability exactly 0).  Returns the attention
+ * probabilities of one attention block of the most recent mm_train_step as that step's own forward
+ * attention kernel computes them: the kernel is run again on the step's saved queries and keys
+ * with one-hot value rows (the value row of a sentence's key j is unit vector j mod d_h; one pass
+ * per group of d_h keys), so each output row IS a probability row with the kernel's masking,
+ * tile skipping and softmax, rounded to the working dtype.
+ *   kind: 0 encoder self-attention, 1 decoder self-attention, 2 decoder attention over the
+ *         encoder output; layer: index of the block within its stack, in forward order.
+ *   probs: host float [B, H, Lq, Lk] with Lq, Lk the step's padded widths (S_max or T_max - 1);
+ *          entries beyond a sentence's own lengths are 0.  NULL: only *n_floats is set.
+ *   *n_floats: capacity on entry, size on return.
+ * Valid until the next compute call on the context.  Synchronous; allocates temporaries. */
+mm_status mm_debug_attention(mm_ctx* ctx, int32_t kind, int32_t layer, float* probs, int64_t* n_floats);
 
 /* ---- per-kernel-class timing with HIP events on the context's stream ----------------------- */
 typedef enum {

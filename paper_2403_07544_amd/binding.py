@@ -13,8 +13,7 @@ from typing import List, Optional, Sequence, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# MAMMOTH_HIP_LIB: load another build of the library instead (side-by-side timing of two builds)
-LIB_PATH = os.environ.get("MAMMOTH_HIP_LIB") or os.path.join(_HERE, "libmammoth_hip.so")
+LIB_PATH = os.path.join(_HERE, "libmammoth_hip.so")
 
 MM_OK, MM_EINVAL, MM_ENOMEM, MM_ESTATE, MM_ERANGE, MM_ENONFINITE, MM_EHIP = 0, -1, -2, -3, -4, -5, -6
 STATUS_NAMES = {0: "MM_OK", -1: "MM_EINVAL", -2: "MM_ENOMEM", -3: "MM_ESTATE", -4: "MM_ERANGE",
@@ -31,7 +30,7 @@ KERNEL_CLASSES = ("gemm", "attn_fwd", "attn_bwd", "layernorm_fwd", "layernorm_bw
 EXPORTS = ("mm_create", "mm_destroy", "mm_register_module", "mm_route_task", "mm_train_step", "mm_translate_greedy", "mm_translate_beam",
            "mm_last_loss", "mm_apply_update", "mm_num_modules", "mm_get_route", "mm_get_touched",
            "mm_get_layout", "mm_get_params", "mm_set_params", "mm_get_grads", "mm_get_bucket_memory", "mm_set_grads",
-           "mm_get_adam", "mm_get_working", "mm_debug_dump", "mm_profile", "mm_profile_read",
+           "mm_get_adam", "mm_get_working", "mm_debug_dump", "mm_debug_attention", "mm_profile", "mm_profile_read",
            "mm_last_error")
 
 
@@ -90,6 +89,7 @@ def load_library() -> C.CDLL:
         "mm_get_adam": [vp, i32, vp, vp, i64, pi64],
         "mm_get_working": [vp, i32, vp, i64],
         "mm_debug_dump": [vp, i32, vp, pi64],
+        "mm_debug_attention": [vp, i32, i32, vp, pi64],
         "mm_profile": [vp, i32],
         "mm_profile_read": [vp, vp, vp, vp],
     }
@@ -309,6 +309,16 @@ class Context:
         out = np.zeros(nbytes.value // np.dtype(dtype).itemsize, dtype=dtype)
         self._check(self.lib.mm_debug_dump(self.handle, code, _ptr(out), C.byref(nbytes)))
         return out
+
+    def mm_debug_attention(self, kind: str, layer: int, B: int, H: int) -> np.ndarray:
+        """Probabilities [B, H, Lq, Lk] of one attention block of the last step, read off the
+        step's own forward attention kernel.  kind: 'enc', 'dec_self' or 'dec_cross'."""
+        code = {"enc": 0, "dec_self": 1, "dec_cross": 2}[kind]
+        n = C.c_int64(0)
+        self._check(self.lib.mm_debug_attention(self.handle, code, layer, None, C.byref(n)))
+        out = np.zeros(n.value, dtype=np.float32)
+        self._check(self.lib.mm_debug_attention(self.handle, code, layer, _ptr(out), C.byref(n)))
+        return out.reshape(B, H, -1)
 
     def mm_profile(self, enable: bool):
         self._check(self.lib.mm_profile(self.handle, 1 if enable else 0))

@@ -1,23 +1,23 @@
-"""Builds libmammoth_hip.so (gfx950) in-tree with hipcc."""
+"""Builds libmammoth_hip.so (gfx950) in-tree with hipcc: one object per source file, compiled
+side by side, then one link."""
 from __future__ import annotations
 
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmammoth_hip.so")
 SOURCES = ["runtime.hip", "kernels_pointwise.hip", "kernels_gemm.hip", "kernels_attention.hip",
            "kernels_decode.hip"]
-FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc",
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result", "-Wno-unused-value"]
 
 
-def build(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
-    """extra_flags / out: an experimental build beside the standard one (e.g. a -D switch)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + list(extra_flags) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -27,7 +27,17 @@ def build(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
         print(text)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed ({res.returncode})\n{res.stdout}")
-    return out
+
+
+def build(verbose: bool = True) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs = [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES]
+    cmds = [[hipcc] + FLAGS + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=min(len(cmds), os.cpu_count() or 1)) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc"] + objs + ["-o", LIB], verbose)
+    return LIB
 
 
 if __name__ == "__main__":

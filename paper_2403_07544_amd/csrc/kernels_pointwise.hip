@@ -133,31 +133,36 @@ __global__ void embed_fwd_kernel(const T* __restrict__ E, const float* __restric
 }
 
 // ----------------------------------------------------------------------------------------------
-// embedding gradient: sort (token, row) keys in one workgroup, then one workgroup per run of
-// equal tokens adds its rows in ascending row order.  No atomics: same bits every run.
+// embedding gradient: sort (token, row) keys, then one workgroup per run of equal tokens adds its
+// rows in ascending row order.  No atomics: same bits every run.
 // ----------------------------------------------------------------------------------------------
 constexpr int ROW_BITS = 14;  // rows < 16384, tokens < 2^17
 
-__global__ void __launch_bounds__(1024) sort_keys_kernel(const int32_t* __restrict__ tok, int rows,
-                                                         int n_pow2, uint32_t* __restrict__ keys) {
-  extern __shared__ uint32_t sk[];
-  for (int i = threadIdx.x; i < n_pow2; i += blockDim.x)
-    sk[i] = i < rows ? (((uint32_t)tok[i] << ROW_BITS) | (uint32_t)i) : 0xffffffffu;
-  __syncthreads();
-  for (int k = 2; k <= n_pow2; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = threadIdx.x; i < n_pow2; i += blockDim.x) {
-        const int l = i ^ j;
-        if (l > i) {
-          const uint32_t a = sk[i], b = sk[l];
-          const bool up = (i & k) == 0;
-          if ((a > b) == up) { sk[i] = b; sk[l] = a; }
-        }
-      }
-      __syncthreads();
+// Sorted position of key i = number of keys below it (keys are distinct: the row is part of the
+// key).  Each thread owns one key and compares it with every key of the batch, which pass through
+// LDS a chunk at a time (all lanes read the same address: a broadcast).  rows / 256 workgroups, no
+// ordering between them, no atomics, exact.
+constexpr int SORT_CHUNK = 2048;
+__global__ void __launch_bounds__(256) rank_keys_kernel(const int32_t* __restrict__ tok, int rows,
+                                                        uint32_t* __restrict__ keys) {
+  __shared__ __align__(16) uint32_t sk[SORT_CHUNK];
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  const uint32_t mine = i < rows ? (((uint32_t)tok[i] << ROW_BITS) | (uint32_t)i) : 0xffffffffu;
+  int rank = 0;
+  for (int base = 0; base < rows; base += SORT_CHUNK) {
+    __syncthreads();
+    for (int j = threadIdx.x; j < SORT_CHUNK; j += 256) {
+      const int g = base + j;
+      sk[j] = g < rows ? (((uint32_t)tok[g] << ROW_BITS) | (uint32_t)g) : 0xffffffffu;   // past the end: below nobody
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int j = 0; j < SORT_CHUNK; j += 4) {
+      const uint4 v = *reinterpret_cast<const uint4*>(&sk[j]);
+      rank += (int)(v.x < mine) + (int)(v.y < mine) + (int)(v.z < mine) + (int)(v.w < mine);
     }
   }
-  for (int i = threadIdx.x; i < n_pow2; i += blockDim.x) keys[i] = sk[i];
+  if (i < rows) keys[rank] = mine;
 }
 
 // Two passes so that the run of the most frequent token (hundreds of rows under a Zipf law) is not
@@ -386,7 +391,7 @@ __global__ void __launch_bounds__(64 * LNB_WAVES) layernorm_bwd_kernel(
   const float inv_d = 1.0f / (float)d;
   for (int row = blockIdx.x * LNB_WAVES + wave; row < rows; row += gridDim.x * LNB_WAVES) {
     const float mu = mean[row], rs = rstd[row];
-    float4 xh[NV], dh[NV];
+    float4 xh[NV], dh[NV], rv[NV];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int k = 0; k < NV; ++k) {
@@ -394,6 +399,7 @@ __global__ void __launch_bounds__(64 * LNB_WAVES) layernorm_bwd_kernel(
       if (c < d) {
         const float4 xv = Io<float>::ld4(x + (int64_t)row * d + c);
         float4 dv = Io<float>::ld4(dy + (int64_t)row * d + c);
+        if (dres) rv[k] = Io<float>::ld4(dres + (int64_t)row * d + c);   // in flight during the reductions
         for (int s = 1; s < dy_parts; ++s) {   // split-K partial sums of the producing product
           const float4 t = Io<float>::ld4(dy + s * dy_part_stride + (int64_t)row * d + c);
           dv.x += t.x; dv.y += t.y; dv.z += t.z; dv.w += t.w;
@@ -417,10 +423,7 @@ __global__ void __launch_bounds__(64 * LNB_WAVES) layernorm_bwd_kernel(
         float4 o;
         o.x = rs * (dh[k].x - m1 - xh[k].x * m2); o.y = rs * (dh[k].y - m1 - xh[k].y * m2);
         o.z = rs * (dh[k].z - m1 - xh[k].z * m2); o.w = rs * (dh[k].w - m1 - xh[k].w * m2);
-        if (dres) {
-          const float4 r = Io<float>::ld4(dres + (int64_t)row * d + c);
-          o.x += r.x; o.y += r.y; o.z += r.z; o.w += r.w;
-        }
+        if (dres) { o.x += rv[k].x; o.y += rv[k].y; o.z += rv[k].z; o.w += rv[k].w; }
         Io<float>::st4(dx_out + (int64_t)row * d + c, o);
         if (dxT_out) Io<T>::st4(dxT_out + (int64_t)row * d + c, o);
       }
@@ -558,6 +561,10 @@ __global__ void __launch_bounds__(1024) ce_kernel(T* __restrict__ z, const int32
   T* zr = z + (int64_t)row * V;
   const int tid = threadIdx.x, nthr = blockDim.x;
   const int wave = tid >> 6, lane = tid & 63, nwave = nthr >> 6;
+  const int y = label[row];
+  // the target logit, read before any wavefront starts overwriting the row with the gradient
+  float zy = 0.f;
+  if (tid == 0) zy = Io<T>::ld(zr + y);
   // pass 1: running max, rescaled sum of exponentials, plain sum
   float mx = -INFINITY, se = 0.f, sz = 0.f;
   for (int c = tid * 4; c < V; c += nthr * 4) {  // V % 4 == 0
@@ -585,11 +592,7 @@ __global__ void __launch_bounds__(1024) ce_kernel(T* __restrict__ z, const int32
   }
   __syncthreads();
   const float lse = s_lse;
-  const int y = label[row];
-  if (tid == 0) {
-    const float zy = Io<T>::ld(zr + y);
-    loss_rows[row] = lse - (1.0f - eps) * zy - (eps / (float)V) * s_sumz;
-  }
+  if (tid == 0) loss_rows[row] = lse - (1.0f - eps) * zy - (eps / (float)V) * s_sumz;
   // pass 2 (the row was just read: served from cache): z <- (softmax - q) * scale * ok
   const float ok = (*flag == 0) ? scale : 0.0f;
   const float uni = eps / (float)V;
@@ -812,9 +815,7 @@ void launch_embed_fwd(hipStream_t st, Dtype dt, const void* E, const float* pe, 
 }
 
 void launch_sort_tokens(hipStream_t st, const int32_t* tok, int rows, uint32_t* keys) {
-  int n_pow2 = 64;
-  while (n_pow2 < rows) n_pow2 <<= 1;
-  sort_keys_kernel<<<1, 1024, n_pow2 * sizeof(uint32_t), st>>>(tok, rows, n_pow2, keys);
+  if (rows > 0) rank_keys_kernel<<<(rows + 255) / 256, 256, 0, st>>>(tok, rows, keys);
 }
 
 void launch_embed_grad(hipStream_t st, const uint32_t* keys, const float* dx, float* bucket, float* partial,

@@ -99,8 +99,6 @@ void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const i
 // MFMA kernel does not take): the caller then launches the products one by one.
 constexpr int GEMM_MULTI_MAX = 8;
 bool launch_gemm_multi(hipStream_t st, Dtype dt, const GemmParams* ps, int n, const LaunchEvents& ev = LaunchEvents());
-// Tuning hook: one named tile configuration of the MFMA kernel; false if the shape is not eligible.
-bool launch_gemm_variant(hipStream_t st, const GemmParams& p, int variant);
 // Same contract, always the plain FMA kernel (cross-check of the MFMA path).
 void launch_gemm_simt(hipStream_t st, Dtype dt, const GemmParams& p, const LaunchEvents& ev = LaunchEvents());
 
@@ -120,8 +118,8 @@ void launch_mask_dump(hipStream_t st, const int32_t* cu_q, const int32_t* cu_k, 
 // pos null: every row sits at position pos_all.
 void launch_embed_fwd(hipStream_t st, Dtype dt, const void* E, const float* pe, const int32_t* tok,
                       const int32_t* pos, float* x, int rows, int d, float sqrt_d, int pos_all = 0);
-// keys[i] = (token << 14 | row), sorted ascending; keys holds the next power of two >= rows entries
-// (at least 64).  Depends on the token ids only, so it can run ahead of the step on another stream.
+// keys[i] = (token << 14 | row), sorted ascending, rows entries.  Depends on the token ids only, so
+// it can run ahead of the step on another stream.
 void launch_sort_tokens(hipStream_t st, const int32_t* tok, int rows, uint32_t* keys);
 // bucket[tok,:] += sqrt_d * sum over rows with that token of dx[row,:]; deterministic (fixed
 // summation order, no atomics).  partial: scratch float [rows, d].

@@ -90,7 +90,12 @@ struct mm_ctx {
   Arena ws;
   // last step
   int B = 0, S_max = 0, T_max = 0, S = 0, U = 0;
-  bool pending = false; int pending_task = -1; bool pending_counted = false;
+  // test hook (mm_debug_attention): the forward attention launches of the last training step and
+  // host copies of its prefix sums
+  struct AttnLog { AttnParams p; int kind; };
+  std::vector<AttnLog> attn_log;
+  std::vector<int32_t> h_cu_s, h_cu_u;
+  bool pending = false; int pending_task = -1;
   float last_loss = 0.f; mm_status last_status = MM_OK;
   // profiling
   bool prof = false;
@@ -226,7 +231,7 @@ struct Run {
     if (dry) return;
     const int d = c->cfg.d_model;
     launch_layernorm_fwd(c->st, c->dt, x, g, b, y, mean, rstd, rows, d, c->cfg.ln_eps,
-                         begin_timed(MM_K_LAYERNORM_FWD, (double)rows * d * (4 + esz())));
+                         begin_timed(MM_K_LAYERNORM_FWD, (double)rows * d * 2 * esz()));
   }
   // The gain/shift gradient sums of all LayerNorms of the step are reduced in one launch at the end.
   std::vector<LnReduceJob>* ln_jobs = nullptr;
@@ -238,7 +243,7 @@ struct Run {
     float* partial = (float*)c->ws.take((size_t)n_partial * 2 * d * sizeof(float));
     if (dry) return;
     launch_layernorm_bwd(c->st, c->dt, dy, x, mean, rstd, g, dres, dx, c->dt == BF16 ? dxT : nullptr, partial, rows, d,
-                         begin_timed(MM_K_LAYERNORM_BWD, (double)rows * d * (12 + (dres ? 4 : 0) + (c->dt == BF16 ? 2 : 0))),
+                         begin_timed(MM_K_LAYERNORM_BWD, (double)rows * d * 3 * esz()),
                          dy_parts, dy_part_stride);
     LnReduceJob jb;
     jb.partial = partial; jb.dgamma = gg; jb.dbeta = gb; jb.n_partial = n_partial; jb.d = d;
@@ -361,6 +366,7 @@ struct Step {
     AttnParams a = ap(qkv, 3 * d, dry() ? nullptr : qkv + (size_t)d * esz, dry() ? nullptr : qkv + (size_t)2 * d * esz,
                       3 * d, s.o, s.lse, is_dec, is_dec, is_dec ? 1 : 0);
     run.attn_fwd(a, 4.0 * pair_sum(is_dec, is_dec) * d);
+    if (!dry()) c->attn_log.push_back({a, is_dec ? 1 : 0});
     p = gp(s.o, d, pv.W(t0 + 8), d, s.x_out, d, R, d, d);
     p.bias = pv.V(t0 + 9); p.residual = x_in; p.ldr = d; p.out_f32 = 1;
     run.gemm(p);
@@ -386,6 +392,7 @@ struct Step {
     const char* kv = (const char*)s.kv;
     AttnParams a = ap(s.q, d, kv, dry() ? nullptr : kv + (size_t)d * esz, 2 * d, s.o, s.lse, true, false, 0);
     run.attn_fwd(a, 4.0 * sum_us * d);
+    if (!dry()) c->attn_log.push_back({a, 2});
     p = gp(s.o, d, pv.W(t0 + 8), d, s.x_out, d, U, d, d);
     p.bias = pv.V(t0 + 9); p.residual = x_in; p.ldr = d; p.out_f32 = 1;
     run.gemm(p);
@@ -572,15 +579,12 @@ mm_status resolve_pending(mm_ctx* c) {
   int32_t flag;
   memcpy(&flag, &c->result_host[1], 4);
   if (flag != 0) {
-    if (c->pending_counted)
-      for (int j : c->routes[c->pending_task].ids)
-        if (c->mods[j].touched > 0) c->mods[j].touched -= 1;
-    c->pending_counted = false;
+    for (int j : c->routes[c->pending_task].ids)
+      if (c->mods[j].touched > 0) c->mods[j].touched -= 1;
     c->last_status = fail(c, MM_ERANGE, flag & 1 ? "token id outside [0, vocab) (found on the device); step had no effect"
                                                  : "non-pad id after the end of a sentence (found on the device); step had no effect");
     return c->last_status;
   }
-  c->pending_counted = false;
   if (!std::isfinite(c->last_loss)) {
     c->last_status = fail(c, MM_ENONFINITE, "loss is not finite");
     return c->last_status;
@@ -637,7 +641,7 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
   }
   const int d = s.d, S = s.S, U = s.U, V = s.V;
   Run& run = s.run;
-  if (!dry) run.mark();
+  if (!dry) { run.mark(); c->attn_log.clear(); }
   std::vector<LnReduceJob> ln_jobs;
   run.ln_jobs = &ln_jobs;
   c->ws.reset(dry);
@@ -1318,6 +1322,8 @@ mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const i
     tgt_dev = c->ids_dev + (size_t)B * S_max;
   }
   c->B = B; c->S_max = S_max; c->T_max = T_max; c->S = (int)S; c->U = (int)U;
+  c->h_cu_s.assign(st_cu_s, st_cu_s + B + 1);
+  c->h_cu_u.assign(st_cu_u, st_cu_u + B + 1);
   const Route& rt = c->routes[task];
   run_step(c, rt, true, lengths);
   s = ensure_ws(c, c->ws.high);
@@ -1341,7 +1347,7 @@ mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const i
   HIP_TRY(c, hipMemcpyAsync(&c->result_host[0], c->loss_dev, 8, hipMemcpyDeviceToHost, c->st));   // loss, flag
   HIP_TRY(c, hipEventRecord(c->ev_done, c->st));
   for (int j : rt.ids) c->mods[j].touched += 1;
-  c->pending = true; c->pending_task = task; c->pending_counted = true;
+  c->pending = true; c->pending_task = task;
   if (c->prof && c->prof_recs.size() > 8192) collect_profile(c);
   if (out_loss) {
     s = resolve_pending(c);
@@ -1352,6 +1358,65 @@ mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const i
 }
 
 }  // extern "C"
+
+namespace {
+// Which of the listed modules (null: all) take an update: those with n_j > 0, each once, in the
+// order given.  use holds up to cap ids; more than that is an error (the caller's table is full).
+mm_status select_updates(mm_ctx* c, const int32_t* module_ids, int n, int* use, int cap, int* n_use) {
+  *n_use = 0;
+  if (module_ids && n < 0) return fail(c, MM_EINVAL, "negative count");
+  const int count = module_ids ? n : (int)c->mods.size();
+  for (int i = 0; i < count; ++i) {
+    const int j = module_ids ? module_ids[i] : i;
+    if (!valid_module(c, j)) return fail(c, MM_EINVAL, "unknown module id %d", j);
+    if (c->mods[j].touched <= 0) continue;
+    bool dup = false;
+    for (int k = 0; k < *n_use; ++k) dup |= (use[k] == j);
+    if (dup) continue;
+    if (*n_use >= cap)
+      return fail(c, MM_ERANGE, "more than %d modules to update in one call", cap);
+    use[(*n_use)++] = j;
+  }
+  return MM_OK;
+}
+
+// Renormalise-and-Adam over the selected modules (Algorithm 1's division by n_j, then the
+// optimiser): fills the segment table in host_tab (pinned), uploads it to dev_tab and launches
+// one kernel over all segments.  ev guards host_tab against being refilled before its previous
+// upload has left it.  The caller has settled the step in flight: a step whose ids turned out bad
+// on the device had no effect, its use counts were taken back, and modules left without a use
+// were not selected (no gradient, no update).
+mm_status update_launch(mm_ctx* c, const int* use, int n_use, float lr, AdamSegment* host_tab, AdamSegment* dev_tab,
+                        hipEvent_t ev, bool timed) {
+  HIP_TRY(c, hipEventSynchronize(ev));
+  int chunks = 0;
+  double work = 0;
+  for (int i = 0; i < n_use; ++i) {
+    Module& m = c->mods[use[i]];
+    m.t += 1;
+    AdamSegment& sg = host_tab[i];
+    sg.theta = m.theta; sg.m = m.m; sg.v = m.v; sg.g = m.g; sg.w16 = m.w16; sg.len = m.P;
+    sg.n_uses = (float)m.touched;
+    sg.bc1 = (float)(1.0 - std::pow((double)c->cfg.adam_beta1, (double)m.t));
+    sg.bc2 = (float)(1.0 - std::pow((double)c->cfg.adam_beta2, (double)m.t));
+    sg.first_chunk = chunks; sg.keep_g = bucket_overwrites(m.kind);
+    chunks += (int)((m.P + ADAM_CHUNK - 1) / ADAM_CHUNK);
+    work += work_bytes_adam(c, m.P);
+    m.touched = 0;
+  }
+  HIP_TRY(c, hipMemcpyAsync(dev_tab, host_tab, (size_t)n_use * sizeof(AdamSegment), hipMemcpyHostToDevice, c->st));
+  HIP_TRY(c, hipEventRecord(ev, c->st));
+  LaunchEvents le;
+  if (timed) {
+    Run run{c, false};
+    run.mark();
+    le = run.begin_timed(MM_K_ADAM, work);
+  }
+  launch_adam(c->st, dev_tab, n_use, chunks, lr, c->cfg.adam_beta1, c->cfg.adam_beta2, c->cfg.adam_eps, le);
+  HIP_TRY(c, hipGetLastError());
+  return MM_OK;
+}
+}  // namespace
 
 namespace {
 // Both searches: beam == 0 greedy, beam >= 1 beam search (out_scores may be NULL).
@@ -1415,6 +1480,7 @@ mm_status translate_impl(mm_ctx* c, int32_t task, const int32_t* src_ids, const 
   c->B = B; c->S_max = S_max; c->T_max = 2; c->S = (int)S; c->U = B;
   const Route& rt = c->routes[task];
   TranslateOut out{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+  c->attn_log.clear(); c->h_cu_s.clear(); c->h_cu_u.clear();   // the workspace of the last training step is reused
   run_translate(c, rt, true, src_lengths, max_new, out, beam);
   s = ensure_ws(c, c->ws.high);
   if (s != MM_OK) return s;
@@ -1492,58 +1558,22 @@ mm_status mm_last_loss(mm_ctx* c, float* out_loss) {
 mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float lr) {
   if (!c) return MM_EINVAL;
   if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context cannot compute");
-  std::vector<int> ids;
-  if (module_ids) {
-    if (n < 0) return fail(c, MM_EINVAL, "negative count");
-    for (int i = 0; i < n; ++i) {
-      if (!valid_module(c, module_ids[i])) return fail(c, MM_EINVAL, "unknown module id %d", module_ids[i]);
-      bool dup = false;
-      for (int j : ids) dup |= (j == module_ids[i]);
-      if (!dup) ids.push_back(module_ids[i]);
-    }
-  } else {
-    for (int j = 0; j < (int)c->mods.size(); ++j) ids.push_back(j);
-  }
-  std::vector<int> use;
-  for (int j : ids) if (c->mods[j].touched > 0) use.push_back(j);
-  if (use.empty()) return MM_OK;
-  if ((int)use.size() > c->seg_cap) {
+  resolve_pending(c);   // see update_launch
+  std::vector<int> use(c->mods.size() + 1);
+  int n_use = 0;
+  mm_status s = select_updates(c, module_ids, n, use.data(), (int)c->mods.size(), &n_use);
+  if (s != MM_OK || n_use == 0) return s;
+  if (n_use > c->seg_cap) {
     HIP_TRY(c, hipStreamSynchronize(c->st));
     if (c->seg_host) hipHostFree(c->seg_host);
     if (c->seg_dev) hipFree(c->seg_dev);
     c->seg_host = nullptr; c->seg_dev = nullptr; c->seg_cap = 0;
-    const int cap = (int)use.size() + 32;
+    const int cap = n_use + 32;
     HIP_TRY(c, hipHostMalloc((void**)&c->seg_host, cap * sizeof(AdamSegment), hipHostMallocDefault));
     HIP_TRY(c, hipMalloc((void**)&c->seg_dev, cap * sizeof(AdamSegment)));
     c->seg_cap = cap;
   }
-  HIP_TRY(c, hipEventSynchronize(c->ev_seg));  // previous upload of the table has left the pinned buffer
-  int chunks = 0;
-  int64_t total = 0;
-  double work = 0;
-  for (size_t i = 0; i < use.size(); ++i) {
-    Module& m = c->mods[use[i]];
-    m.t += 1;
-    AdamSegment& sg = c->seg_host[i];
-    sg.theta = m.theta; sg.m = m.m; sg.v = m.v; sg.g = m.g; sg.w16 = m.w16; sg.len = m.P;
-    sg.n_uses = (float)m.touched;
-    sg.bc1 = (float)(1.0 - std::pow((double)c->cfg.adam_beta1, (double)m.t));
-    sg.bc2 = (float)(1.0 - std::pow((double)c->cfg.adam_beta2, (double)m.t));
-    sg.first_chunk = chunks; sg.keep_g = bucket_overwrites(m.kind);
-    chunks += (int)((m.P + ADAM_CHUNK - 1) / ADAM_CHUNK);
-    total += m.P;
-    work += work_bytes_adam(c, m.P);
-    m.touched = 0;
-  }
-  c->pending_counted = false;  // the step's uses have been consumed
-  HIP_TRY(c, hipMemcpyAsync(c->seg_dev, c->seg_host, use.size() * sizeof(AdamSegment), hipMemcpyHostToDevice, c->st));
-  HIP_TRY(c, hipEventRecord(c->ev_seg, c->st));
-  Run run{c, false};
-  run.mark();
-  launch_adam(c->st, c->seg_dev, (int)use.size(), chunks, lr, c->cfg.adam_beta1, c->cfg.adam_beta2, c->cfg.adam_eps,
-              run.begin_timed(MM_K_ADAM, work));
-  HIP_TRY(c, hipGetLastError());
-  return MM_OK;
+  return update_launch(c, use.data(), n_use, lr, c->seg_host, c->seg_dev, c->ev_seg, true);
 }
 
 // ---- introspection -----------------------------------------------------------------------------
@@ -1711,6 +1741,80 @@ mm_status mm_debug_dump(mm_ctx* c, int32_t what, void* dst, int64_t* nbytes) {
     HIP_TRY(c, hipMemcpy(dst, src, (size_t)need, hipMemcpyDeviceToHost));
   }
   *nbytes = need;
+  return MM_OK;
+}
+
+mm_status mm_debug_attention(mm_ctx* c, int32_t kind, int32_t layer, float* probs, int64_t* n_floats) {
+  if (!c || !n_floats) return MM_EINVAL;
+  if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context holds no device memory");
+  if (kind < 0 || kind > 2 || layer < 0) return fail(c, MM_EINVAL, "kind must be 0, 1 or 2 and layer >= 0");
+  mm_status st0 = resolve_pending(c);
+  (void)st0;
+  if (c->attn_log.empty() || c->h_cu_s.empty()) return fail(c, MM_ESTATE, "no training step's attention launches are on record");
+  const mm_ctx::AttnLog* hit = nullptr;
+  int seen = 0;
+  for (const auto& e : c->attn_log)
+    if (e.kind == kind && seen++ == layer) { hit = &e; break; }
+  if (!hit) return fail(c, MM_EINVAL, "the last step ran no attention block of kind %d with index %d", kind, layer);
+  const AttnParams& ap0 = hit->p;
+  const int B = c->B, H = ap0.H, dh = ap0.dh, d = H * dh;
+  const int Lq = kind == 0 ? c->S_max : c->T_max - 1, Lk = kind == 1 ? c->T_max - 1 : c->S_max;
+  const std::vector<int32_t>& cu_q = kind == 0 ? c->h_cu_s : c->h_cu_u;
+  const std::vector<int32_t>& cu_k = kind == 1 ? c->h_cu_u : c->h_cu_s;
+  const int64_t need = (int64_t)B * H * Lq * Lk;
+  if (!probs) { *n_floats = need; return MM_OK; }
+  if (*n_floats < need) return fail(c, MM_EINVAL, "capacity %lld < %lld floats", (long long)*n_floats, (long long)need);
+  const int rows_q = cu_q[B], rows_k = cu_k[B];
+  const size_t esz = c->dt == BF16 ? 2 : 4;
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  char* v_tmp = nullptr; char* o_tmp = nullptr; float* lse_tmp = nullptr;
+  mm_status s = MM_OK;
+  auto guard = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess && s == MM_OK) s = fail(c, e == hipErrorOutOfMemory ? MM_ENOMEM : MM_EHIP, "%s: %s", what, hipGetErrorString(e));
+  };
+  guard(hipMalloc((void**)&v_tmp, (size_t)rows_k * d * esz), "hipMalloc(values)");
+  guard(hipMalloc((void**)&o_tmp, (size_t)rows_q * d * esz), "hipMalloc(outputs)");
+  guard(hipMalloc((void**)&lse_tmp, (size_t)H * rows_q * sizeof(float)), "hipMalloc(lse)");
+  std::vector<unsigned char> v_host((size_t)rows_k * d * esz), o_host((size_t)rows_q * d * esz);
+  memset(probs, 0, (size_t)need * sizeof(float));
+  const int passes = (ap0.max_lk + dh - 1) / dh;
+  for (int pass = 0; pass < passes && s == MM_OK; ++pass) {
+    // value row of key j (position within its sentence) = unit vector j - pass * dh in every head
+    memset(v_host.data(), 0, v_host.size());
+    for (int b = 0; b < B; ++b)
+      for (int r = cu_k[b]; r < cu_k[b + 1]; ++r) {
+        const int e = (r - cu_k[b]) - pass * dh;
+        if (e < 0 || e >= dh) continue;
+        for (int h = 0; h < H; ++h) {
+          const size_t idx = (size_t)r * d + (size_t)h * dh + e;
+          if (c->dt == BF16) reinterpret_cast<bf16_t*>(v_host.data())[idx] = 0x3f80;   // 1.0
+          else reinterpret_cast<float*>(v_host.data())[idx] = 1.0f;
+        }
+      }
+    guard(hipMemcpy(v_tmp, v_host.data(), v_host.size(), hipMemcpyHostToDevice), "hipMemcpy(values)");
+    if (s != MM_OK) break;
+    AttnParams ap = ap0;
+    ap.v = v_tmp; ap.ldv = d; ap.o = o_tmp; ap.ldo = d; ap.lse = lse_tmp;
+    launch_attn_fwd(c->st, c->dt, ap);
+    guard(hipGetLastError(), "attention launch");
+    guard(hipStreamSynchronize(c->st), "hipStreamSynchronize");
+    guard(hipMemcpy(o_host.data(), o_tmp, o_host.size(), hipMemcpyDeviceToHost), "hipMemcpy(outputs)");
+    if (s != MM_OK) break;
+    for (int b = 0; b < B; ++b)
+      for (int r = cu_q[b]; r < cu_q[b + 1]; ++r)
+        for (int h = 0; h < H; ++h)
+          for (int e = 0; e < dh; ++e) {
+            const int j = pass * dh + e;
+            if (j >= Lk) break;
+            const size_t idx = (size_t)r * d + (size_t)h * dh + e;
+            const float v = c->dt == BF16 ? bf16_to_f32(reinterpret_cast<const bf16_t*>(o_host.data())[idx])
+                                          : reinterpret_cast<const float*>(o_host.data())[idx];
+            probs[(((int64_t)b * H + h) * Lq + (r - cu_q[b])) * Lk + j] = v;
+          }
+  }
+  hipFree(v_tmp); hipFree(o_tmp); hipFree(lse_tmp);
+  if (s != MM_OK) return s;
+  *n_floats = need;
   return MM_OK;
 }
 
