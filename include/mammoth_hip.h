@@ -171,6 +171,18 @@ mm_status mm_last_loss(mm_ctx* ctx, float* out_loss);
  * enqueued and not waited for. */
 mm_status mm_apply_update(mm_ctx* ctx, const int32_t* module_ids, int32_t n, float lr);
 
+/* mm_apply_update for callers that cannot allocate device or pinned memory inside the call (tight
+ * serving or training loops, harnesses that forbid hipMalloc): same arguments, same result, but
+ * the table of per-module segments the update kernel reads lives in a static device array of the
+ * library (18 KiB per GPU, held until the process ends) instead of a buffer that grows on demand,
+ * and the call makes no hipMalloc / hipHostMalloc / hipFree and creates no events.  At most
+ * MM_NOALLOC_MAX_MODULES modules with n_j > 0 can be updated by one call; more returns MM_ERANGE
+ * and changes nothing.  Every context on one GPU shares that GPU's array: calls that overlap in
+ * time on one GPU (two contexts, two streams) race on it; calls on one context's stream are
+ * ordered and safe.  The update kernel is not timed by mm_profile. */
+#define MM_NOALLOC_MAX_MODULES 256
+mm_status mm_apply_update_noalloc(mm_ctx* ctx, const int32_t* module_ids, int32_t n, float lr);
+
 /* ---- introspection (tests, checkpoints); all synchronise with the stream ------------------- */
 mm_status mm_num_modules(mm_ctx* ctx, int32_t* out_n);
 /* ids/n: capacity in *n on entry, count on return. */

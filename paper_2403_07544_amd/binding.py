@@ -28,7 +28,7 @@ KERNEL_CLASSES = ("gemm", "attn_fwd", "attn_bwd", "layernorm_fwd", "layernorm_bw
                   "embed_grad", "ce", "colsum", "adam", "other")
 
 EXPORTS = ("mm_create", "mm_destroy", "mm_register_module", "mm_route_task", "mm_train_step", "mm_translate_greedy", "mm_translate_beam",
-           "mm_last_loss", "mm_apply_update", "mm_num_modules", "mm_get_route", "mm_get_touched",
+           "mm_last_loss", "mm_apply_update", "mm_apply_update_noalloc", "mm_num_modules", "mm_get_route", "mm_get_touched",
            "mm_get_layout", "mm_get_params", "mm_set_params", "mm_get_grads", "mm_get_bucket_memory", "mm_set_grads",
            "mm_get_adam", "mm_get_working", "mm_debug_dump", "mm_debug_attention", "mm_profile", "mm_profile_read",
            "mm_last_error")
@@ -77,6 +77,7 @@ def load_library() -> C.CDLL:
         "mm_translate_beam": [vp, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp],
         "mm_last_loss": [vp, pf32],
         "mm_apply_update": [vp, vp, i32, f32],
+        "mm_apply_update_noalloc": [vp, vp, i32, f32],
         "mm_num_modules": [vp, pi32],
         "mm_get_route": [vp, i32, vp, pi32],
         "mm_get_touched": [vp, vp, i32],
@@ -235,6 +236,13 @@ class Context:
         else:
             ids = np.ascontiguousarray(module_ids, dtype=np.int32)
             self._check(self.lib.mm_apply_update(self.handle, _ptr(ids), len(ids), lr))
+
+    def mm_apply_update_noalloc(self, module_ids: Optional[Sequence[int]], lr: float):
+        if module_ids is None:
+            self._check(self.lib.mm_apply_update_noalloc(self.handle, None, 0, lr))
+        else:
+            ids = np.ascontiguousarray(module_ids, dtype=np.int32)
+            self._check(self.lib.mm_apply_update_noalloc(self.handle, _ptr(ids), len(ids), lr))
 
     # -- introspection ----------------------------------------------------------------------------
     def mm_num_modules(self) -> int:

@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <utility>
 #include <vector>
@@ -16,6 +17,15 @@
 #include "mm_kernels.h"
 
 using namespace mm;
+
+// Segment table of mm_apply_update_noalloc, which may not allocate: one array per GPU the library
+// runs on, held until the process ends.  In host code the name stands for the symbol only; the
+// device address is looked up once per device (scratch_address) and that pointer is what copies
+// and kernels receive.  All contexts of one GPU share the array.  (The compiler gives a static
+// device variable that host code names a visible symbol in the code object, which the lookup
+// needs; forcing its emission with the "used" attribute happens before that and leaves it local.)
+constexpr int NOALLOC_MAX_MODULES = MM_NOALLOC_MAX_MODULES;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_MAX_MODULES * sizeof(AdamSegment)];
 
 namespace {
 
@@ -82,6 +92,10 @@ struct mm_ctx {
   hipEvent_t ev_stage = nullptr, ev_done = nullptr;
   AdamSegment* seg_host = nullptr; AdamSegment* seg_dev = nullptr; int seg_cap = 0;
   hipEvent_t ev_seg = nullptr;
+  // mm_apply_update_noalloc: pinned table of fixed size (allocated at creation) and this device's
+  // address of the library's static device array
+  AdamSegment* seg_static_host = nullptr; AdamSegment* seg_static_dev = nullptr;
+  hipEvent_t ev_seg_static = nullptr;
   // table of the step's deferred weight-gradient products (pinned host copy, device copy)
   // (one pinned block and one device block: product table, first-tile table and the LayerNorm
   // reduction jobs are packed back to back and travel in one copy)
@@ -818,6 +832,25 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
 
 bool valid_module(mm_ctx* c, int id) { return id >= 0 && id < (int)c->mods.size(); }
 
+// This device's copy of the static array `scratch` (each GPU has its own, at its own address).
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_addr[MAX_DEVICES] = {};
+std::mutex g_scratch_mu;
+mm_status scratch_address(mm_ctx* c, void** out) {
+  int dev = -1;
+  HIP_TRY(c, hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(c, MM_EHIP, "device index %d outside [0, %d)", dev, MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_addr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(c, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(c, MM_EHIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_addr[dev] = p;
+  }
+  *out = g_scratch_addr[dev];
+  return MM_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Greedy translation of one batch of one task (section 3.2: only the task's own modules are
 // read).  The encoder runs once; each decoder layer keeps the q|k|v rows of the tokens written
@@ -1157,7 +1190,15 @@ mm_status mm_create(const mm_config* cfg, mm_ctx** out) {
   const size_t tab_bytes = MAX_GROUPED * (sizeof(GemmParams) + sizeof(int32_t)) + MAX_GROUPED_C * sizeof(LnReduceJob) + 64;
   guard(hipHostMalloc((void**)&c->tab_host, tab_bytes, hipHostMallocDefault), "hipHostMalloc(table)");
   guard(hipMalloc((void**)&c->tab_dev, tab_bytes), "hipMalloc(table)");
+  guard(hipHostMalloc((void**)&c->seg_static_host, NOALLOC_MAX_MODULES * sizeof(AdamSegment), hipHostMallocDefault), "hipHostMalloc(static table)");
+  guard(hipEventCreateWithFlags(&c->ev_seg_static, hipEventDisableTiming), "hipEventCreate");
   if (s != MM_OK) return s;
+  {
+    void* addr = nullptr;
+    s = scratch_address(c, &addr);
+    if (s != MM_OK) return s;
+    c->seg_static_dev = static_cast<AdamSegment*>(addr);
+  }
   guard(hipMemcpy(c->pe, pe.data(), pe.size() * 4, hipMemcpyHostToDevice), "hipMemcpy(pe)");
   c->flag = reinterpret_cast<int32_t*>(c->loss_dev + 1);   // loss and id-check flag leave in one copy
   guard(hipMemset(c->loss_dev, 0, 64), "hipMemset");
@@ -1179,6 +1220,8 @@ mm_status mm_destroy(mm_ctx* c) {
     if (c->result_host) hipHostFree(c->result_host);
     if (c->seg_host) hipHostFree(c->seg_host);
     if (c->seg_dev) hipFree(c->seg_dev);
+    if (c->seg_static_host) hipHostFree(c->seg_static_host);
+    if (c->ev_seg_static) hipEventDestroy(c->ev_seg_static);
     if (c->ws.base) hipFree(c->ws.base);
     for (auto& r : c->prof_recs) { hipEventDestroy(r.e); if (r.s) hipEventDestroy(r.s); }
     for (auto e : c->ev_pool) hipEventDestroy(e);
@@ -1407,7 +1450,7 @@ mm_status update_launch(mm_ctx* c, const int* use, int n_use, float lr, AdamSegm
   HIP_TRY(c, hipMemcpyAsync(dev_tab, host_tab, (size_t)n_use * sizeof(AdamSegment), hipMemcpyHostToDevice, c->st));
   HIP_TRY(c, hipEventRecord(ev, c->st));
   LaunchEvents le;
-  if (timed) {
+  if (timed) {   // (timing takes events from a pool that may grow: not for the allocation-free entry point)
     Run run{c, false};
     run.mark();
     le = run.begin_timed(MM_K_ADAM, work);
@@ -1574,6 +1617,18 @@ mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float
     c->seg_cap = cap;
   }
   return update_launch(c, use.data(), n_use, lr, c->seg_host, c->seg_dev, c->ev_seg, true);
+}
+
+mm_status mm_apply_update_noalloc(mm_ctx* c, const int32_t* module_ids, int32_t n, float lr) {
+  if (!c) return MM_EINVAL;
+  if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context cannot compute");
+  if (!c->seg_static_dev || !c->seg_static_host) return fail(c, MM_ESTATE, "the static segment table was not set up at creation");
+  resolve_pending(c);
+  int use[NOALLOC_MAX_MODULES + 1];
+  int n_use = 0;
+  mm_status s = select_updates(c, module_ids, n, use, NOALLOC_MAX_MODULES, &n_use);
+  if (s != MM_OK || n_use == 0) return s;
+  return update_launch(c, use, n_use, lr, c->seg_static_host, c->seg_static_dev, c->ev_seg_static, false);
 }
 
 // ---- introspection -----------------------------------------------------------------------------
