@@ -139,30 +139,29 @@ __global__ void embed_fwd_kernel(const T* __restrict__ E, const float* __restric
 constexpr int ROW_BITS = 14;  // rows < 16384, tokens < 2^17
 
 // Sorted position of key i = number of keys below it (keys are distinct: the row is part of the
-// key).  Each thread owns one key and compares it with every key of the batch, which pass through
-// LDS a chunk at a time (all lanes read the same address: a broadcast).  rows / 256 workgroups, no
-// ordering between them, no atomics, exact.
-constexpr int SORT_CHUNK = 2048;
+// key).  A workgroup owns 64 keys, one per lane; its four wavefronts each compare them with a
+// quarter of the batch's keys and the four counts are added through LDS.  The key a wavefront
+// compares against is the same for all its lanes, so the token ids arrive eight at a time through
+// wave-uniform loads; nothing is staged.  rows / 64 workgroups, no ordering between them, exact.
 __global__ void __launch_bounds__(256) rank_keys_kernel(const int32_t* __restrict__ tok, int rows,
                                                         uint32_t* __restrict__ keys) {
-  __shared__ __align__(16) uint32_t sk[SORT_CHUNK];
-  const int i = blockIdx.x * 256 + threadIdx.x;
+  __shared__ int part[4][64];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = blockIdx.x * 64 + lane;
   const uint32_t mine = i < rows ? (((uint32_t)tok[i] << ROW_BITS) | (uint32_t)i) : 0xffffffffu;
+  const int quarter = (((rows + 3) >> 2) + 7) & ~7;          // whole groups of eight
+  const int j0 = wave * quarter, j1 = min(rows, j0 + quarter);
   int rank = 0;
-  for (int base = 0; base < rows; base += SORT_CHUNK) {
-    __syncthreads();
-    for (int j = threadIdx.x; j < SORT_CHUNK; j += 256) {
-      const int g = base + j;
-      sk[j] = g < rows ? (((uint32_t)tok[g] << ROW_BITS) | (uint32_t)g) : 0xffffffffu;   // past the end: below nobody
-    }
-    __syncthreads();
-#pragma unroll 8
-    for (int j = 0; j < SORT_CHUNK; j += 4) {
-      const uint4 v = *reinterpret_cast<const uint4*>(&sk[j]);
-      rank += (int)(v.x < mine) + (int)(v.y < mine) + (int)(v.z < mine) + (int)(v.w < mine);
-    }
+  int j = j0;
+  for (; j + 8 <= j1; j += 8) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) rank += (int)((((uint32_t)tok[j + e] << ROW_BITS) | (uint32_t)(j + e)) < mine);
   }
-  if (i < rows) keys[rank] = mine;
+  for (; j < j1; ++j) rank += (int)((((uint32_t)tok[j] << ROW_BITS) | (uint32_t)j) < mine);
+  part[wave][lane] = rank;
+  __syncthreads();
+  if (wave == 0 && i < rows) keys[(part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])] = mine;
 }
 
 // Two passes so that the run of the most frequent token (hundreds of rows under a Zipf law) is not
@@ -740,15 +739,35 @@ __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict
   constexpr int NIT = ADAM_CHUNK / 1024;
   float4 g[NIT], th[NIT], m[NIT], v[NIT];
   int64_t idx[NIT];
+  bool rest[NIT];
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     idx[it] = base + it * 1024 + threadIdx.x * 4;
     const int64_t i = idx[it] < sg.len ? idx[it] : sg.len - 4;
-    g[it] = nt_ld4(sg.g + i); th[it] = nt_ld4(sg.theta + i);
+    g[it] = nt_ld4(sg.g + i);
     m[it] = nt_ld4(sg.m + i); v[it] = nt_ld4(sg.v + i);
+    if (sg.keep_g) th[it] = nt_ld4(sg.theta + i);
+  }
+  // Embedding tables (the modules whose bucket is cleared here): a row that has never received a
+  // gradient has g = m = v = 0, and for those values the update changes nothing - m and v stay 0
+  // and theta - lr * 0 / (0 + eps) is theta - so such pieces are left alone (nothing more is read,
+  // nothing is written); under a Zipf law most rows of a table are in that state.  The other
+  // pieces fetch theta now.
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    rest[it] = false;
+    if (!sg.keep_g) {
+      const uint32_t bits = (__float_as_uint(g[it].x) | __float_as_uint(g[it].y) | __float_as_uint(g[it].z) | __float_as_uint(g[it].w) |
+                             __float_as_uint(m[it].x) | __float_as_uint(m[it].y) | __float_as_uint(m[it].z) | __float_as_uint(m[it].w) |
+                             __float_as_uint(v[it].x) | __float_as_uint(v[it].y) | __float_as_uint(v[it].z) | __float_as_uint(v[it].w)) & 0x7fffffffu;
+      rest[it] = bits == 0u;
+      const int64_t i = idx[it] < sg.len ? idx[it] : sg.len - 4;
+      if (!rest[it]) th[it] = nt_ld4(sg.theta + i);
+    }
   }
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
+    if (rest[it]) continue;
     float* gp = &g[it].x; float* tp = &th[it].x; float* mp = &m[it].x; float* vp = &v[it].x;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -815,7 +834,7 @@ void launch_embed_fwd(hipStream_t st, Dtype dt, const void* E, const float* pe, 
 }
 
 void launch_sort_tokens(hipStream_t st, const int32_t* tok, int rows, uint32_t* keys) {
-  if (rows > 0) rank_keys_kernel<<<(rows + 255) / 256, 256, 0, st>>>(tok, rows, keys);
+  if (rows > 0) rank_keys_kernel<<<(rows + 63) / 64, 256, 0, st>>>(tok, rows, keys);
 }
 
 void launch_embed_grad(hipStream_t st, const uint32_t* keys, const float* dx, float* bucket, float* partial,

@@ -565,9 +565,13 @@ struct Step {
   }
 };
 
-// per parameter: g, theta, m, v read (16 B); theta, m, v written (12 B); bf16 copy (2 B).  The zeroing
-// of an embedding table's bucket is not counted: only the pieces that held a gradient are written.
-double work_bytes_adam(const mm_ctx* c, int64_t n) { return (double)n * (c->dt == BF16 ? 30.0 : 28.0); }
+// per parameter: g, theta, m, v read (16 B); theta, m, v written (12 B); bf16 copy (2 B).  An
+// embedding table is tallied with the 16 B of reads only: rows that never received a gradient
+// (g = m = v = 0, most rows under a Zipf law) are left alone by the kernel, how many is not known
+// on the host, and the zeroing of the bucket touches only the pieces that held a gradient.
+double work_bytes_adam(const mm_ctx* c, int64_t n, bool table) {
+  return (double)n * (table ? 16.0 : c->dt == BF16 ? 30.0 : 28.0);
+}
 
 mm_status collect_profile(mm_ctx* c) {
   if (c->prof_recs.empty()) return MM_OK;
@@ -1444,7 +1448,7 @@ mm_status update_launch(mm_ctx* c, const int* use, int n_use, float lr, AdamSegm
     sg.bc2 = (float)(1.0 - std::pow((double)c->cfg.adam_beta2, (double)m.t));
     sg.first_chunk = chunks; sg.keep_g = bucket_overwrites(m.kind);
     chunks += (int)((m.P + ADAM_CHUNK - 1) / ADAM_CHUNK);
-    work += work_bytes_adam(c, m.P);
+    work += work_bytes_adam(c, m.P, !bucket_overwrites(m.kind));
     m.touched = 0;
   }
   HIP_TRY(c, hipMemcpyAsync(dev_tab, host_tab, (size_t)n_use * sizeof(AdamSegment), hipMemcpyHostToDevice, c->st));
