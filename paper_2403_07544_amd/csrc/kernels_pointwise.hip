@@ -140,9 +140,9 @@ constexpr int ROW_BITS = 14;  // rows < 16384, tokens < 2^17
 
 // Sorted position of key i = number of keys below it (keys are distinct: the row is part of the
 // key).  A workgroup owns 64 keys, one per lane; its four wavefronts each compare them with a
-// quarter of the batch's keys and the four counts are added through LDS.  The key a wavefront
-// compares against is the same for all its lanes, so the token ids arrive eight at a time through
-// wave-uniform loads; nothing is staged.  rows / 64 workgroups, no ordering between them, exact.
+// quarter of the batch's keys and the four counts are added through LDS.  The keys to compare
+// against are fetched 64 at a time, one per lane (the next 64 are in flight meanwhile), and handed
+// round lane by lane.  rows / 64 workgroups, no ordering between them, no atomics, exact.
 __global__ void __launch_bounds__(256) rank_keys_kernel(const int32_t* __restrict__ tok, int rows,
                                                         uint32_t* __restrict__ keys) {
   __shared__ int part[4][64];
@@ -150,15 +150,20 @@ __global__ void __launch_bounds__(256) rank_keys_kernel(const int32_t* __restric
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int i = blockIdx.x * 64 + lane;
   const uint32_t mine = i < rows ? (((uint32_t)tok[i] << ROW_BITS) | (uint32_t)i) : 0xffffffffu;
-  const int quarter = (((rows + 3) >> 2) + 7) & ~7;          // whole groups of eight
+  const int quarter = (((rows + 3) >> 2) + 63) & ~63;         // whole groups of 64
   const int j0 = wave * quarter, j1 = min(rows, j0 + quarter);
+  auto fetch = [&](int j) -> uint32_t {                        // past the end: a key below nobody
+    const int g = j + lane;
+    return g < j1 ? (((uint32_t)tok[g] << ROW_BITS) | (uint32_t)g) : 0xffffffffu;
+  };
   int rank = 0;
-  int j = j0;
-  for (; j + 8 <= j1; j += 8) {
+  uint32_t cur = fetch(j0);
+  for (int j = j0; j < j1; j += 64) {
+    const uint32_t nxt = fetch(j + 64);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) rank += (int)((((uint32_t)tok[j + e] << ROW_BITS) | (uint32_t)(j + e)) < mine);
+    for (int l = 0; l < 64; ++l) rank += (int)((uint32_t)__builtin_amdgcn_readlane((int)cur, l) < mine);
+    cur = nxt;
   }
-  for (; j < j1; ++j) rank += (int)((((uint32_t)tok[j] << ROW_BITS) | (uint32_t)j) < mine);
   part[wave][lane] = rank;
   __syncthreads();
   if (wave == 0 && i < rows) keys[(part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])] = mine;

@@ -42,7 +42,10 @@ def tensor_report(ctx, orc: Oracle, module_ids):
             nr, na = float(np.linalg.norm(r)), float(np.linalg.norm(a))
             err = float(np.linalg.norm(a - r))
             cos = float(a @ r / (na * nr)) if na > 0 and nr > 0 else 1.0 if na == nr else 0.0
-            rows.append((j, s.name, err / nr if nr > 0 else np.inf, cos, nr, float(np.abs(a - r).max()), mod_norm, err))
+            # the module's gradient norm scaled to this tensor's size: what the tensor's norm would be if
+            # its elements had the module's root-mean-square size
+            scale = mod_norm * (s.size / max(1, m.total)) ** 0.5
+            rows.append((j, s.name, err / nr if nr > 0 else np.inf, cos, nr, float(np.abs(a - r).max()), scale, err, mod_norm))
         # alignment gaps must stay zero
         used = np.zeros(m.total, dtype=bool)
         for s in m.specs:
@@ -52,19 +55,27 @@ def tensor_report(ctx, orc: Oracle, module_ids):
 
 
 def check_grads(ctx, orc, module_ids, rel_tol, cos_tol, floor_frac, label=""):
-    """rel L2 <= rel_tol and cosine >= cos_tol per tensor.  A tensor whose reference norm is
-    below floor_frac of its module's gradient norm (key biases: zero by the softmax's shift
-    invariance) is instead required to have an error below rel_tol * floor_frac * module norm."""
+    """rel L2 <= rel_tol and cosine >= cos_tol per tensor.  A tensor whose elements are, by
+    root-mean-square, below floor_frac of the size of its module's gradient elements (key biases:
+    zero by the softmax's shift invariance) is instead required to have an error below rel_tol *
+    floor_frac * (the module's gradient norm).  (The comparison is per element, so that a small vector such as a LayerNorm
+    gain is not excused merely for being short next to a matrix.)"""
     worst = (0.0, None)
-    for j, name, rel, cos, nr, amax, mod_norm, err in tensor_report(ctx, orc, module_ids):
-        floor = floor_frac * mod_norm
-        if nr < floor:
-            assert err <= rel_tol * floor, f"{label} module {j} {name}: error {err:.3e} vs floor {floor:.3e}"
+    under_floor = []
+    for j, name, rel, cos, nr, amax, scale, err, mod_norm in tensor_report(ctx, orc, module_ids):
+        if nr < floor_frac * scale:
+            bound = rel_tol * floor_frac * mod_norm
+            assert err <= bound, f"{label} module {j} {name}: error {err:.3e} vs bound {bound:.3e}"
+            under_floor.append((name, nr / scale if scale > 0 else 0.0))
             continue
         assert rel <= rel_tol, f"{label} module {j} {name}: rel L2 {rel:.3e} > {rel_tol}"
         assert cos >= cos_tol, f"{label} module {j} {name}: cosine {cos:.6f} < {cos_tol}"
         if rel > worst[0]:
             worst = (rel, (j, name))
+    if under_floor:
+        kinds = sorted({n.split(".")[-1] for n, _ in under_floor})
+        say(f"  {label}: {len(under_floor)} tensors whose elements are below {floor_frac:g} of their module's gradient elements (rms), checked by absolute error: "
+            f"kinds {kinds}, largest share {max(f for _, f in under_floor):.2e}")
     return worst
 
 
