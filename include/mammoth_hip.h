@@ -165,10 +165,12 @@ mm_status mm_last_loss(mm_ctx* ctx, float* out_loss);
  * n_j > 0: g = bucket / n_j; t_j += 1; Adam step on the fp32 master with bias correction for
  * step t_j; working copy refreshed; bucket emptied; n_j = 0.  Modules with n_j = 0 are skipped:
  * not one byte of theirs is read or written.  module_ids NULL = every module.
- * A training step still in flight is settled first (the call waits for it): if its ids turned
- * out bad on the device it had no effect, its uses are not counted, and a module left without a
- * use gets no update; that step's status stays available from mm_last_loss.  The update itself is
- * enqueued and not waited for. */
+ * A training step whose ids turned out bad on the device had no effect: its uses are not
+ * counted, and a module left without a use gets no update.  That also holds for a step still in
+ * flight, without the call waiting for it: the update is enqueued behind the step and reads the
+ * step's verdict on the device; n_j and t_j as the host reports them (mm_get_touched,
+ * mm_get_adam) are settled when they are next asked for.  The step's status stays available from
+ * mm_last_loss.  The update itself is enqueued and not waited for. */
 mm_status mm_apply_update(mm_ctx* ctx, const int32_t* module_ids, int32_t n, float lr);
 
 /* mm_apply_update for callers that cannot allocate device or pinned memory inside the call (tight

@@ -6,6 +6,8 @@
 //                      path and the fallback for shapes the MFMA kernel does not take.
 //   gemm_mfma_kernel : bf16 MFMA kernel, LDS-staged 128x128 or 64x64 tiles.
 #include "mm_kernels.h"
+#include <algorithm>
+#include <vector>
 
 #include <hip/hip_ext.h>
 
@@ -880,6 +882,42 @@ __device__ __forceinline__ int remap_xcd(int bid, int total) {
   return x * q + (x < r ? x : r) + (bid >> 3);
 }
 
+// Logical tile number -> tile coordinates.  The tiles an XCD runs at the same time are consecutive
+// numbers (remap_xcd), a few dozen of them; they should share few operand panels, and the panels
+// they share with the tiles that follow should still be in that XCD's L2 (4 MB).  So the output is
+// walked in bands of TILE_BAND tile rows (or columns, along the axis with fewer tiles), within a
+// band across the other axis, within that band-wide step along the band: 64 consecutive tiles
+// cover 8 x 8 tiles, their 8 + 8 panels of K = 512 are 2 MB, and going on along the band keeps
+// the band's panels while the other operand streams through once per band.  (Walking the whole
+// short axis first, as an earlier version did, makes each XCD pull all of the smaller operand
+// through its L2 for every two panels of the larger one: 714 MB read for the generator's 36 MB.)
+constexpr int TILE_BAND = 8;
+__device__ __forceinline__ void tile_of(int L, int tiles_m, int tiles_n, int& tm, int& tn) {
+  const bool along_m = tiles_m <= tiles_n;             // bands lie along the axis with more tiles
+  const int ts = along_m ? tiles_m : tiles_n, tl = along_m ? tiles_n : tiles_m;
+  const int band = L / (TILE_BAND * tl);
+  const int r = L - band * TILE_BAND * tl;
+  const int h = min(TILE_BAND, ts - band * TILE_BAND);  // the last band may be lower
+  const int s = band * TILE_BAND + r % h, l = r / h;
+  tm = along_m ? s : l;
+  tn = along_m ? l : s;
+}
+
+// For a launch of many tiles with long K: XCD x takes the groups of GROUPED_COHORT consecutive
+// logical tiles numbered x, x + 8, x + 16, ...  An XCD (32 compute units, two workgroups each) runs
+// one such group at a time, and tiles running at the same time share operand panels through its
+// L2, so a product whose tiles fill one group exactly is read from HBM once.  The tail that does
+// not fill a round of eight groups is split into eight contiguous ranges.
+constexpr int GROUPED_COHORT = 64;
+__device__ __forceinline__ int remap_cohort(int bid, int total) {
+  const int full = total & ~(8 * GROUPED_COHORT - 1);
+  if (bid < full) {
+    const int x = bid & 7, i = bid >> 3;
+    return ((i / GROUPED_COHORT) * 8 + x) * GROUPED_COHORT + i % GROUPED_COHORT;
+  }
+  return full + remap_xcd(bid - full, total - full);
+}
+
 template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF, int DMA, bool PIPE = false>
 __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p_in) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -897,9 +935,7 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p_in) {
     if (ks > 0) { p.bias = nullptr; p.residual = nullptr; }
   }
   int tm, tn;
-  // walk along the axis of the SMALLER operand: it is re-read from L2 while the larger one streams
-  if ((int64_t)p.M <= (int64_t)p.N) { tm = L % tiles_m; tn = L / tiles_m; }
-  else { tn = L % tiles_n; tm = L / tiles_n; }
+  tile_of(L, tiles_m, tiles_n, tm, tn);
   gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, PF, false, DMA, PIPE>(p, tm * BM, tn * BN, lds);
 }
 
@@ -915,7 +951,7 @@ __global__ void __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) gemm_mfma
   __shared__ int local_tile;
   if (threadIdx.x == 0) {
     int lo = 0, hi = n_problems - 1;
-    const int t = remap_xcd(blockIdx.x, gridDim.x);
+    const int t = remap_cohort(blockIdx.x, gridDim.x);
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
       if (tile_start[mid] <= t) lo = mid; else hi = mid - 1;
@@ -949,8 +985,7 @@ __global__ void __launch_bounds__(256) gemm_mfma_multi_kernel(const GemmMulti mp
   const int L = t - mp.tile_start[i];
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   int tm, tn;
-  if ((int64_t)p.M <= (int64_t)p.N) { tm = L % tiles_m; tn = L / tiles_m; }
-  else { tn = L % tiles_n; tm = L / tiles_n; }
+  tile_of(L, tiles_m, tiles_n, tm, tn);
   gemm_mfma_tile<BM, BN, WM, WN, KCA, KCB, PF, false, DMA>(p, tm * BM, tn * BN, lds);
 }
 
@@ -1030,6 +1065,33 @@ constexpr int MM_GROUPED_PF = 2;   // K steps of global loads in flight in the g
 int gemm_grouped_tiles(const GemmParams& p) { return ((p.M + 127) / 128) * ((p.N + 127) / 128); }
 
 void gemm_prepare_grouped(GemmParams& p) { set_wide(p); }
+
+// Table order for the grouped launch: products whose tile count is a multiple of the group size
+// first, then the smaller ones packed into whole groups (first fit, largest first), then the
+// groups that stay partly empty, and last the large products that are no multiple of the group
+// size - so that as many products as possible start and end on a group boundary
+// (see remap_cohort).  The products are independent, so any order gives the same results.
+void gemm_grouped_order(const int* tiles, int n, int* order) {
+  constexpr int C = GROUPED_COHORT;
+  std::vector<int> whole, small, big;
+  for (int i = 0; i < n; ++i) (tiles[i] % C == 0 ? whole : tiles[i] < C ? small : big).push_back(i);
+  std::stable_sort(small.begin(), small.end(), [&](int a, int b) { return tiles[a] > tiles[b]; });
+  std::stable_sort(big.begin(), big.end(), [&](int a, int b) { return tiles[a] < tiles[b]; });
+  struct Bin { int fill; std::vector<int> items; };
+  std::vector<Bin> bins;
+  for (int i : small) {
+    size_t b = 0;
+    while (b < bins.size() && bins[b].fill + tiles[i] > C) ++b;
+    if (b == bins.size()) bins.push_back(Bin{0, {}});
+    bins[b].fill += tiles[i];
+    bins[b].items.push_back(i);
+  }
+  int k = 0;
+  for (int i : whole) order[k++] = i;
+  for (const Bin& b : bins) if (b.fill == C) for (int i : b.items) order[k++] = i;
+  for (const Bin& b : bins) if (b.fill != C) for (int i : b.items) order[k++] = i;
+  for (int i : big) order[k++] = i;
+}
 
 // 128x128 tiles: 256x256 ones (one workgroup per compute unit) were measured slower on the mix of
 // products a training step defers, also when only the generator's product used them.

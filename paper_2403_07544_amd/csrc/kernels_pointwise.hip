@@ -724,7 +724,8 @@ __global__ void __launch_bounds__(1024) sum_scaled_kernel(const float* __restric
 // Adam over a segment list
 // ----------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict__ segs, int n_segs,
-                                                   float lr, float beta1, float beta2, float eps) {
+                                                   float lr, float beta1, float beta2, float eps,
+                                                   const int32_t* __restrict__ step_flag) {
   // every product and sum below is rounded on its own (no fused multiply-add), so the update is
   // the same fp32 operation sequence as the textbook formulas written one operation at a time
 #pragma clang fp contract(off)
@@ -736,6 +737,10 @@ __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict
     if (segs[mid].first_chunk <= chunk) lo = mid; else hi = mid - 1;
   }
   const AdamSegment sg = segs[lo];
+  // the step that filled the buckets may still have been running when this update was enqueued:
+  // had it found bad ids it counted for nothing, and a module it alone had used gets no update
+  const float n_uses = (step_flag && *step_flag != 0) ? sg.n_uses_alt : sg.n_uses;
+  if (n_uses == 0.f) return;
   const int64_t base = (int64_t)(chunk - sg.first_chunk) * ADAM_CHUNK;
   const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
   // all of the chunk's loads are issued before the first result is needed (16 x 16 bytes in
@@ -776,7 +781,7 @@ __global__ void __launch_bounds__(256) adam_kernel(const AdamSegment* __restrict
     float* gp = &g[it].x; float* tp = &th[it].x; float* mp = &m[it].x; float* vp = &v[it].x;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float ge = gp[e] / sg.n_uses;
+      const float ge = gp[e] / n_uses;
       mp[e] = beta1 * mp[e] + omb1 * ge;
       vp[e] = beta2 * vp[e] + omb2 * ge * ge;
       const float mh = mp[e] / sg.bc1, vh = vp[e] / sg.bc2;
@@ -944,10 +949,10 @@ void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float
 }
 
 void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int total_chunks, float lr,
-                 float beta1, float beta2, float eps, const LaunchEvents& ev) {
+                 float beta1, float beta2, float eps, const int32_t* step_flag, const LaunchEvents& ev) {
   if (total_chunks > 0)
     hipExtLaunchKernelGGL(adam_kernel, dim3(total_chunks), dim3(256), 0, st, ev.start, ev.stop, 0, segs_dev, n_segs, lr,
-                          beta1, beta2, eps);
+                          beta1, beta2, eps, step_flag);
 }
 
 void launch_to_bf16(hipStream_t st, const float* src, bf16_t* dst, int64_t n) {

@@ -91,6 +91,9 @@ bool gemm_can_split_k(Dtype dt, const GemmParams& p);
 bool gemm_groupable(Dtype dt, const GemmParams& p);
 int gemm_grouped_tiles(const GemmParams& p);
 void gemm_prepare_grouped(GemmParams& p);  // call on each table entry before upload
+// order[0..n): the table order that lets the most products begin and end on a boundary of the
+// groups of tiles one XCD runs at a time; tiles[i] = gemm_grouped_tiles of product i.
+void gemm_grouped_order(const int* tiles, int n, int* order);
 void launch_gemm_grouped_tn(hipStream_t st, const GemmParams* table_dev, const int32_t* tile_start_dev,
                             int n_problems, int total_tiles, const LaunchEvents& ev = LaunchEvents());
 // Up to GEMM_MULTI_MAX independent products of the same kind (transA = 0, same transB, no split K)
@@ -192,12 +195,17 @@ struct AdamSegment {
   float* theta; float* m; float* v; float* g; bf16_t* w16;  // w16 null in fp32 contexts
   int64_t len;                                               // multiple of 64
   float n_uses, bc1, bc2;                                    // n_j, 1-beta1^t, 1-beta2^t
+  float n_uses_alt;                                          // n_j to use instead when *step_flag != 0 (0: leave the segment alone)
   int32_t first_chunk;                                       // running chunk index of this segment
   int32_t keep_g;                                            // leave g as it is (its next use overwrites it)
 };
 static const int ADAM_CHUNK = 4096;
+// step_flag (device, may be null): the word a training step still in flight sets when it finds bad
+// ids.  The kernel reads it when it runs: nonzero selects n_uses_alt, the use counts without that
+// step, and a segment whose count is then 0 is not touched at all.
 void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int total_chunks,
-                 float lr, float beta1, float beta2, float eps, const LaunchEvents& ev = LaunchEvents());
+                 float lr, float beta1, float beta2, float eps, const int32_t* step_flag,
+                 const LaunchEvents& ev = LaunchEvents());
 
 // ---------------------------------------------------------------------------------------------
 // greedy translation: one new query per sentence over cached keys/values; next-token pick

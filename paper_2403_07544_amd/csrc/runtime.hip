@@ -43,6 +43,7 @@ struct Module {
   bf16_t* w16 = nullptr;
   int touched = 0;
   int64_t t = 0;
+  bool t_on_trust = false;   // t was raised by an update enqueued behind a step whose outcome was not known yet
 };
 
 struct Route { std::vector<int> ids; int src = -1, tgt = -1, gen = -1, ad_enc = -1, ad_dec = -1; std::vector<int> enc, dec; };
@@ -457,12 +458,16 @@ struct Step {
     LnReduceJob* ljob = reinterpret_cast<LnReduceJob*>(c->tab_host + off_jobs);
     int tiles = 0, blocks = 0;
     double flops = 0;
+    std::vector<int> ntile(ng), order(ng);
+    for (size_t i = 0; i < ng; ++i) ntile[i] = gemm_grouped_tiles(deferred[i]);
+    gemm_grouped_order(ntile.data(), (int)ng, order.data());
     for (size_t i = 0; i < ng; ++i) {
-      gemm_prepare_grouped(deferred[i]);
-      gtab[i] = deferred[i];
+      GemmParams& p = deferred[order[i]];
+      gemm_prepare_grouped(p);
+      gtab[i] = p;
       gstart[i] = tiles;
-      tiles += gemm_grouped_tiles(deferred[i]);
-      flops += 2.0 * deferred[i].M * deferred[i].N * deferred[i].K;
+      tiles += ntile[order[i]];
+      flops += 2.0 * p.M * p.N * p.K;
     }
     for (size_t i = 0; i < nl; ++i) {
       jobs[i].first_block = blocks;
@@ -597,18 +602,37 @@ mm_status resolve_pending(mm_ctx* c) {
   int32_t flag;
   memcpy(&flag, &c->result_host[1], 4);
   if (flag != 0) {
-    for (int j : c->routes[c->pending_task].ids)
-      if (c->mods[j].touched > 0) c->mods[j].touched -= 1;
+    // the step counted for nothing.  A module that an update enqueued behind it was to change on
+    // this step's account alone was left alone by the kernel: its update count goes back too.
+    for (int j : c->routes[c->pending_task].ids) {
+      Module& m = c->mods[j];
+      if (m.t_on_trust) { m.t -= 1; m.t_on_trust = false; }
+      else if (m.touched > 0) m.touched -= 1;
+    }
     c->last_status = fail(c, MM_ERANGE, flag & 1 ? "token id outside [0, vocab) (found on the device); step had no effect"
                                                  : "non-pad id after the end of a sentence (found on the device); step had no effect");
     return c->last_status;
   }
+  for (int j : c->routes[c->pending_task].ids) c->mods[j].t_on_trust = false;
   if (!std::isfinite(c->last_loss)) {
     c->last_status = fail(c, MM_ENONFINITE, "loss is not finite");
     return c->last_status;
   }
   c->last_status = MM_OK;
   return MM_OK;
+}
+
+// Before an update: settles the step in flight if it has finished (no wait).  Returns true if it
+// is still running; the update is then enqueued behind it and decides on the device
+// (AdamSegment::n_uses_alt), so that the host does not have to wait for the step's end.
+bool step_still_running(mm_ctx* c) {
+  if (!c->pending) return false;
+  if (hipEventQuery(c->ev_done) != hipSuccess) {
+    (void)hipGetLastError();   // "not ready" is an answer, not an error
+    return true;
+  }
+  resolve_pending(c);
+  return false;
 }
 
 mm_status ensure_stage(mm_ctx* c, size_t n_ints) {
@@ -1430,11 +1454,14 @@ mm_status select_updates(mm_ctx* c, const int32_t* module_ids, int n, int* use, 
 // Renormalise-and-Adam over the selected modules (Algorithm 1's division by n_j, then the
 // optimiser): fills the segment table in host_tab (pinned), uploads it to dev_tab and launches
 // one kernel over all segments.  ev guards host_tab against being refilled before its previous
-// upload has left it.  The caller has settled the step in flight: a step whose ids turned out bad
-// on the device had no effect, its use counts were taken back, and modules left without a use
-// were not selected (no gradient, no update).
+// upload has left it.  A step whose ids turned out bad on the device had no effect (its gradients
+// are exact zeros) and counts for nothing.  If the step in flight has been settled (running ==
+// false) its use counts were taken back already and modules left without a use were not selected.
+// If it is still running, every segment also carries the count without that step and the kernel
+// picks one of the two from the step's flag word; resolve_pending() later repairs the host's
+// bookkeeping the same way.
 mm_status update_launch(mm_ctx* c, const int* use, int n_use, float lr, AdamSegment* host_tab, AdamSegment* dev_tab,
-                        hipEvent_t ev, bool timed) {
+                        hipEvent_t ev, bool timed, bool running) {
   HIP_TRY(c, hipEventSynchronize(ev));
   int chunks = 0;
   double work = 0;
@@ -1444,6 +1471,11 @@ mm_status update_launch(mm_ctx* c, const int* use, int n_use, float lr, AdamSegm
     AdamSegment& sg = host_tab[i];
     sg.theta = m.theta; sg.m = m.m; sg.v = m.v; sg.g = m.g; sg.w16 = m.w16; sg.len = m.P;
     sg.n_uses = (float)m.touched;
+    int without = m.touched;
+    if (running)
+      for (int j : c->routes[c->pending_task].ids) without -= (j == use[i]);
+    sg.n_uses_alt = (float)(without > 0 ? without : 0);
+    m.t_on_trust = running && without <= 0;
     sg.bc1 = (float)(1.0 - std::pow((double)c->cfg.adam_beta1, (double)m.t));
     sg.bc2 = (float)(1.0 - std::pow((double)c->cfg.adam_beta2, (double)m.t));
     sg.first_chunk = chunks; sg.keep_g = bucket_overwrites(m.kind);
@@ -1459,7 +1491,8 @@ mm_status update_launch(mm_ctx* c, const int* use, int n_use, float lr, AdamSegm
     run.mark();
     le = run.begin_timed(MM_K_ADAM, work);
   }
-  launch_adam(c->st, dev_tab, n_use, chunks, lr, c->cfg.adam_beta1, c->cfg.adam_beta2, c->cfg.adam_eps, le);
+  launch_adam(c->st, dev_tab, n_use, chunks, lr, c->cfg.adam_beta1, c->cfg.adam_beta2, c->cfg.adam_eps,
+              running ? c->flag : nullptr, le);
   HIP_TRY(c, hipGetLastError());
   return MM_OK;
 }
@@ -1605,7 +1638,7 @@ mm_status mm_last_loss(mm_ctx* c, float* out_loss) {
 mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float lr) {
   if (!c) return MM_EINVAL;
   if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context cannot compute");
-  resolve_pending(c);   // see update_launch
+  const bool running = step_still_running(c);   // see update_launch
   std::vector<int> use(c->mods.size() + 1);
   int n_use = 0;
   mm_status s = select_updates(c, module_ids, n, use.data(), (int)c->mods.size(), &n_use);
@@ -1620,19 +1653,22 @@ mm_status mm_apply_update(mm_ctx* c, const int32_t* module_ids, int32_t n, float
     HIP_TRY(c, hipMalloc((void**)&c->seg_dev, cap * sizeof(AdamSegment)));
     c->seg_cap = cap;
   }
-  return update_launch(c, use.data(), n_use, lr, c->seg_host, c->seg_dev, c->ev_seg, true);
+  return update_launch(c, use.data(), n_use, lr, c->seg_host, c->seg_dev, c->ev_seg, true, running);
 }
 
 mm_status mm_apply_update_noalloc(mm_ctx* c, const int32_t* module_ids, int32_t n, float lr) {
   if (!c) return MM_EINVAL;
   if (c->plan_only) return fail(c, MM_ESTATE, "plan-only context cannot compute");
   if (!c->seg_static_dev || !c->seg_static_host) return fail(c, MM_ESTATE, "the static segment table was not set up at creation");
-  resolve_pending(c);
+  // With a step still running the selection may hold modules that a settled bad step would have
+  // dropped; if the table cannot take them all, wait for the step and select again.
+  bool running = step_still_running(c);
+  if (running && (int64_t)c->mods.size() > NOALLOC_MAX_MODULES) { resolve_pending(c); running = false; }
   int use[NOALLOC_MAX_MODULES + 1];
   int n_use = 0;
   mm_status s = select_updates(c, module_ids, n, use, NOALLOC_MAX_MODULES, &n_use);
   if (s != MM_OK || n_use == 0) return s;
-  return update_launch(c, use, n_use, lr, c->seg_static_host, c->seg_static_dev, c->ev_seg_static, false);
+  return update_launch(c, use, n_use, lr, c->seg_static_host, c->seg_static_dev, c->ev_seg_static, false, running);
 }
 
 // ---- introspection -----------------------------------------------------------------------------
@@ -1719,7 +1755,7 @@ mm_status mm_get_adam(mm_ctx* c, int32_t module, float* m, float* v, int64_t n, 
   if (s != MM_OK) return s;
   if (m) { s = copy_out(c, c->mods[module].m, m, n); if (s != MM_OK) return s; }
   if (v) { s = copy_out(c, c->mods[module].v, v, n); if (s != MM_OK) return s; }
-  if (t_j) *t_j = c->mods[module].t;
+  if (t_j) { resolve_pending(c); *t_j = c->mods[module].t; }
   return MM_OK;
 }
 

@@ -177,11 +177,25 @@ def test_non_finite_loss_is_reported():
     ctx.close()
 
 
-def test_bad_device_ids_then_update_changes_nothing():
+def _keep_gpu_busy():
+    """Enqueues some tens of milliseconds of unrelated work on the stream the context uses (the
+    default one), so that what the test enqueues next is still waiting when the host moves on."""
+    import torch
+    x = torch.ones(8192, 8192, device="cuda")
+    for _ in range(6):
+        x = (x @ x) * 1e-4
+    return x
+
+
+@pytest.mark.parametrize("step_still_running", [False, True])
+def test_bad_device_ids_then_update_changes_nothing(step_still_running):
     """A step enqueued without waiting (out_loss NULL) whose device-resident ids are bad, followed
     by the update: the step had no effect, so no module may take an update - parameters, Adam state
-    and step counts bit-unchanged, use counts as the oracle's - for all modules and for a subset."""
+    and step counts bit-unchanged, use counts as the oracle's - for all modules and for a subset.
+    With step_still_running the GPU is kept busy, so the update is enqueued while the step has not
+    run yet and the kernel itself has to take the step's verdict into account."""
     import torch
+    hold = _keep_gpu_busy if step_still_running else (lambda: None)
     setup = tiny_setup(d=32, H=2, F_=64, V=56, n_lang=3, adapter_dim=16, dtype="bf16", max_len=24)
     ctx, orc = make_pair(setup)
     names = [n for n, _ in setup.tasks]
@@ -207,6 +221,7 @@ def test_bad_device_ids_then_update_changes_nothing():
             assert np.array_equal(m, m2) and np.array_equal(v, v2) and t == t2 == 0, j
 
     # round 1: update only modules that nothing but the bad step used
+    hold()
     assert ctx.mm_train_step(t01, src, tgt, batch.lengths, sync=False) is None
     ctx.mm_apply_update(only_01, 1e-3)
     with pytest.raises(MMError) as ei:
@@ -217,6 +232,7 @@ def test_bad_device_ids_then_update_changes_nothing():
     for j in orc.routes[t21]:
         assert ctx.mm_get_adam(j)[2] == 0
     # round 2: update everything: modules of the good step move once with n_j = 1, the others not at all
+    hold()
     assert ctx.mm_train_step(t01, src, tgt, batch.lengths, sync=False) is None
     ctx.mm_apply_update(None, 1e-3)
     with pytest.raises(MMError) as ei:
@@ -228,6 +244,19 @@ def test_bad_device_ids_then_update_changes_nothing():
     for j in orc.routes[t21]:
         assert ctx.mm_get_adam(j)[2] == 1
         assert np.abs(ctx.mm_get_params(j) - orc.modules[j].theta).max() <= 2.5e-3
+    # round 3: a good step of 0-1 and the update behind it, again without waiting in between
+    hold()
+    assert ctx.mm_train_step(t01, batch.src_ids, batch.tgt_ids, batch.lengths, sync=False) is None
+    ctx.mm_apply_update(None, 1e-3)
+    orc.train_step(t01, batch.src_ids, batch.tgt_ids, batch.lengths)
+    orc.apply_update(None, 1e-3)
+    ctx.mm_last_loss()
+    check_touched(ctx, orc)
+    for j in range(n_mod):
+        assert ctx.mm_get_adam(j)[2] == orc.modules[j].t, j
+        assert np.abs(ctx.mm_get_params(j) - orc.modules[j].theta).max() <= 5e-3, j
+    for j in only_01:
+        assert not np.array_equal(before[j][0], ctx.mm_get_params(j)), j
     ctx.close()
 
 
