@@ -168,7 +168,7 @@ mm_status mm_last_loss(mm_ctx* ctx, float* out_loss);
  * A training step whose ids turned out bad on the device had no effect: its uses are not
  * counted, and a module left without a use gets no update.  That also holds for a step still in
  * flight, without the call waiting for it: the update is enqueued behind the step and reads the
- * step's verdict on the device; n_j and t_j as the host reports them (mm_get_touched,
+ * step's outcome on the device; n_j and t_j as the host reports them (mm_get_touched,
  * mm_get_adam) are settled when they are next asked for.  The step's status stays available from
  * mm_last_loss.  The update itself is enqueued and not waited for. */
 mm_status mm_apply_update(mm_ctx* ctx, const int32_t* module_ids, int32_t n, float lr);

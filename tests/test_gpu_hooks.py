@@ -193,7 +193,7 @@ def test_bad_device_ids_then_update_changes_nothing(step_still_running):
     by the update: the step had no effect, so no module may take an update - parameters, Adam state
     and step counts bit-unchanged, use counts as the oracle's - for all modules and for a subset.
     With step_still_running the GPU is kept busy, so the update is enqueued while the step has not
-    run yet and the kernel itself has to take the step's verdict into account."""
+    run yet and the kernel itself has to take the outcome of the step into account."""
     import torch
     hold = _keep_gpu_busy if step_still_running else (lambda: None)
     setup = tiny_setup(d=32, H=2, F_=64, V=56, n_lang=3, adapter_dim=16, dtype="bf16", max_len=24)
@@ -220,7 +220,7 @@ def test_bad_device_ids_then_update_changes_nothing(step_still_running):
             assert np.array_equal(th, ctx.mm_get_params(j)) and np.array_equal(w, ctx.mm_get_working(j)), j
             assert np.array_equal(m, m2) and np.array_equal(v, v2) and t == t2 == 0, j
 
-    # round 1: update only modules that nothing but the bad step used
+    # part 1: update only modules that nothing but the bad step used
     hold()
     assert ctx.mm_train_step(t01, src, tgt, batch.lengths, sync=False) is None
     ctx.mm_apply_update(only_01, 1e-3)
@@ -231,7 +231,7 @@ def test_bad_device_ids_then_update_changes_nothing(step_still_running):
     only_01_unchanged()
     for j in orc.routes[t21]:
         assert ctx.mm_get_adam(j)[2] == 0
-    # round 2: update everything: modules of the good step move once with n_j = 1, the others not at all
+    # part 2: update everything: modules of the good step move once with n_j = 1, the others not at all
     hold()
     assert ctx.mm_train_step(t01, src, tgt, batch.lengths, sync=False) is None
     ctx.mm_apply_update(None, 1e-3)
@@ -244,7 +244,7 @@ def test_bad_device_ids_then_update_changes_nothing(step_still_running):
     for j in orc.routes[t21]:
         assert ctx.mm_get_adam(j)[2] == 1
         assert np.abs(ctx.mm_get_params(j) - orc.modules[j].theta).max() <= 2.5e-3
-    # round 3: a good step of 0-1 and the update behind it, again without waiting in between
+    # part 3: a good step of 0-1 and the update behind it, again without waiting in between
     hold()
     assert ctx.mm_train_step(t01, batch.src_ids, batch.tgt_ids, batch.lengths, sync=False) is None
     ctx.mm_apply_update(None, 1e-3)
