@@ -189,6 +189,10 @@ def _keep_gpu_busy():
 
 @pytest.mark.parametrize("step_still_running", [False, True])
 def test_bad_device_ids_then_update_changes_nothing(step_still_running):
+    bad_ids_then_update(step_still_running, "mm_apply_update")
+
+
+def bad_ids_then_update(step_still_running, entry):
     """A step enqueued without waiting (out_loss NULL) whose device-resident ids are bad, followed
     by the update: the step had no effect, so no module may take an update - parameters, Adam state
     and step counts bit-unchanged, use counts as the oracle's - for all modules and for a subset.
@@ -198,6 +202,7 @@ def test_bad_device_ids_then_update_changes_nothing(step_still_running):
     hold = _keep_gpu_busy if step_still_running else (lambda: None)
     setup = tiny_setup(d=32, H=2, F_=64, V=56, n_lang=3, adapter_dim=16, dtype="bf16", max_len=24)
     ctx, orc = make_pair(setup)
+    apply_update = getattr(ctx, entry)
     names = [n for n, _ in setup.tasks]
     batch = tiny_batch(setup)
     t01, t21 = names.index("0-1"), names.index("2-1")
@@ -223,7 +228,7 @@ def test_bad_device_ids_then_update_changes_nothing(step_still_running):
     # part 1: update only modules that nothing but the bad step used
     hold()
     assert ctx.mm_train_step(t01, src, tgt, batch.lengths, sync=False) is None
-    ctx.mm_apply_update(only_01, 1e-3)
+    apply_update(only_01, 1e-3)
     with pytest.raises(MMError) as ei:
         ctx.mm_last_loss()
     assert ei.value.status == MM_ERANGE
@@ -234,7 +239,7 @@ def test_bad_device_ids_then_update_changes_nothing(step_still_running):
     # part 2: update everything: modules of the good step move once with n_j = 1, the others not at all
     hold()
     assert ctx.mm_train_step(t01, src, tgt, batch.lengths, sync=False) is None
-    ctx.mm_apply_update(None, 1e-3)
+    apply_update(None, 1e-3)
     with pytest.raises(MMError) as ei:
         ctx.mm_last_loss()
     assert ei.value.status == MM_ERANGE
@@ -247,7 +252,7 @@ def test_bad_device_ids_then_update_changes_nothing(step_still_running):
     # part 3: a good step of 0-1 and the update behind it, again without waiting in between
     hold()
     assert ctx.mm_train_step(t01, batch.src_ids, batch.tgt_ids, batch.lengths, sync=False) is None
-    ctx.mm_apply_update(None, 1e-3)
+    apply_update(None, 1e-3)
     orc.train_step(t01, batch.src_ids, batch.tgt_ids, batch.lengths)
     orc.apply_update(None, 1e-3)
     ctx.mm_last_loss()

@@ -81,3 +81,11 @@ def test_noalloc_update_refuses_more_modules_than_its_table_holds():
     assert ctx.mm_get_touched().tolist() == [0] * 256 + [1] * 4
     assert ctx.mm_get_adam(ids[255])[2] == 1 and ctx.mm_get_adam(ids[256])[2] == 0
     ctx.close()
+
+
+@pytest.mark.parametrize("step_still_running", [False, True])
+def test_noalloc_update_behind_a_step_with_bad_ids(step_still_running):
+    """The same sequence as the allocating entry point's test: a step with bad device-resident ids,
+    enqueued without waiting, then the update - also while the step has not run yet."""
+    from tests.test_gpu_hooks import bad_ids_then_update
+    bad_ids_then_update(step_still_running, "mm_apply_update_noalloc")
