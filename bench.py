@@ -29,8 +29,9 @@ PEAK_F32_FLOPS = 157.3e12  # fp32 vector
 PEAK_HBM = 8.0e12
 
 
-def cpu_baseline(setup, batch, target_tokens=4096):
-    """The CPU oracle (fp64 numpy, as it stands) on one batch (about 10 s on the box's 16 cores)."""
+def cpu_baseline(setup, batch, target_tokens=4096, reps=3):
+    """The CPU oracle (fp64 numpy, as it stands): reps steps and updates on one batch (about 5 s
+    each on the box's 16 cores)."""
     import numpy as np
     from threadpoolctl import threadpool_info
 
@@ -46,12 +47,13 @@ def cpu_baseline(setup, batch, target_tokens=4096):
     tgt = batch.tgt_ids[:n, :int(lengths[:, 1].max())]
     orc = build_from_setup(setup, dtype=np.float64, fill_params=mm_synth.fill_params)
     t0 = time.perf_counter()
-    orc.train_step(0, src, tgt, lengths)
-    orc.apply_update(None, setup.shape.lr)
+    for _ in range(reps):
+        orc.train_step(0, src, tgt, lengths)
+        orc.apply_update(None, setup.shape.lr)
     dt = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    return {"value": tok / dt, "unit": "target tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"fwd+bwd+Adam of the fp64 numpy oracle on the first {n} sentence pairs "
+    return {"value": reps * tok / dt, "unit": "target tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{reps} x (fwd+bwd+Adam) of the fp64 numpy oracle on the first {n} sentence pairs "
                       f"({tok} target tokens) of one batch, {dt:.1f} s"}
 
 
