@@ -248,7 +248,14 @@ __global__ void __launch_bounds__(256) attn_bwd_kernel(const AttnParams p) {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
-__device__ __forceinline__ int swz64(int row) { return ((row >> 1) & 7) ^ ((row >> 4) & 3); }
+// Slot swizzle of a [rows][64] bf16 tile (eight 16-byte slots per 128-byte row; the LDS has 64
+// banks, so rows of different parity never meet).  Two access shapes must both spread over the
+// banks: a row fragment (one pass = 16 consecutive rows, the same chunk of each: the 8 rows of one
+// parity need 8 different slots) and a transposing read (4 or 8 consecutive rows, the same two or
+// four adjacent chunks of each: rows 2 apart must differ in the slot's top bit, rows 4 apart in
+// the middle one).  Reversing the three bits of row / 2 does both (measured: no bank conflicts
+// in either; the plain (row / 2) & 7 made every transposing read take two passes).
+__device__ __forceinline__ int swz64(int row) { return ((row & 2) << 1) | ((row >> 1) & 2) | ((row >> 3) & 1); }
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return pack2_bf16(a, b);
 }
@@ -319,8 +326,9 @@ __device__ __forceinline__ bf16x8_t frag_from_regs(const float* v) {
 // owns output row lcol and, per register group g4 of column tile ct, the four consecutive columns
 // ct*32 + 8*g4 + 4*hh ...  Written from there each store instruction would put 16 bytes into each
 // of 32 different rows.  Each half of the tile (32 columns) goes through the wavefront's own 2 KB
-// LDS patch instead (rows of 64 bytes, 16-byte chunk c of row r in slot c ^ (r & 3)) and leaves
-// as 64-byte row pieces, four lanes per row.  Only LDS traffic of this wavefront is involved, so
+// LDS patch instead (rows of 64 bytes, the 8-byte piece p of row r at position p ^ ((r >> 1) & 7),
+// so that the 16 rows one pass of a write touches use all banks) and leaves as 64-byte row
+// pieces, four lanes per row.  Only LDS traffic of this wavefront is involved, so
 // a wavefront-level fence orders the patch writes before the reads; no workgroup barrier.
 constexpr int STORE_PATCH_BYTES = 2048;
 __device__ __forceinline__ void store_tile_rows(unsigned char* patch, const f32x16_t (&acc)[2], bf16_t* dst0, int64_t ld,
@@ -333,7 +341,7 @@ __device__ __forceinline__ void store_tile_rows(unsigned char* patch, const f32x
       uint2 o;
       o.x = pack_bf16(acc[ct][4 * g4 + 0], acc[ct][4 * g4 + 1]);
       o.y = pack_bf16(acc[ct][4 * g4 + 2], acc[ct][4 * g4 + 3]);
-      *reinterpret_cast<uint2*>(patch + lcol * 64 + ((g4 ^ (lcol & 3)) << 4) + (hh << 3)) = o;
+      *reinterpret_cast<uint2*>(patch + lcol * 64 + ((((g4 << 1) | hh) ^ ((lcol >> 1) & 7)) << 3)) = o;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -341,7 +349,11 @@ __device__ __forceinline__ void store_tile_rows(unsigned char* patch, const f32x
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int row = 16 * i + (lane >> 2), c = lane & 3;
-      const uint4 v = *reinterpret_cast<const uint4*>(patch + row * 64 + ((c ^ (row & 3)) << 4));
+      // pieces 2c and 2c + 1 sit next to each other at positions (2c) ^ x and (2c + 1) ^ x: one
+      // 16-byte read, halves exchanged when x is odd
+      const int x = (row >> 1) & 7;
+      uint4 v = *reinterpret_cast<const uint4*>(patch + row * 64 + ((c ^ (x >> 1)) << 4));
+      if (x & 1) v = make_uint4(v.z, v.w, v.x, v.y);
       if (row < rows_valid) *reinterpret_cast<uint4*>(dst0 + (int64_t)row * ld + ct * 32 + c * 8) = v;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the patch is free again once these reads are done
