@@ -166,6 +166,9 @@ template <int R, bool KC>
 struct TileLoader {
   static constexpr int NL = KC ? R / 32 : (R >= 128 ? R / 128 : 1);  // work items per thread
   static constexpr int NV = KC ? NL : NL * 4;                          // 16-byte registers per K step
+  // row-contiguous tiles of 128 or 256 rows give every one of the 256 threads a k-row quad inside
+  // the 64 k rows of a tile (R = 64 leaves half the threads without one): no test, no branch
+  static constexpr bool ALL_ITEMS = KC || R >= 128;
   const bf16_t* ptr[NL];      // item address at k = 0
   int klim[NL];               // KC: item valid while k0 < klim; else: k row j valid while k0 + j < klim
   int off[KC ? NL : NL * 4];  // LDS byte offsets inside the tile (row-contiguous operand: one per k row)
@@ -261,7 +264,7 @@ struct TileLoader {
     } else {
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
-        if (off[i * 4] < 0) continue;
+        if (!ALL_ITEMS && off[i * 4] < 0) continue;
 #pragma unroll
         for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4_t*>(lds + off[i * 4 + j]) = v[i * 4 + j];
       }
@@ -294,7 +297,7 @@ struct TileLoader {
       const char* b = ubase + ((int64_t)(k_ld + Q) * ld) * 2;
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
-        if (off[i * 4] >= 0)
+        if (ALL_ITEMS || off[i * 4] >= 0)
           *reinterpret_cast<u32x4_t*>(lds + off[i * 4 + Q]) = (F || k_st + Q < klim[i]) ? v[i * 4 + Q] : zero;
         if (F) v[i * 4 + Q] = *(global_u4_ptr)(b + voff[i]);
         else v[i * 4 + Q] = load16_global(k_ld + Q < klim[i] ? ptr[i] + (int64_t)(k_ld + Q) * ld : safe);
@@ -311,7 +314,7 @@ struct TileLoader {
     } else {
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
-        if (off[i * 4] < 0) continue;
+        if (!ALL_ITEMS && off[i * 4] < 0) continue;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           *reinterpret_cast<u32x4_t*>(lds + off[i * 4 + j]) = k0 + j < klim[i] ? v[i * 4 + j] : zero;
