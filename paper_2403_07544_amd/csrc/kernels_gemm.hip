@@ -350,7 +350,10 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts");
   constexpr int MT = WM / 32, NT = WN / 32;
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // the wavefront's number is the same in all its lanes: held in a scalar register, so that what
+  // derives from it (the LDS destination of a direct-to-LDS load goes through M0) needs no
+  // lane-to-scalar moves inside the K loop
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int wm = wave / (BN / WN), wn = wave % (BN / WN);
 
   static_assert(!DMA || (KCA && !CS), "direct-to-LDS loads need a k-contiguous A");
@@ -665,16 +668,24 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     constexpr int KEEP = (DMA - 2) * LPW;        // loads that may stay in flight at the top of a step
     for (int t = 0; t < DMA - 1; ++t)
       for (int q = 0; q < 4; ++q) dma_issue(t * STAGE, min(t, nk - 1), dma_kb(min(t, nk - 1)), q);
-    int st = 0;                                   // kt % DMA
-    for (int kt = 0; kt < nk; ++kt) {
+    // The stage of a step (kt % DMA) is a compile-time constant: the loop body is written out once
+    // per stage, so that every LDS address in it is a register plus an immediate offset.
+    constexpr int NS = DMA ? DMA : 1;
+    auto one = [&](auto st_tag, int kt) {
+      constexpr int ST = decltype(st_tag)::value;
+      constexpr int ST_NEW = (ST + NS - 1) % NS;     // (kt + DMA - 1) % DMA
       wait_vmcnt<(KEEP > 0 ? KEEP : 0)>();
       __builtin_amdgcn_s_barrier();
-      const int st_new = st == 0 ? DMA - 1 : st - 1;   // (kt + DMA - 1) % DMA
       const int kt_new = min(kt + DMA - 1, nk - 1);
       const int64_t kb_new = dma_kb(kt_new);
-      compute(S0(), [&](auto q_tag) { dma_issue(st_new * STAGE, kt_new, kb_new, decltype(q_tag)::value); }, st * STAGE);
-      st = st + 1 == DMA ? 0 : st + 1;
-    }
+      compute(st_tag, [&](auto q_tag) { dma_issue(ST_NEW * STAGE, kt_new, kb_new, decltype(q_tag)::value); });
+    };
+    int kt = 0;
+    for (; kt + NS <= nk; kt += NS)
+      static_for<0, NS>([&](auto s_tag) { one(s_tag, kt + decltype(s_tag)::value); });
+    static_for<0, NS>([&](auto s_tag) {
+      if (kt + decltype(s_tag)::value < nk) one(s_tag, kt + decltype(s_tag)::value);
+    });
     wait_vmcnt<0>();   // the re-fetched tiles have landed before LDS is reused
   };
   // The same tiles, stages and loads as run_dma, but the fragment reads run D MFMA groups ahead of
@@ -740,11 +751,12 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     wait_vmcnt<(S - 2) * LPW>();
     __builtin_amdgcn_s_barrier();
     static_for<0, D>([&](auto g) { rd(g, decltype(g)::value, 0); });
-    int st = 0;                                       // kt % S
     __builtin_amdgcn_s_setprio(1);
-    for (int kt = 0; kt < nk; ++kt) {
-      const int st_next = st + 1 == S ? 0 : st + 1;
-      const int st_new = st == 0 ? S - 1 : st - 1;    // (kt + S - 1) % S: held tile kt - 1
+    // one K step with its stage (kt % S) known at compile time, see run_dma
+    auto one = [&](auto st_tag, int kt) {
+      constexpr int ST = decltype(st_tag)::value;
+      constexpr int ST_NEXT = (ST + 1) % S;
+      constexpr int ST_NEW = (ST + S - 1) % S;        // (kt + S - 1) % S: held tile kt - 1
       const int kt_new = min(kt + S - 1, nk - 1);
       const int64_t kb_new = dma_kb(kt_new);
       static_for<0, 4>([&](auto g_tag) {
@@ -757,14 +769,19 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
           __builtin_amdgcn_s_waitcnt(0xC07F | ((RPG < 15 ? RPG : 15) << 8));
           __builtin_amdgcn_s_barrier();
         }
-        if constexpr (T < 4) rd(std::integral_constant<int, T % NB>(), T, st * STAGE);
-        else rd(std::integral_constant<int, T % NB>(), T - 4, st_next * STAGE);
+        if constexpr (T < 4) rd(std::integral_constant<int, T % NB>(), T, ST * STAGE);
+        else rd(std::integral_constant<int, T % NB>(), T - 4, ST_NEXT * STAGE);
         mm_(std::integral_constant<int, G % NB>(), g_tag);
-        dma_issue(st_new * STAGE, kt_new, kb_new, G);
+        dma_issue(ST_NEW * STAGE, kt_new, kb_new, G);
         __builtin_amdgcn_sched_barrier(0);
       });
-      st = st_next;
-    }
+    };
+    int kt = 0;
+    for (; kt + S <= nk; kt += S)
+      static_for<0, S>([&](auto s_tag) { one(s_tag, kt + decltype(s_tag)::value); });
+    static_for<0, S>([&](auto s_tag) {
+      if (kt + decltype(s_tag)::value < nk) one(s_tag, kt + decltype(s_tag)::value);
+    });
     __builtin_amdgcn_s_setprio(0);
     wait_vmcnt<0>();   // the re-fetched tiles have landed before LDS is reused
     if constexpr (TWO) {
