@@ -436,6 +436,16 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // A wavefront tile of 32 x 32 has one accumulator, and the four MFMAs of a K step on it would
+  // form one dependent chain (an MFMA can issue every 8 passes, its result is ready after 16):
+  // the odd MFMA groups of a K step go to a second accumulator, added in at the end.
+  constexpr bool TWO_ACC = (MT * NT == 1);
+  f32x16_t acc2;
+  if constexpr (TWO_ACC) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc2[r] = 0.f;
+  }
+
   float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const bool do_cs = CS && p.colsum_dst != nullptr && m0 == 0;
   static_assert(PF == 1 || PF == 2, "one or two K steps of global loads in flight");
@@ -511,9 +521,16 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   // latency), all four groups at the top of the step when a group is only one or two.  After
   // each group, `between(kk)` may slot other work into the instruction stream, and a scheduling
   // fence keeps the compiler from gathering that work in one place.
-  auto compute = [&](auto stage_tag, auto&& between, int rt_off = 0) {
-    const int SOFF = decltype(stage_tag)::value * STAGE + rt_off;
+  auto compute = [&](auto stage_tag, auto&& between) {
+    constexpr int SOFF = decltype(stage_tag)::value * STAGE;
     constexpr int NBUF = (MT * NT <= 2) ? 4 : 2;
+    // The transposing reads of a tile that direct-to-LDS loads fill are written as inline
+    // assembly: through the builtin the compiler cannot tell them from the LDS locations the loads
+    // still in flight will write and puts `s_waitcnt vmcnt(0)` in front of the first one, which
+    // drains the prefetched tiles in every K step (the stage being read was waited for at the top
+    // of the step; the loads in flight fill another one).  The compiler does not know when such a
+    // read's result arrives, so the fragments pass through frag_wait() before the first MFMA.
+    constexpr bool ASM_TR = BTR && NBUF == 4;
     bf16x8_t af[NBUF][MT], bfr[NBUF][NT];
     auto read_frags = [&](auto buf_tag, int kk) {
       constexpr int BUF = decltype(buf_tag)::value % NBUF;
@@ -532,7 +549,14 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
       }
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
-        if constexpr (TRB) {
+        if constexpr (ASM_TR) {
+          union { s16x4_t h[2]; bf16x8_t f; } u;
+          const uint32_t a0 = (uint32_t)(uintptr_t)(lds_s16x4_ptr)(lds + bt_off[j][kk][0]);
+          const uint32_t a1 = (uint32_t)(uintptr_t)(lds_s16x4_ptr)(lds + bt_off[j][kk][1]);
+          asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(u.h[0]) : "v"(a0), "n"(SOFF) : "memory");
+          asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(u.h[1]) : "v"(a1), "n"(SOFF) : "memory");
+          bfr[BUF][j] = u.f;
+        } else if constexpr (TRB) {
           union { s16x4_t h[2]; bf16x8_t f; } u;
           u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + bt_off[j][kk][0] + SOFF));
           u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + bt_off[j][kk][1] + SOFF));
@@ -542,13 +566,28 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
         }
       }
     };
+    // all LDS reads issued so far have arrived; the fragments are operands of the statement so that
+    // no MFMA that uses them can be scheduled ahead of it
+    auto frag_wait = [&]() {
+      if constexpr (ASM_TR) {
+        static_assert(NT == 1, "one B fragment per group");
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(bfr[0][0]), "+v"(bfr[1][0]), "+v"(bfr[2][0]), "+v"(bfr[3][0])
+                     :
+                     : "memory");
+      }
+    };
     auto mfmas = [&](auto buf_tag) {
       constexpr int BUF = decltype(buf_tag)::value % NBUF;
+      if constexpr (TWO_ACC && (decltype(buf_tag)::value & 1)) {
+        acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[BUF][0], bfr[BUF][0], acc2, 0, 0, 0);
+      } else {
 #pragma unroll
-      for (int i = 0; i < MT; ++i)
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[BUF][i], bfr[BUF][j], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < NT; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[BUF][i], bfr[BUF][j], acc[i][j], 0, 0, 0);
+      }
     };
     typedef std::integral_constant<int, 0> I0;
     typedef std::integral_constant<int, 1> I1;
@@ -558,6 +597,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     __builtin_amdgcn_s_setprio(1);
     if constexpr (NBUF == 4) {
       read_frags(I0(), 0); read_frags(I1(), 1); read_frags(I2(), 2); read_frags(I3(), 3);
+      frag_wait();
       mfmas(I0()); between(I0()); __builtin_amdgcn_sched_barrier(0);
       mfmas(I1()); between(I1()); __builtin_amdgcn_sched_barrier(0);
       mfmas(I2()); between(I2()); __builtin_amdgcn_sched_barrier(0);
@@ -708,14 +748,9 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     constexpr int PER = LPW / 4, REM = LPW % 4;       // loads per quarter: PER (+1 for the first REM quarters)
     constexpr int ISSUED = GW * PER + (GW < REM ? GW : REM);   // issued in quarters 0 .. GW-1 of this step
     constexpr int KEEP = (S - 3) * LPW + ISSUED;      // may stay in flight when tile kt + 1 is needed
-    constexpr bool TWO = (MT * NT == 1);
+    constexpr bool TWO = TWO_ACC;
     constexpr int RPG = MT + NT * (TRB ? 2 : 1);      // LDS read instructions per group
     bf16x8_t af[NB][MT], bfr[NB][NT];
-    f32x16_t acc2;
-    if constexpr (TWO) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc2[r] = 0.f;
-    }
     typedef short s16x4_t __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
     auto rd = [&](auto buf_tag, int kk, int soff) {
@@ -784,10 +819,6 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     });
     __builtin_amdgcn_s_setprio(0);
     wait_vmcnt<0>();   // the re-fetched tiles have landed before LDS is reused
-    if constexpr (TWO) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[0][0][r] += acc2[r];
-    }
   };
   if constexpr (DMA && PIPE) run_dma_pipe();
   else if constexpr (DMA) run_dma();
@@ -796,6 +827,10 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     if (fast) run(std::true_type());
     else if (CS && inside && p.K / BK > PF + 3) run_mixed();
     else run(std::false_type());
+  }
+  if constexpr (TWO_ACC) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][0][r] += acc2[r];
   }
   __syncthreads();
 
