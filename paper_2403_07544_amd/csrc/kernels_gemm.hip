@@ -179,12 +179,18 @@ struct TileLoader {
   // wave-uniform base pointer plus one 32-bit byte offset per item; a K step only moves the base
   const char* ubase;
   uint32_t voff[NL];
+  // The same operand as a raw buffer: a fast-path load is then `buffer_load_dwordx4 v, voff, rsrc,
+  // soffset` with the K step's byte offset in a scalar register - no vector instruction forms the
+  // address (through a flat pointer the compiler folded base + voff into a 64-bit vector value and
+  // added the K offset with a 64-bit vector multiply-add per load).
+  __amdgpu_buffer_rsrc_t rsrc;
 
   __device__ __forceinline__ void init(const bf16_t* base, int64_t ld_, int row0, int row_lim, int K, int split,
                                        int split_on_k, int64_t seg_stride_, int tid) {
     ld = (int64_t)uniform64((uint64_t)ld_);
     safe = base;
     ubase = reinterpret_cast<const char*>(uniform64(reinterpret_cast<uint64_t>(base)));
+    rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)ubase, 0, 0x7fffffff, 0x00020000);   // fast path only: operand < 2 GiB
     ksplit = (KC && split && split_on_k) ? __builtin_amdgcn_readfirstlane(split) : 0;
     seg_stride = (int64_t)uniform64((uint64_t)seg_stride_);
 #pragma unroll
@@ -244,15 +250,15 @@ struct TileLoader {
     if (KC) {
       int64_t koff = k0;
       if (ksplit) { const int sg = k0 / ksplit; koff = (int64_t)sg * seg_stride + (k0 - sg * ksplit); }
-      const char* b = ubase + koff * 2;
+      const int so = (int)(koff * 2);
 #pragma unroll
-      for (int i = 0; i < NL; ++i) v[i] = *(global_u4_ptr)(b + voff[i]);
+      for (int i = 0; i < NL; ++i) v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff[i], so, 0);
     } else {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const char* b = ubase + ((int64_t)(k0 + j) * ld) * 2;
+        const int so = (int)(((int64_t)(k0 + j) * ld) * 2);
 #pragma unroll
-        for (int i = 0; i < NL; ++i) v[i * 4 + j] = *(global_u4_ptr)(b + voff[i]);
+        for (int i = 0; i < NL; ++i) v[i * 4 + j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff[i], so, 0);
       }
     }
   }
@@ -285,21 +291,21 @@ struct TileLoader {
     if (KC) {
       constexpr int I0 = NL >= 4 ? Q * (NL / 4) : Q, I1 = NL >= 4 ? (Q + 1) * (NL / 4) : (Q < NL ? Q + 1 : Q);
       if (I0 == I1) return;
-      const char* b = ubase + koff * 2;
+      const int so = (int)(koff * 2);
 #pragma unroll
       for (int i = I0; i < I1; ++i) {
         *reinterpret_cast<u32x4_t*>(lds + off[i]) = (F || k_st < klim[i]) ? v[i] : zero;
-        if (F) v[i] = *(global_u4_ptr)(b + voff[i]);
+        if (F) v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff[i], so, 0);
         else v[i] = load16_global(k_ld < klim[i] ? ptr[i] + koff : safe);
       }
     } else {
       // quarter Q moves k row Q of every item
-      const char* b = ubase + ((int64_t)(k_ld + Q) * ld) * 2;
+      const int so = (int)(((int64_t)(k_ld + Q) * ld) * 2);
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
         if (ALL_ITEMS || off[i * 4] >= 0)
           *reinterpret_cast<u32x4_t*>(lds + off[i * 4 + Q]) = (F || k_st + Q < klim[i]) ? v[i * 4 + Q] : zero;
-        if (F) v[i * 4 + Q] = *(global_u4_ptr)(b + voff[i]);
+        if (F) v[i * 4 + Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff[i], so, 0);
         else v[i * 4 + Q] = load16_global(k_ld + Q < klim[i] ? ptr[i] + (int64_t)(k_ld + Q) * ld : safe);
       }
     }
