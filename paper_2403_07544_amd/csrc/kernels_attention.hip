@@ -409,9 +409,15 @@ __global__ void __launch_bounds__(512, 1) attn_fwd_mfma_kernel(const AttnParams 
 #pragma unroll
       for (int r = 0; r < 16; ++r) sc[kt][r] = 0.f;
       if (kt < kt_end) {
+        // the four fragments of the key tile are requested together: with the read inside each
+        // MFMA's operand the compiler waited for every one of them in turn
+        bf16x8_t kfr[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) kfr[s] = frag_natural(Kn, kt * 32 + lcol, 2 * s + hh);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < 4; ++s)
-          sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Kn, kt * 32 + lcol, 2 * s + hh), qf[s], sc[kt], 0, 0, 0);
+          sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qf[s], sc[kt], 0, 0, 0);
       }
     }
     // softmax over keys: registers, then the other half of the keys in lane ^ 32.  The maximum is
@@ -464,10 +470,13 @@ __global__ void __launch_bounds__(512, 1) attn_fwd_mfma_kernel(const AttnParams 
           float pv[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) pv[e] = sc[kt][8 * s2 + e];
+          bf16x8_t vtr[2];
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct) vtr[ct] = frag_tr(Vn, kt * 32 + s2 * 16, ct, lane);
           const bf16x8_t pf = frag_from_regs(pv);
 #pragma unroll
           for (int ct = 0; ct < 2; ++ct)
-            oc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Vn, kt * 32 + s2 * 16, ct, lane), pf, oc[ct], 0, 0, 0);
+            oc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vtr[ct], pf, oc[ct], 0, 0, 0);
         }
       }
     }
@@ -578,11 +587,25 @@ __global__ void __launch_bounds__(512, 1) attn_bwd_mfma_kernel(const AttnParams 
       f32x16_t sc, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+      // all fragments of the tile pair are requested before the first MFMA (see the forward kernel)
+      bf16x8_t kfr[4], vfr[4];
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Kn, kt * 32 + lcol, 2 * s + hh), qf[s], sc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Vn, kt * 32 + lcol, 2 * s + hh), dof[s], dp, 0, 0, 0);
+        kfr[s] = frag_natural(Kn, kt * 32 + lcol, 2 * s + hh);
+        vfr[s] = frag_natural(Vn, kt * 32 + lcol, 2 * s + hh);
       }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qf[s], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[s], dof[s], dp, 0, 0, 0);
+      }
+      // the transposed fragments of K for dQ travel while the exponentials are taken
+      bf16x8_t ktr[2][2];
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) ktr[s2][ct] = frag_tr(Kn, kt * 32 + s2 * 16, ct, lane);
       // Keys past the sentence end need no mask here: their rows of K are zeros in LDS, so
       // whatever dS holds for them adds nothing to dQ.  Only the causal diagonal tile is masked.
       float ds[16];
@@ -603,7 +626,7 @@ __global__ void __launch_bounds__(512, 1) attn_bwd_mfma_kernel(const AttnParams 
         const bf16x8_t dsf = frag_from_regs(&ds[8 * s2]);
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct)
-          dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Kn, kt * 32 + s2 * 16, ct, lane), dsf, dq[ct], 0, 0, 0);
+          dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktr[s2][ct], dsf, dq[ct], 0, 0, 0);
       }
     }
     store_tile_rows(patch, dq, (bf16_t*)p.dq + (int64_t)(q0 + qt * 32) * p.lddq + h * 64, p.lddq, lq - qt * 32, lane);
@@ -629,11 +652,26 @@ __global__ void __launch_bounds__(512, 1) attn_bwd_mfma_kernel(const AttnParams 
       f32x16_t sc, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+      bf16x8_t qfr[4], dofr[4];
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(Qn, qt * 32 + lcol, 2 * s + hh), kf[s], sc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_natural(dOn, qt * 32 + lcol, 2 * s + hh), vf[s], dp, 0, 0, 0);
+        qfr[s] = frag_natural(Qn, qt * 32 + lcol, 2 * s + hh);
+        dofr[s] = frag_natural(dOn, qt * 32 + lcol, 2 * s + hh);
       }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[s], kf[s], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dofr[s], vf[s], dp, 0, 0, 0);
+      }
+      bf16x8_t dotr[2][2], qtr[2][2];
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+          dotr[s2][ct] = frag_tr(dOn, qt * 32 + s2 * 16, ct, lane);
+          qtr[s2][ct] = frag_tr(Qn, qt * 32 + s2 * 16, ct, lane);
+        }
       // Queries past the sentence end have zero rows of Q and dO in LDS and add nothing; this
       // wavefront's own keys past the end produce columns that are never stored.  Only the
       // causal diagonal tile is masked.
@@ -664,8 +702,8 @@ __global__ void __launch_bounds__(512, 1) attn_bwd_mfma_kernel(const AttnParams 
         const bf16x8_t dsf = frag_from_regs(&ds[8 * s2]);
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
-          dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(dOn, qt * 32 + s2 * 16, ct, lane), pf, dv[ct], 0, 0, 0);
-          dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Qn, qt * 32 + s2 * 16, ct, lane), dsf, dk[ct], 0, 0, 0);
+          dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dotr[s2][ct], pf, dv[ct], 0, 0, 0);
+          dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtr[s2][ct], dsf, dk[ct], 0, 0, 0);
         }
       }
     }
