@@ -647,23 +647,103 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
   // Nothing in a step is conditional: past the end the last tile is fetched again and never
   // used.  With a branch around the loads the compiler could no longer tell how many are still
   // in flight at the next wait and would drain them all, which serialises the pipeline.
+  // Register-staged loop with wavefront tiles of four or more MFMAs per group (XPIPE): the K steps
+  // overlap.  A step's barrier sits in front of its LAST MFMA group instead of in front of its
+  // first: by then this wavefront has parked its whole share of the next tile, so after the
+  // barrier the next tile is complete in LDS, the fragments of the next step's first group are
+  // requested at once, and the last group's MFMAs run while they travel.  (With the barrier at the
+  // top of a step the first group waited for an LDS round trip with an idle matrix pipeline.)  The
+  // two fragment buffers therefore live across steps: on entry to a step buffer 0 holds group 0.
+  constexpr bool XPIPE = !DMA && (MT * NT >= 4);
+  bf16x8_t xa[2][MT], xb[2][NT];
+  auto xread = [&](auto buf_tag, int kk, auto stage_tag) {
+    constexpr int BUF = decltype(buf_tag)::value, SOFF = decltype(stage_tag)::value * STAGE;
+    typedef short s16x4_t __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      if constexpr (TRA) {
+        union { s16x4_t h[2]; bf16x8_t f; } u;
+        u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + at_off[i][kk][0] + SOFF));
+        u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + at_off[i][kk][1] + SOFF));
+        xa[BUF][i] = u.f;
+      } else {
+        xa[BUF][i] = *reinterpret_cast<const bf16x8_t*>(lds + a_off[i][kk] + SOFF);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      if constexpr (TRB) {
+        union { s16x4_t h[2]; bf16x8_t f; } u;
+        u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + bt_off[j][kk][0] + SOFF));
+        u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + bt_off[j][kk][1] + SOFF));
+        xb[BUF][j] = u.f;
+      } else {
+        xb[BUF][j] = *reinterpret_cast<const bf16x8_t*>(lds + b_off[j][kk] + SOFF);
+      }
+    }
+  };
+  auto xmm = [&](auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[BUF][i], xb[BUF][j], acc[i][j], 0, 0, 0);
+  };
+  typedef std::integral_constant<int, 0> B0;
+  typedef std::integral_constant<int, 1> B1;
+  // before the first step: tile 0 is parked, wait for everybody's share and fetch group 0
+  auto xprime = [&]() {
+    if constexpr (XPIPE) {
+      __syncthreads();
+      xread(B0(), 0, S0());
+    }
+  };
   auto step = [&](auto cur_tag, auto nxt_tag, auto set_tag, auto fast_tag, int kt) {
     constexpr int SN = decltype(nxt_tag)::value * STAGE;
     constexpr int SET = decltype(set_tag)::value;
     constexpr bool F = decltype(fast_tag)::value;
     const int k_st = (kt + 1) * BK, k_ld = min(kt + 1 + PF, nk - 1) * BK;
     const int64_t koff_a = la.k_offset(k_ld), koff_b = lb.k_offset(k_ld);
-    __syncthreads();
-    add_colsum(k_st, vb[SET]);
-    compute(cur_tag, [&](auto q_tag) {
+    auto between = [&](auto q_tag) {
       constexpr int Q = decltype(q_tag)::value;
       la.template roll<Q, F>(lds + SN, k_st, k_ld, koff_a, va[SET]);
       lb.template roll<Q, F>(lds + SN + A_BYTES, k_st, k_ld, koff_b, vb[SET]);
-    });
+    };
+    if constexpr (XPIPE) {
+      typedef std::integral_constant<int, 0> Q0;
+      typedef std::integral_constant<int, 1> Q1;
+      typedef std::integral_constant<int, 2> Q2;
+      typedef std::integral_constant<int, 3> Q3;
+      add_colsum(k_st, vb[SET]);
+      __builtin_amdgcn_s_setprio(1);
+      xread(B1(), 1, cur_tag); xmm(B0()); between(Q0()); __builtin_amdgcn_sched_barrier(0);
+      xread(B0(), 2, cur_tag); xmm(B1()); between(Q1()); __builtin_amdgcn_sched_barrier(0);
+      xread(B1(), 3, cur_tag); xmm(B0()); between(Q2()); __builtin_amdgcn_sched_barrier(0);
+      between(Q3());
+      __syncthreads();             // everybody's share of the next tile is in LDS; this stage is read out
+      xread(B0(), 0, nxt_tag);
+      xmm(B1());
+      __builtin_amdgcn_s_setprio(0);
+    } else {
+      __syncthreads();
+      add_colsum(k_st, vb[SET]);
+      compute(cur_tag, between);
+    }
   };
   auto last = [&](auto cur_tag) {
-    __syncthreads();
-    compute(cur_tag, [&](auto) {});
+    if constexpr (XPIPE) {
+      __builtin_amdgcn_s_setprio(1);
+      xread(B1(), 1, cur_tag); xmm(B0());
+      xread(B0(), 2, cur_tag); xmm(B1());
+      xread(B1(), 3, cur_tag); xmm(B0());
+      xmm(B1());
+      __builtin_amdgcn_s_setprio(0);
+    } else {
+      __syncthreads();
+      compute(cur_tag, [&](auto) {});
+    }
   };
   auto run = [&](auto fast_tag) {
     typedef std::integral_constant<int, 1 % PF> SetOdd;   // tiles with odd index
@@ -671,6 +751,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     if (PF > 1) fetch(SetOdd(), fast_tag, min(1, nk - 1));
     stash(S0(), S0(), fast_tag, 0);
     fetch(S0(), fast_tag, min(PF, nk - 1));
+    xprime();
     int kt = 0;
     for (; kt + 2 < nk2; kt += 2) {
       step(S0(), S1(), SetOdd(), fast_tag, kt);
@@ -691,6 +772,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     if (PF > 1) fetch(SetOdd(), std::true_type(), 1);
     stash(S0(), S0(), std::true_type(), 0);
     fetch(S0(), std::true_type(), PF);
+    xprime();
     int kt = 0;
     for (; kt + 2 < nk2 && kt + 2 + PF < nfull; kt += 2) {   // step kt + 1 parks tile kt + 2 and fetches tile kt + 2 + PF
       step(S0(), S1(), SetOdd(), std::true_type(), kt);
