@@ -363,8 +363,10 @@ __device__ __forceinline__ void store_tile_rows(unsigned char* patch, const f32x
 }
 
 template <int NKT>
-__global__ void __launch_bounds__(512, 1) attn_fwd_mfma_kernel(const AttnParams p) {
+__global__ void __launch_bounds__(512, 1) attn_fwd_mfma_kernel(const AttnParams p_in) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
+  (void)p_in;
+  const AttnParams p = kernarg_block<AttnParams>();
   const int b = blockIdx.x / p.H, h = blockIdx.x % p.H;
   const int q0 = p.cu_q[b], lq = p.cu_q[b + 1] - q0;
   const int k0 = p.cu_k[b], lk = p.cu_k[b + 1] - k0;
@@ -502,8 +504,10 @@ inline size_t mfma_fwd_lds(int max_lq, int max_lk, int waves) {
 // and walks the query tiles: S = Q K^T, dP = dO V^T, then dV^T += dO^T P and dK^T += Q^T dS.
 // P is recomputed from the saved log-sum-exp in both phases; nothing is exchanged between them, and
 // nothing is accumulated with atomics.
-__global__ void __launch_bounds__(512, 1) attn_bwd_mfma_kernel(const AttnParams p) {
+__global__ void __launch_bounds__(512, 1) attn_bwd_mfma_kernel(const AttnParams p_in) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
+  (void)p_in;
+  const AttnParams p = kernarg_block<AttnParams>();
   const int b = blockIdx.x / p.H, h = blockIdx.x % p.H;
   const int q0 = p.cu_q[b], lq = p.cu_q[b + 1] - q0;
   const int k0 = p.cu_k[b], lk = p.cu_k[b + 1] - k0;

@@ -1035,15 +1035,27 @@ __device__ __forceinline__ int remap_xcd(int bid, int total) {
 // short axis first, as an earlier version did, makes each XCD pull all of the smaller operand
 // through its L2 for every two panels of the larger one: 714 MB read for the generator's 36 MB.)
 constexpr int TILE_BAND = 8;
+// (This runs in front of a workgroup's first load, and the GPU has no integer divide instruction:
+// the band is found by subtraction when there are few, and a full band's split is a shift.)
 __device__ __forceinline__ void tile_of(int L, int tiles_m, int tiles_n, int& tm, int& tn) {
   const bool along_m = tiles_m <= tiles_n;             // bands lie along the axis with more tiles
-  const int ts = along_m ? tiles_m : tiles_n, tl = along_m ? tiles_n : tiles_m;
-  const int band = L / (TILE_BAND * tl);
-  const int r = L - band * TILE_BAND * tl;
-  const int h = min(TILE_BAND, ts - band * TILE_BAND);  // the last band may be lower
-  const int s = band * TILE_BAND + r % h, l = r / h;
-  tm = along_m ? s : l;
-  tn = along_m ? l : s;
+  const unsigned ts = along_m ? tiles_m : tiles_n, tl = along_m ? tiles_n : tiles_m;
+  const unsigned per_band = TILE_BAND * tl;
+  unsigned band = 0, r = (unsigned)L;
+  if (ts <= 16 * TILE_BAND) {
+    while (r >= per_band) { r -= per_band; ++band; }
+  } else {
+    band = r / per_band;
+    r -= band * per_band;
+  }
+  const unsigned h = min((unsigned)TILE_BAND, ts - band * TILE_BAND);  // the last band may be lower
+  unsigned s, l;
+  static_assert(TILE_BAND == 8, "shift below");
+  if (h == TILE_BAND) { s = r & (TILE_BAND - 1); l = r >> 3; }
+  else { l = r / h; s = r - l * h; }
+  s += band * TILE_BAND;
+  tm = (int)(along_m ? s : l);
+  tn = (int)(along_m ? l : s);
 }
 
 // For a launch of many tiles with long K: XCD x takes the groups of GROUPED_COHORT consecutive
@@ -1064,9 +1076,12 @@ __device__ __forceinline__ int remap_cohort(int bid, int total) {
 template <int BM, int BN, int WM, int WN, bool KCA, bool KCB, int PF, int DMA, bool PIPE = false>
 __global__ void __launch_bounds__(256) gemm_mfma_kernel(const GemmParams p_in) {
   extern __shared__ __align__(16) unsigned char lds[];
-  GemmParams p = p_in;
+  // (kernarg_block: one group of scalar loads for all fields.  The grid size is recomputed from
+  // the shape for the same reason: gridDim sits in the implicit arguments, another cache line away.)
+  GemmParams p = kernarg_block<GemmParams>();
+  (void)p_in;
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-  int L = remap_xcd(blockIdx.x, gridDim.x);
+  int L = remap_xcd(blockIdx.x, tiles_m * tiles_n * (p.k_splits > 1 ? p.k_splits : 1));
   if (p.k_splits > 1) {   // this workgroup's share of K: shift the operands, shorten K, pick the part
     const int ks = L / (tiles_m * tiles_n);
     L -= ks * tiles_m * tiles_n;
@@ -1090,17 +1105,31 @@ __global__ void __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) gemm_mfma
                                                                 const int32_t* __restrict__ tile_start,
                                                                 int n_problems) {
   extern __shared__ __align__(16) unsigned char lds[];
+  // Which problem this workgroup's tile belongs to: every thread compares the tile number with a
+  // few entries of the (ascending) table of first tiles, and the count of entries that do not
+  // exceed it, less one, is the problem - one memory round trip for the whole workgroup; then the
+  // problem's parameter block is fetched a word per thread, a second one.  (A binary search by
+  // one thread was seven or more dependent round trips in front of every tile.)
   __shared__ GemmParams prm;
-  __shared__ int local_tile;
-  if (threadIdx.x == 0) {
-    int lo = 0, hi = n_problems - 1;
-    const int t = remap_cohort(blockIdx.x, gridDim.x);
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if (tile_start[mid] <= t) lo = mid; else hi = mid - 1;
-    }
-    prm = table[lo];
-    local_tile = t - tile_start[lo];
+  __shared__ int local_tile, n_below;
+  const int t = remap_cohort(blockIdx.x, gridDim.x);
+  if (threadIdx.x == 0) n_below = 0;
+  __syncthreads();
+  {
+    int cnt = 0;
+    for (int i = threadIdx.x; i < n_problems; i += blockDim.x) cnt += (tile_start[i] <= t) ? 1 : 0;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
+    if ((threadIdx.x & 63) == 0 && cnt) atomicAdd(&n_below, cnt);
+  }
+  __syncthreads();
+  {
+    const int lo = n_below - 1;                  // tile_start[0] = 0, so there is at least one
+    constexpr int NW = (int)(sizeof(GemmParams) / 4);
+    static_assert(sizeof(GemmParams) % 4 == 0 && NW <= 256, "a word per thread");
+    if ((int)threadIdx.x < NW)
+      reinterpret_cast<uint32_t*>(&prm)[threadIdx.x] = reinterpret_cast<const uint32_t*>(table + lo)[threadIdx.x];
+    if (threadIdx.x == 0) local_tile = t - tile_start[lo];
   }
   __syncthreads();
   const int tiles_n = (prm.N + BN - 1) / BN;

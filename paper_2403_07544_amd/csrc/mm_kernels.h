@@ -247,4 +247,44 @@ void launch_to_bf16(hipStream_t st, const float* src, bf16_t* dst, int64_t n);
 void launch_fill_f32(hipStream_t st, float* dst, int64_t n, float v);
 void launch_fill_i32(hipStream_t st, int32_t* dst, int64_t n, int32_t v);
 
+
+// The parameter block of a kernel whose only argument is one struct T passed by value, fetched
+// from the kernel-argument segment by ONE group of scalar loads with one wait.  Left to the
+// compiler the fields are fetched where they are first used, a scalar-cache round trip (about
+// 0.2 us) at a time, several of them one after another in front of a workgroup's first load.
+// Whole 64-byte pieces are read: up to 60 bytes past T, which lie in the implicit arguments that
+// follow the explicit ones in the segment.
+template <typename T>
+__device__ __forceinline__ T kernarg_block() {
+  static_assert(sizeof(T) % 4 == 0 && sizeof(T) <= 256, "one to four 16-dword loads");
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+  constexpr int NW = (int)(sizeof(T) / 4), NC = (NW + 15) / 16;
+  const auto ka = __builtin_amdgcn_kernarg_segment_ptr();
+  u32x16 c[4];
+  if constexpr (NC == 1) {
+    asm volatile("s_load_dwordx16 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=&s"(c[0]) : "s"(ka) : "memory");
+  } else if constexpr (NC == 2) {
+    asm volatile("s_load_dwordx16 %0, %2, 0x0\n\ts_load_dwordx16 %1, %2, 0x40\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(c[0]), "=&s"(c[1]) : "s"(ka) : "memory");
+  } else if constexpr (NC == 3) {
+    asm volatile("s_load_dwordx16 %0, %3, 0x0\n\ts_load_dwordx16 %1, %3, 0x40\n\ts_load_dwordx16 %2, %3, 0x80\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&s"(c[0]), "=&s"(c[1]), "=&s"(c[2]) : "s"(ka) : "memory");
+  } else {
+    asm volatile("s_load_dwordx16 %0, %4, 0x0\n\ts_load_dwordx16 %1, %4, 0x40\n\ts_load_dwordx16 %2, %4, 0x80\n\t"
+                 "s_load_dwordx16 %3, %4, 0xc0\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(c[0]), "=&s"(c[1]), "=&s"(c[2]), "=&s"(c[3]) : "s"(ka) : "memory");
+  }
+  uint32_t w[NW];
+#pragma unroll
+  for (int i = 0; i < NW; ++i) w[i] = c[i / 16][i % 16];
+  T out;
+  __builtin_memcpy(&out, w, sizeof(T));
+  return out;
+#else
+  return T();   // (the host pass only parses kernels)
+#endif
+}
+
 }  // namespace mm
