@@ -536,7 +536,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     // drains the prefetched tiles in every K step (the stage being read was waited for at the top
     // of the step; the loads in flight fill another one).  The compiler does not know when such a
     // read's result arrives, so the fragments pass through frag_wait() before the first MFMA.
-    constexpr bool ASM_TR = BTR && NBUF == 4;
+    constexpr bool ASM_TR = BTR && NBUF == 4 && NT == 1;
     bf16x8_t af[NBUF][MT], bfr[NBUF][NT];
     auto read_frags = [&](auto buf_tag, int kk) {
       constexpr int BUF = decltype(buf_tag)::value % NBUF;
@@ -576,7 +576,6 @@ __device__ __forceinline__ void gemm_mfma_tile(const GemmParams& p, const int m0
     // no MFMA that uses them can be scheduled ahead of it
     auto frag_wait = [&]() {
       if constexpr (ASM_TR) {
-        static_assert(NT == 1, "one B fragment per group");
         asm volatile("s_waitcnt lgkmcnt(0)"
                      : "+v"(bfr[0][0]), "+v"(bfr[1][0]), "+v"(bfr[2][0]), "+v"(bfr[3][0])
                      :
