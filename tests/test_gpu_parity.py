@@ -82,6 +82,29 @@ def test_midsize_bf16_step():
     check_untouched_zero(ctx, orc, set(orc.routes[0]))
 
 
+@pytest.mark.parametrize("accumulate", [False, True])
+def test_model_width_512_bf16_step(accumulate):
+    """d = 512 (the benchmark's model width, eight heads) at ~650 tokens, which the oracle still
+    finishes in seconds: the kernel choices that depend on the model width (direct-to-LDS tiles,
+    the pipelined K loop of the input gradients, K = 512 / 1024 / 1536 with the fused q|k|v
+    segments) run here with token counts that are not multiples of any tile height, beside the
+    adapters' K = 16 products.  Second case: two steps into the same buckets before the check."""
+    setup = tiny_setup(d=512, H=8, F_=1024, V=512, adapter_dim=16, dtype="bf16", max_len=64)
+    rng = np.random.default_rng(1)
+    batch = tiny_batch(setup, lengths=[(int(a), int(b)) for a, b in rng.integers(5, 60, (21, 2))])
+    say(f"[case] d=512 bf16: {batch.n_src_tokens} src / {batch.n_tgt_tokens} tgt tokens, accumulate={accumulate}")
+    assert batch.n_src_tokens % 32 and (batch.n_tgt_tokens) % 32
+    ctx, orc = make_pair(setup, max_batch_tokens=2048)
+    for _ in range(2 if accumulate else 1):
+        loss = ctx.mm_train_step(0, batch.src_ids, batch.tgt_ids, batch.lengths)
+        ref = orc.train_step(0, batch.src_ids, batch.tgt_ids, batch.lengths)
+        say(f"  loss {loss:.6f} oracle {ref:.6f}")
+        assert abs(loss - ref) <= 1e-2 * abs(ref)
+    worst = check_grads(ctx, orc, orc.routes[0], label="d512", **bf16_tol(min(batch.n_src_tokens, batch.n_tgt_tokens)))
+    say(f"  worst {worst}")
+    check_untouched_zero(ctx, orc, set(orc.routes[0]))
+
+
 def test_config1_fp32_step_and_update():
     setup = mm_synth.build_setup(1)
     say("[case] config 1 fp32")
