@@ -107,3 +107,50 @@ def test_paper_benchmark_shapes(index):
     three sharing schemes (language-specific 6+6; 4+4 partially shared encoder with 4 decoder
     layers; shared 9-layer encoder with 4 decoder layers)."""
     _modular_case(index, n_tasks=1, seed=10 + index)
+
+
+def test_full_size_properties_that_need_no_oracle():
+    """Set-up 2's full batch (the shapes bench.py times), properties that hold at any size:
+    (a) a second identical step into the same buckets doubles every gradient bit for bit (the first
+        use of a bucket overwrites, the second adds the same fp32 values; embedding buckets add twice);
+    (b) the same sentences in another order: every sentence is computed on its own, so only the order
+        of the sums over tokens changes (weight, bias and LayerNorm gradients, embedding rows, the
+        loss) - equal up to fp32 summation order;
+    (c) embedding rows of ids that do not occur in the batch receive no gradient at all."""
+    from paper_2403_07544_amd import context_from_setup
+    setup = mm_synth.build_setup(2)
+    batch = mm_synth.make_batches(setup, 1)[0]
+    route = list(setup.tasks[0][1])
+    ctx = context_from_setup(setup, fill_params=mm_synth.fill_params)
+    say(f"[case] config 2 full-size properties: B={len(batch.lengths)} S={batch.n_src_tokens} U={batch.n_tgt_tokens}")
+    loss1 = ctx.mm_train_step(0, batch.src_ids, batch.tgt_ids, batch.lengths)
+    g1 = {j: ctx.mm_get_grads(j) for j in route}
+    loss2 = ctx.mm_train_step(0, batch.src_ids, batch.tgt_ids, batch.lengths)
+    assert loss1 == loss2
+    for j in route:                                                   # (a)
+        assert np.array_equal(ctx.mm_get_grads(j), 2.0 * g1[j]), f"module {j}: second step is not an exact doubling"
+    V, d = setup.shape.vocab, setup.shape.d_model
+    # (c) the encoder reads every source token, the decoder every target token but the last (EOS is only a label)
+    for kind, ids, lens in (("src_emb", batch.src_ids, batch.lengths[:, 0]), ("tgt_emb", batch.tgt_ids, batch.lengths[:, 1] - 1)):
+        j = next(m for m in route if setup.modules[m].kind == kind)
+        rows = g1[j][:V * d].reshape(V, d)
+        present = np.zeros(V, bool)
+        present[np.unique(np.concatenate([ids[b, :lens[b]] for b in range(len(lens))]))] = True
+        assert not rows[~present].any(), f"{kind}: a row of an absent id has a gradient"
+        assert np.abs(rows[present]).sum(axis=1).min() > 0, f"{kind}: a row of a present id has none"
+    ctx.close()
+    # (b) on a fresh context (same seeded weights, empty buckets)
+    perm = np.random.default_rng(5).permutation(len(batch.lengths))
+    ctx = context_from_setup(setup, fill_params=mm_synth.fill_params)
+    loss3 = ctx.mm_train_step(0, np.ascontiguousarray(batch.src_ids[perm]), np.ascontiguousarray(batch.tgt_ids[perm]),
+                              np.ascontiguousarray(batch.lengths[perm]))
+    say(f"  loss {loss1:.7f}, permuted {loss3:.7f}")
+    assert abs(loss3 - loss1) <= 2e-6 * abs(loss1)
+    worst = 0.0
+    for j in route:
+        a, b = ctx.mm_get_grads(j).astype(np.float64), g1[j].astype(np.float64)
+        rel = np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30)
+        worst = max(worst, rel)
+        assert rel <= 1e-5, f"module {j}: permuted batch differs by {rel:.2e}"
+    say(f"  worst relative L2 between the two sentence orders: {worst:.2e}")
+    ctx.close()
