@@ -1344,13 +1344,25 @@ void launch_gemm(hipStream_t st, Dtype dt, const GemmParams& p, const LaunchEven
     // Measured on the step's shapes: 128x128 tiles once they fill the chip, with two K steps of
     // loads in flight when there are several rounds of tiles or a long K; otherwise 64x64.
     const long tiles_big = (long)((p.M + 127) / 128) * ((p.N + 127) / 128) * (p.k_splits > 1 ? p.k_splits : 1);
-    if (tiles_big >= 192) {
+    const long tiles_small = (long)((p.M + 63) / 64) * ((p.N + 63) / 64) * (p.k_splits > 1 ? p.k_splits : 1);
+    // A compute unit holds two workgroups of the 128x128 kernels and of the four-stage 64x64 kernel
+    // (512 at a time on the chip), three of the three-stage 64x64 kernels (768).  A product with a
+    // few tiles more than 512 - a batch of slightly more than 4096 tokens - would run a second,
+    // nearly empty round; measured on such shapes the three-stage 64x64 kernels, which take all
+    // tiles at once, are faster (K = 512, N = 2048, M = 4160: 21.6 against 24.1 us forward, 20.4
+    // against 22.2 us for the input gradient; N = 512, K = 2048: 19.9 against 23.7 us).
+    const bool dma_ok = p.transA == 0 && p.K % BK == 0;
+    if (tiles_big > 512 && tiles_big <= 576 && dma_ok && p.K <= 512) {
+      if (p.transB) launch_mfma_cfg<64, 64, 32, 32, 1, 3, true>(st, p, ev);
+      else launch_mfma_cfg<64, 64, 32, 32, 1, 3>(st, p, ev);
+    } else if (tiles_big >= 192) {
       if (tiles_big >= 1024 || p.K >= 1024) launch_mfma_cfg<128, 128, 64, 64, 2>(st, p, ev);
       else launch_mfma_cfg<128, 128, 64, 64, 1>(st, p, ev);
     } else if (p.transA == 0 && p.transB != 0 && p.K % BK == 0) {
       // both operands k-contiguous (input-gradient products): direct-to-LDS loads, four stages, the
       // K loop pipelined across K steps (measured 5-8 % faster than the loop below at K >= 1536)
-      launch_mfma_cfg<64, 64, 32, 32, 1, 4, true>(st, p, ev);
+      if (tiles_small > 512 && tiles_small <= 768) launch_mfma_cfg<64, 64, 32, 32, 1, 3, true>(st, p, ev);
+      else launch_mfma_cfg<64, 64, 32, 32, 1, 4, true>(st, p, ev);
     } else {
       // (when A is k-contiguous and K is a multiple of 64 this runs the variant with direct-to-LDS
       // loads and three stages)
