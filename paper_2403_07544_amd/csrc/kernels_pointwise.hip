@@ -705,8 +705,11 @@ __global__ void __launch_bounds__(THREADS) ce_rows_kernel(bf16_t* __restrict__ z
   }
 }
 
+// host_out (may be null): pinned host memory that also receives the sum and, behind it, the word at
+// flag - written from here, the result needs no device-to-host copy at the end of the step.
 __global__ void __launch_bounds__(1024) sum_scaled_kernel(const float* __restrict__ v, int n, float scale,
-                                                          float* __restrict__ out) {
+                                                          float* __restrict__ out, float* __restrict__ host_out,
+                                                          const int32_t* __restrict__ flag) {
   __shared__ float part[16];
   float s = 0.f;
   for (int i = threadIdx.x; i < n; i += blockDim.x) s += v[i];
@@ -717,7 +720,22 @@ __global__ void __launch_bounds__(1024) sum_scaled_kernel(const float* __restric
     float t = 0.f;
     for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += part[w];
     out[0] = t * scale;
+    if (host_out) {
+      host_out[0] = t * scale;
+      reinterpret_cast<int32_t*>(host_out)[1] = *flag;
+    }
   }
+}
+
+// Copies n 4-byte words from pinned host memory (read by the kernel itself, across the bus) into
+// device memory, and clears one more word if asked to.  For the few kilobytes of tables a step and
+// an update need on the device: a copy command in their place left the stream idle for several
+// microseconds on either side of it.
+__global__ void __launch_bounds__(256) upload_words_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst,
+                                                           int n, int32_t* __restrict__ zero_word) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+  if (zero_word && i == 0) *zero_word = 0;
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -944,8 +962,15 @@ void launch_ce(hipStream_t st, Dtype dt, void* z, const int32_t* label, float* l
                           loss_rows, V, eps, scale, flag);
 }
 
-void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float* out) {
-  sum_scaled_kernel<<<1, 1024, 0, st>>>(v, n, scale, out);
+void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float* out, float* host_out,
+                       const int32_t* flag) {
+  sum_scaled_kernel<<<1, 1024, 0, st>>>(v, n, scale, out, host_out, flag);
+}
+
+void launch_upload_words(hipStream_t st, const void* src_pinned, void* dst_dev, size_t n_bytes, int32_t* zero_word) {
+  const int n = (int)((n_bytes + 3) / 4);
+  if (n <= 0 && !zero_word) return;
+  upload_words_kernel<<<n > 0 ? (n + 255) / 256 : 1, 256, 0, st>>>((const uint32_t*)src_pinned, (uint32_t*)dst_dev, n, zero_word);
 }
 
 void launch_adam(hipStream_t st, const AdamSegment* segs_dev, int n_segs, int total_chunks, float lr,

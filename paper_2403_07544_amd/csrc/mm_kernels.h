@@ -186,7 +186,11 @@ void launch_attn_bwd(hipStream_t st, Dtype dt, const AttnParams& p, const Launch
 void launch_ce(hipStream_t st, Dtype dt, void* z, const int32_t* label, float* loss_rows, int U,
                int V, float eps, float scale, const int32_t* flag, const LaunchEvents& ev = LaunchEvents());
 // out[0] = (sum of loss_rows) * scale
-void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float* out);
+void launch_sum_scaled(hipStream_t st, const float* v, int n, float scale, float* out, float* host_out = nullptr,
+                       const int32_t* flag = nullptr);
+// n_bytes (rounded up to whole words; both buffers hold that many) from pinned host memory to device
+// memory by a kernel that reads the host memory itself; zero_word (may be null) is cleared as well.
+void launch_upload_words(hipStream_t st, const void* src_pinned, void* dst_dev, size_t n_bytes, int32_t* zero_word);
 
 // ---------------------------------------------------------------------------------------------
 // Adam over a list of module buckets, one launch

@@ -474,7 +474,7 @@ struct Step {
       blocks += (2 * jobs[i].d + 63) / 64;
       ljob[i] = jobs[i];
     }
-    hipMemcpyAsync(c->tab_dev, c->tab_host, total, hipMemcpyHostToDevice, c->st);
+    launch_upload_words(c->st, c->tab_host, c->tab_dev, total, nullptr);
     hipEventRecord(c->ev_gtab, c->st);
     if (ng)
       launch_gemm_grouped_tn(c->st, reinterpret_cast<const GemmParams*>(c->tab_dev),
@@ -793,7 +793,7 @@ void run_step(mm_ctx* c, const Route& rt, bool dry, const int32_t* lens_host) {
     launch_ce(c->st, c->dt, z, c->label, loss_rows, U, V, c->cfg.label_smoothing, 1.0f / (float)U, c->flag,
               run.begin_timed(MM_K_CE, (double)U * V * s.esz * 2));
     run.begin(MM_K_OTHER, (double)U * 4);
-    launch_sum_scaled(c->st, loss_rows, U, 1.0f / (float)U, c->loss_dev);
+    launch_sum_scaled(c->st, loss_rows, U, 1.0f / (float)U, c->loss_dev, c->result_host, c->flag);   // loss and flag go to the host from here
     run.end();
   }
 
@@ -1402,9 +1402,8 @@ mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const i
 
   // lengths and both prefix sums lie back to back in the staging block and travel in one copy
   c->lens = c->meta; c->cu_s = c->meta + 2 * B; c->cu_u = c->cu_s + B + 1;
-  HIP_TRY(c, hipMemcpyAsync(c->meta, st_lens, n_meta * 4, hipMemcpyHostToDevice, c->st));
+  launch_upload_words(c->st, st_lens, c->meta, n_meta * 4, c->flag);   // (also clears the id-check flag)
   HIP_TRY(c, hipEventRecord(c->ev_stage, c->st));
-  launch_fill_i32(c->st, c->flag, 1, 0);
   launch_pack_ids(c->st, src_dev, tgt_dev, c->lens, c->cu_s, c->cu_u, B, S_max, T_max, c->cfg.vocab, c->src_tok,
                   c->src_pos, c->dec_tok, c->dec_pos, c->label, c->flag);
   // the two token sorts need only the packed ids: they run on the side stream during the forward pass
@@ -1415,7 +1414,6 @@ mm_status mm_train_step(mm_ctx* c, int32_t task, const int32_t* src_ids, const i
   HIP_TRY(c, hipEventRecord(c->ev_sorted, c->aux));
   run_step(c, rt, false, lengths);
   HIP_TRY(c, hipGetLastError());
-  HIP_TRY(c, hipMemcpyAsync(&c->result_host[0], c->loss_dev, 8, hipMemcpyDeviceToHost, c->st));   // loss, flag
   HIP_TRY(c, hipEventRecord(c->ev_done, c->st));
   for (int j : rt.ids) c->mods[j].touched += 1;
   c->pending = true; c->pending_task = task;
@@ -1483,7 +1481,7 @@ mm_status update_launch(mm_ctx* c, const int* use, int n_use, float lr, AdamSegm
     work += work_bytes_adam(c, m.P, !bucket_overwrites(m.kind));
     m.touched = 0;
   }
-  HIP_TRY(c, hipMemcpyAsync(dev_tab, host_tab, (size_t)n_use * sizeof(AdamSegment), hipMemcpyHostToDevice, c->st));
+  launch_upload_words(c->st, host_tab, dev_tab, (size_t)n_use * sizeof(AdamSegment), nullptr);
   HIP_TRY(c, hipEventRecord(ev, c->st));
   LaunchEvents le;
   if (timed) {   // (timing takes events from a pool that may grow: not for the allocation-free entry point)
